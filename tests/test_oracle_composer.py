@@ -1,0 +1,196 @@
+"""Pins for oracle/composer.py: the properties the paper states for Dynamic SplitFuse.
+
+Sec. 3.2 rule 1: a prompt's chunks run over several passes, only the last one generates.
+Sec. 3.2 rule 2: the token budget is met exactly whenever enough tokens are waiting.
+Sec. 3.2 (closing paragraph) / Sec. 2.2: generation is never stalled behind prompts.
+Sec. 2.1: storage is fixed-size blocks; no block belongs to two live sequences.
+"""
+import numpy as np
+import pytest
+
+from oracle.composer import NoBlocksError, SplitFuseComposer
+
+
+def test_hand_worked_schedule():
+    """Budget 8, block 4: prompts of 10 and 5 tokens, 3 new tokens each.
+
+    pass 0: A[0:8]                      (8 tokens, no generation)
+    pass 1: A[8:10] emits, B[0:5] emits, budget under-filled (7) because nothing else waits
+    pass 2: decode A (c=10), decode B (c=5)
+    pass 3: decode A (c=11), decode B (c=6)  -> both have emitted 3 tokens and retire
+    """
+    comp = SplitFuseComposer(8, 16, 4, 8)
+    comp.add_request(100, 10, 3)
+    comp.add_request(200, 5, 3)
+    d, t, e = comp.compose()
+    assert d == [(8, 0, 0, 100)] and t == [[0, 1]] and e == [0]
+    comp.step_done()
+    d, t, e = comp.compose()
+    assert d == [(2, 8, 0, 100), (5, 0, 2, 200)] and t == [[0, 1, 2], [3, 4]] and e == [1, 1]
+    comp.step_done()
+    d, t, e = comp.compose()
+    assert d == [(1, 10, 0, 100), (1, 5, 1, 200)] and t == [[0, 1, 2], [3, 4]] and e == [1, 1]
+    comp.step_done()
+    d, t, e = comp.compose()
+    assert d == [(1, 11, 0, 100), (1, 6, 1, 200)] and e == [1, 1]
+    comp.step_done()
+    assert comp.n_live() == 0 and comp.n_free_blocks() == 8
+    assert list(comp.free) == [5, 6, 7, 0, 1, 2, 3, 4]          # freed blocks rejoin at the back
+    assert comp.compose() == ([], [], [])
+
+
+def test_fuses_short_prompts_to_fill_budget_exactly():
+    comp = SplitFuseComposer(16, 16, 4, 64)
+    for sid, plen in enumerate([5, 5, 5, 5]):
+        comp.add_request(sid, plen, 2)
+    d, _, e = comp.compose()
+    assert [x[0] for x in d] == [5, 5, 5, 1] and e == [1, 1, 1, 0]       # 4th prompt is split
+    comp.step_done()
+    d, _, e = comp.compose()
+    # three generations first, then the rest of prompt 3
+    assert d == [(1, 5, 0, 0), (1, 5, 1, 1), (1, 5, 2, 2), (4, 1, 3, 3)] and e == [1, 1, 1, 1]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants_on_random_streams(seed):
+    rng = np.random.default_rng(seed)
+    budget = int(rng.integers(8, 200))
+    B = int(rng.choice([1, 4, 16, 64]))
+    max_seqs = int(rng.integers(4, 64))
+    n_steps = 20000                 # upper bound; the loop stops once every request has retired
+    arrivals, sid, req = {}, 0, {}
+    for step in range(100):
+        for _ in range(rng.poisson(0.4)):
+            plen, gen = int(rng.integers(1, 4 * budget)), int(rng.integers(1, 40))
+            arrivals.setdefault(step, []).append((sid, plen, gen))
+            req[sid] = (plen, gen)
+            sid += 1
+    worst = max((-(-(p + g) // B) for p, g in req.values()), default=1)
+    num_blocks = max(sum(-(-(p + g) // B) for p, g in req.values()), worst)   # never runs dry
+    free_order = rng.permutation(num_blocks)
+    comp = SplitFuseComposer(budget, max_seqs, B, num_blocks, free_order)
+
+    cached = {}        # sid -> tokens in cache
+    emitted = {}       # sid -> tokens generated
+    owner = {}         # physical block -> sid
+    prompt_order = []  # sids in order of first scheduling
+    waiting_decodes_prev = set()
+
+    def check(step, comp, descs, tables, emits):
+        nonlocal waiting_decodes_prev
+        total = sum(d[0] for d in descs)
+        assert total <= budget and len(descs) <= max_seqs
+        sids = [d[3] for d in descs]
+        assert len(set(sids)) == len(sids)                          # each sequence at most once
+        off = 0
+        seen_prompt = False
+        for (n, c, qo, s), tab, em in zip(descs, tables, emits):
+            assert n >= 1 and qo == off
+            off += n
+            plen, gen = req[s]
+            assert c == cached.get(s, 0)                            # n_cached = sum of earlier n_new
+            if c >= plen:                                           # generation pass
+                assert n == 1 and em == 1 and not seen_prompt       # generations come first
+            else:
+                seen_prompt = True
+                assert c + n <= plen
+                assert em == (1 if c + n == plen else 0)            # only the last chunk generates
+                if s not in prompt_order:
+                    prompt_order.append(s)
+            assert len(tab) == -(-(c + n) // B)                     # exactly the blocks it needs
+            for b in tab:
+                assert owner.setdefault(b, s) == s                  # no block shared
+        # budget met exactly unless supply or the sequence bound ran out
+        supply = sum(p - cached.get(s, 0) for s, (p, g) in req.items()
+                     if s in arrived and cached.get(s, 0) < p)
+        n_dec = sum(1 for s in arrived if cached.get(s, 0) >= req[s][0] and not done(s))
+        if len(descs) < max_seqs:
+            assert total == min(budget, supply + n_dec), (step, total, supply, n_dec)
+        # generation never stalls: every live generation runs unless the bound cuts it, and a
+        # generation left out in one pass runs in the next (rotation)
+        live_dec = {s for s in arrived if cached.get(s, 0) >= req[s][0] and not done(s)}
+        sched_dec = {s for (n, c, qo, s) in descs if c >= req[s][0]}
+        assert len(sched_dec) == min(len(live_dec), budget, max_seqs)
+        assert waiting_decodes_prev & live_dec <= sched_dec or len(waiting_decodes_prev) > min(budget, max_seqs)
+        waiting_decodes_prev = live_dec - sched_dec
+        # bookkeeping for the next pass
+        for (n, c, qo, s), em in zip(descs, emits):
+            cached[s] = c + n
+            emitted[s] = emitted.get(s, 0) + em
+            if done(s):
+                for b in [b for b, o in owner.items() if o == s]:
+                    del owner[b]
+
+    def done(s):
+        return emitted.get(s, 0) >= req[s][1]
+
+    arrived = set()
+    history = []
+    for step in range(n_steps):
+        for a in arrivals.get(step, []):
+            comp.add_request(*a)
+            arrived.add(a[0])
+        out = comp.compose()
+        check(step, comp, *out)
+        history.append(out)
+        comp.step_done()
+        if step > 100 and comp.n_live() == 0:
+            break
+    # every request ran to completion: chunks sum to the prompt, max_new tokens emitted
+    assert comp.n_live() == 0
+    for s, (plen, gen) in req.items():
+        assert cached[s] == plen + gen - 1 and emitted[s] == gen
+    assert prompt_order == sorted(prompt_order)                      # first come, first served
+    assert comp.n_free_blocks() == num_blocks and sorted(comp.free) == list(range(num_blocks))
+
+
+def test_consistent_forward_size_under_load():
+    """With a backlog of long prompts every pass carries exactly the budget (Sec. 3.2)."""
+    comp = SplitFuseComposer(512, 256, 64, 4096)
+    for sid in range(12):
+        comp.add_request(sid, 2600, 60)
+    sizes = []
+    for _ in range(40):
+        d, _, _ = comp.compose()
+        sizes.append(sum(x[0] for x in d))
+        comp.step_done()
+    assert sizes == [512] * 40
+
+
+def test_block_shortage_shrinks_chunk_then_reports_no_blocks():
+    comp = SplitFuseComposer(32, 8, 4, 3)            # 12 token slots in total
+    comp.add_request(0, 20, 4)
+    comp.add_request(1, 6, 2)
+    d, t, e = comp.compose()
+    assert d == [(12, 0, 0, 0)] and len(t[0]) == 3 and e == [0]     # shrunk to what fits; next prompt not started
+    comp.step_done()
+    with pytest.raises(NoBlocksError):
+        comp.compose()
+
+
+def test_generation_skipped_when_it_cannot_get_a_block():
+    comp = SplitFuseComposer(8, 8, 4, 3)
+    comp.add_request(0, 4, 5)       # one block, next token needs a second block
+    comp.add_request(1, 8, 5)       # two blocks
+    comp.compose(); comp.step_done()                 # pass 0: 4 + 4
+    d, _, _ = comp.compose()                         # pass 1: decode 0 needs a block: 1 free -> ok; prompt 1 gets none
+    assert d[0] == (1, 4, 0, 0) and len(d) == 1
+    comp.step_done()
+    d, _, _ = comp.compose()                         # pass 2: decode 0 (c=5) fits its block; prompt 1 still starved
+    assert d == [(1, 5, 0, 0)]
+
+
+def test_generations_hold_the_budget_before_new_prompts():
+    """Budget 3: three running generations fill every pass; waiting prompts start only when one retires."""
+    comp = SplitFuseComposer(3, 8, 4, 64)
+    for sid in range(5):
+        comp.add_request(sid, 1, 4)
+    seen = []
+    for _ in range(8):
+        d, _, _ = comp.compose()
+        seen.append([(x[3], x[1]) for x in d])
+        comp.step_done()
+    assert seen[0] == [(0, 0), (1, 0), (2, 0)]
+    assert seen[1] == [(0, 1), (1, 1), (2, 1)] and seen[3] == [(0, 3), (1, 3), (2, 3)]
+    assert seen[4] == [(3, 0), (4, 0)]                    # generations 0-2 retired after 4 tokens each
+    assert seen[7] == [(3, 3), (4, 3)] and comp.n_live() == 0
