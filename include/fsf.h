@@ -1,0 +1,190 @@
+/*
+ * fsf.h - C ABI of the Dynamic SplitFuse attention step for AMD MI355X (gfx950).
+ *
+ * One forward pass of the serving loop hands the model a ragged batch: for each
+ * sequence n_new tokens to process now and n_cached tokens already in the KV cache.
+ * A prompt pass brings many tokens, a generation pass exactly one (paper Sec. 2, the
+ * two phases of text generation).  Dynamic SplitFuse cuts prompts into chunks and fuses
+ * them with running generations so that every pass carries a fixed token budget
+ * (Sec. 3.2).  The cache is a pool of fixed-size blocks that a sequence owns in any
+ * order (Sec. 2.1, blocked KV caching).
+ *
+ * The library covers the per-layer attention part of such a pass
+ *     fsf_kv_append        new K/V rows -> cache blocks (bit-exact copy)
+ *     fsf_ragged_attention causal attention of every new row over its sequence's
+ *                          cached + new tokens, read through the block table
+ * and the host-side decision that precedes it
+ *     fsf_compose_batch    pick generations and prompt chunks that fill the budget and
+ *                          hand out cache blocks.
+ *
+ * Conventions
+ *   - All functions return FSF_OK (0) or a negative fsf_status; none throws, aborts or
+ *     prints.  fsf_strerror() names a status.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library allocates no device memory and keeps no device
+ *     state between calls.  Device work is enqueued on the given hipStream_t (passed as
+ *     void*, NULL = default stream) and is asynchronous; host arrays may be reused as
+ *     soon as a call returns.
+ *   - Token tensors are row-major [T, H, d], sequences back to back in descriptor
+ *     order; q_offset of a descriptor is the running sum of n_new.
+ *   - Caches: K and V separate, each row-major [num_blocks, n_kv_heads, block_size, d].
+ *   - Block table: int32 [n_seqs, max_blocks]; entry b of row s is the physical block
+ *     holding positions [b*block_size, (b+1)*block_size) of sequence s; unused entries
+ *     are -1 and never dereferenced.  Block ids are trusted (not range-checked on device).
+ *   - Query head hq reads KV head hq / (n_q_heads / n_kv_heads).
+ *   - fsf_kv_append for a pass must be enqueued before fsf_ragged_attention of the same
+ *     pass: attention reads this pass's tokens from the cache, n_cached counts tokens
+ *     present before the pass.
+ */
+#ifndef FSF_H
+#define FSF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FSF_OK = 0,
+  FSF_ERR_INVALID_ARG = -1, /* null pointer, bad shape, inconsistent descriptors           */
+  FSF_ERR_UNSUPPORTED = -2, /* dtype / head_dim / group size no kernel is built for        */
+  FSF_ERR_WORKSPACE = -3,   /* workspace missing or smaller than ..._workspace_bytes()      */
+  FSF_ERR_NO_BLOCKS = -4,   /* composer: requests wait but no KV block is free             */
+  FSF_ERR_HIP = -5          /* a HIP runtime call failed (launch error)                    */
+} fsf_status;
+
+typedef enum { FSF_F32 = 0, FSF_BF16 = 1, FSF_F16 = 2 } fsf_dtype;
+
+/* fsf_attn_cfg.flags */
+#define FSF_FLAG_FORCE_GENERIC 1 /* run the generic fp32 kernel even where a fast path exists */
+
+/* One sequence of the pass (paper Sec. 2: tokens processed now vs tokens in the cache). */
+typedef struct {
+  int32_t n_new;    /* tokens processed in this pass, >= 1                                  */
+  int32_t n_cached; /* tokens in the cache BEFORE this pass, >= 0                          */
+  int32_t q_offset; /* first row of this sequence in the [T, H, d] token tensors           */
+  int32_t seq_id;   /* caller's tag; not interpreted by the kernels                        */
+} fsf_seq_desc;
+
+typedef struct {
+  int32_t n_q_heads;
+  int32_t n_kv_heads; /* divides n_q_heads                                                  */
+  int32_t head_dim;
+  int32_t block_size; /* tokens per cache block                                             */
+  int32_t window;     /* 0: row at position p sees keys 0..p; W>0: keys j with 0 <= p-j < W */
+  float scale;        /* multiplies q.k before the softmax, normally 1/sqrt(head_dim)      */
+  int32_t dtype;      /* fsf_dtype of q, k_new, v_new, both caches and out                  */
+  int32_t flags;      /* 0, or FSF_FLAG_* bits                                              */
+  int64_t num_blocks; /* physical blocks in each cache                                      */
+} fsf_attn_cfg;
+
+const char* fsf_strerror(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fsf_version(void);
+
+/*
+ * KV-cache append (paper Sec. 2: a pass adds its tokens to the sequence's cache;
+ * Sec. 2.1: storage is block granular).  For token i of sequence s (position
+ * p = n_cached + i) and every KV head h, copies k_new[q_offset+i, h, :] to
+ * k_cache[block_tables[s, p / block_size], h, p % block_size, :], same for V.
+ * Bit-exact; no other cache byte is written.
+ *   k_new, v_new        device, [n_tokens, n_kv_heads, d]
+ *   k_cache, v_cache    device, [num_blocks, n_kv_heads, block_size, d]
+ *   descs_dev           device, [n_seqs]
+ *   block_tables_dev    device, [n_seqs, max_blocks]
+ * n_seqs == 0 or n_tokens == 0 is a no-op.  Requires head_dim * sizeof(element) % 4 == 0.
+ */
+int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new, void* k_cache,
+                  void* v_cache, const fsf_seq_desc* descs_dev, const int32_t* block_tables_dev,
+                  int32_t n_seqs, int32_t max_blocks, int32_t n_tokens, void* hip_stream);
+
+/*
+ * Bytes of device workspace fsf_ragged_attention needs for a pass of at most n_seqs
+ * sequences, n_tokens tokens and max_blocks table columns.  Never zero (a small plan
+ * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.
+ */
+size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_seqs,
+                                            int32_t n_tokens, int32_t max_blocks);
+
+/*
+ * Ragged blocked-KV causal attention (paper Sec. 2 and 3.2: prompt chunks attend to
+ * their own earlier chunks in the cache, generations to their whole history, all in one
+ * pass).  For row i of sequence s (p = n_cached + i), query head hq, KV head hk:
+ *     J = { j : 0 <= j <= p and (window == 0 or p - j < window) }
+ *     out[q_offset+i, hq, :] = sum_{j in J} softmax_J(scale * q.k_j)_j * v_j
+ * with k_j, v_j read from the caches through the block table.  Scores, softmax and
+ * accumulation are fp32; bf16/f16 inputs use matrix cores with the softmax weights
+ * rounded to the storage type for the second product; the result is rounded to the
+ * storage type (nearest even).  Cache slots beyond a row's visible set never influence
+ * the result, whatever bits they hold.
+ *   q, out              device, [n_tokens, n_q_heads, d]
+ *   descs_dev           device copy of the descriptors
+ *   descs_host          host copy of the same descriptors (validated, sizes the launch)
+ *   workspace           device, >= fsf_ragged_attention_workspace_bytes(...), 256-aligned;
+ *                       contents are scratch, not preserved, no initialisation needed
+ * Validation (host side): n_new >= 1, n_cached >= 0, q_offsets are the running sum of
+ * n_new and end at n_tokens, ceil((n_cached+n_new)/block_size) <= max_blocks.
+ * Fast paths: bf16/f16 with head_dim 128 and block_size a multiple of 32; every other
+ * supported shape (any dtype, head_dim <= 256 and a multiple of 4/sizeof-ratio, any
+ * block_size) runs a generic fp32 kernel.
+ */
+int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
+                         const void* v_cache, const fsf_seq_desc* descs_dev,
+                         const fsf_seq_desc* descs_host, const int32_t* block_tables_dev,
+                         int32_t n_seqs, int32_t max_blocks, int32_t n_tokens, void* out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Host-side Dynamic SplitFuse scheduler with a block allocator (paper Sec. 2.2: one
+ * batch decision per forward pass; Sec. 3.2: long prompts are split over passes with
+ * only the last chunk generating, and prompts are fused with generations to meet the
+ * token budget exactly when enough tokens wait).  Policy where the paper is silent:
+ * generations first, one token each, least recently scheduled first; prompts first come
+ * first served, a partly processed prompt continues before a new one starts; a chunk
+ * takes min(remaining prompt, remaining budget); blocks are popped from the front of
+ * the free list and returned to its back when a sequence retires; without free blocks
+ * a generation is skipped for the pass and a prompt chunk shrinks to what fits, after
+ * which no later prompt is started; there is no eviction.
+ */
+typedef struct fsf_sched fsf_sched;
+
+/* free_list_order: NULL (blocks 0..num_blocks-1) or a permutation of them (host). */
+int fsf_sched_create(fsf_sched** out, int32_t token_budget, int32_t max_seqs, int32_t block_size,
+                     int64_t num_blocks, const int32_t* free_list_order);
+void fsf_sched_destroy(fsf_sched* s);
+
+/* Queue a request: prompt_len >= 1 tokens to read, max_new_tokens >= 1 tokens to emit.
+ * The sequence emits its first token in the pass that consumes its last prompt token,
+ * then runs as a generation until max_new_tokens are emitted; the last emitted token
+ * is never fed back, so the cache ends at prompt_len + max_new_tokens - 1 tokens. */
+int fsf_sched_add_request(fsf_sched* s, int32_t seq_id, int32_t prompt_len, int32_t max_new_tokens);
+
+/*
+ * Compose the next pass.  All outputs are host arrays:
+ *   descs_out         [max_seqs]               descriptors, generations first
+ *   block_tables_out  [max_seqs, max_blocks]   every block of each scheduled sequence, -1 padded
+ *   emits_token_out   [max_seqs]               1 if the sequence produces a token in this pass
+ * Blocks are allocated here; the pass stays pending until fsf_sched_step_done().
+ * Returns FSF_ERR_INVALID_ARG if a pass is already pending or a sequence would need more
+ * than max_blocks blocks (state unchanged), FSF_ERR_NO_BLOCKS if requests exist but
+ * nothing can be scheduled.  With no requests at all: FSF_OK and *n_seqs_out = 0.
+ */
+int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t* block_tables_out,
+                      int32_t max_blocks, int32_t* n_seqs_out, int32_t* n_tokens_out,
+                      int32_t* emits_token_out);
+
+/* Commit the pending pass: advance n_cached, turn finished prompts into generations,
+ * retire sequences that emitted max_new_tokens and free their blocks. */
+int fsf_sched_step_done(fsf_sched* s);
+
+/* Introspection (host): free blocks, live sequences (waiting prompts + generations). */
+int64_t fsf_sched_free_blocks(const fsf_sched* s);
+int32_t fsf_sched_live_seqs(const fsf_sched* s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSF_H */

@@ -1,0 +1,111 @@
+// C-ABI entry points: argument validation, path selection, launches.
+//
+// The entry points follow the paper's statement of the problem: a pass is a list of
+// (tokens now, tokens cached) per sequence (Sec. 2) over a blocked cache (Sec. 2.1).
+#include <string.h>
+
+#include "fsf_internal.h"
+
+namespace {
+
+using fsf::Pass;
+
+bool cfg_ok(const fsf_attn_cfg* c) {
+  if (!c) return false;
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return false;
+  if (c->head_dim < 1 || c->block_size < 1 || c->window < 0 || c->num_blocks < 1) return false;
+  if (c->dtype != FSF_F32 && c->dtype != FSF_BF16 && c->dtype != FSF_F16) return false;
+  return true;
+}
+
+int elem_size(const fsf_attn_cfg* c) { return c->dtype == FSF_F32 ? 4 : 2; }
+
+Pass make_pass(const fsf_attn_cfg* c, const fsf_seq_desc* descs_dev, const int32_t* bt_dev,
+               int32_t n_seqs, int32_t max_blocks, int32_t n_tokens) {
+  Pass p;
+  p.n_q_heads = c->n_q_heads;
+  p.n_kv_heads = c->n_kv_heads;
+  p.group = c->n_q_heads / c->n_kv_heads;
+  p.head_dim = c->head_dim;
+  p.block_size = c->block_size;
+  p.window = c->window;
+  p.scale = c->scale;
+  p.dtype = c->dtype;
+  p.n_seqs = n_seqs;
+  p.max_blocks = max_blocks;
+  p.n_tokens = n_tokens;
+  p.descs = descs_dev;
+  p.block_tables = bt_dev;
+  return p;
+}
+
+// Descriptors must tile [0, n_tokens) in order and fit the block table.
+bool descs_ok(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs, int32_t max_blocks,
+              int32_t n_tokens) {
+  int64_t off = 0;
+  for (int32_t s = 0; s < n_seqs; ++s) {
+    if (h[s].n_new < 1 || h[s].n_cached < 0 || h[s].q_offset != off) return false;
+    const int64_t total = (int64_t)h[s].n_new + h[s].n_cached;
+    if ((total + c->block_size - 1) / c->block_size > max_blocks) return false;
+    off += h[s].n_new;
+  }
+  return off == n_tokens;
+}
+
+}  // namespace
+
+extern "C" const char* fsf_strerror(int status) {
+  switch (status) {
+    case FSF_OK: return "ok";
+    case FSF_ERR_INVALID_ARG: return "invalid argument";
+    case FSF_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or group size";
+    case FSF_ERR_WORKSPACE: return "workspace missing or too small";
+    case FSF_ERR_NO_BLOCKS: return "no free KV block";
+    case FSF_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int fsf_version(void) { return 100; }
+
+extern "C" int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new,
+                             void* k_cache, void* v_cache, const fsf_seq_desc* descs_dev,
+                             const int32_t* block_tables_dev, int32_t n_seqs, int32_t max_blocks,
+                             int32_t n_tokens, void* hip_stream) {
+  if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return FSF_ERR_INVALID_ARG;
+  if (n_seqs == 0 || n_tokens == 0) return FSF_OK;
+  if (!k_new || !v_new || !k_cache || !v_cache || !descs_dev || !block_tables_dev)
+    return FSF_ERR_INVALID_ARG;
+  if ((cfg->head_dim * elem_size(cfg)) % 4) return FSF_ERR_UNSUPPORTED;
+  const Pass p = make_pass(cfg, descs_dev, block_tables_dev, n_seqs, max_blocks, n_tokens);
+  const hipError_t e =
+      fsf::launch_kv_append(p, k_new, v_new, k_cache, v_cache, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+}
+
+extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_seqs,
+                                                       int32_t n_tokens, int32_t max_blocks) {
+  if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return 0;
+  return 256;
+}
+
+extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
+                                    const void* v_cache, const fsf_seq_desc* descs_dev,
+                                    const fsf_seq_desc* descs_host,
+                                    const int32_t* block_tables_dev, int32_t n_seqs,
+                                    int32_t max_blocks, int32_t n_tokens, void* out,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return FSF_ERR_INVALID_ARG;
+  if (n_seqs == 0 && n_tokens == 0) return FSF_OK;
+  if (!q || !k_cache || !v_cache || !descs_dev || !descs_host || !block_tables_dev || !out)
+    return FSF_ERR_INVALID_ARG;
+  if (!descs_ok(cfg, descs_host, n_seqs, max_blocks, n_tokens)) return FSF_ERR_INVALID_ARG;
+  if (cfg->head_dim > 256) return FSF_ERR_UNSUPPORTED;
+  const size_t need = fsf_ragged_attention_workspace_bytes(cfg, n_seqs, n_tokens, max_blocks);
+  if (!workspace || workspace_bytes < need) return FSF_ERR_WORKSPACE;
+
+  const Pass p = make_pass(cfg, descs_dev, block_tables_dev, n_seqs, max_blocks, n_tokens);
+  const hipError_t e =
+      fsf::launch_attn_generic(p, q, k_cache, v_cache, out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+}

@@ -1,0 +1,62 @@
+// KV-cache append: scatter this pass's K/V rows into their cache blocks, bit for bit.
+//
+// Paper Sec. 2 (a pass adds its tokens to the sequence's cache) and Sec. 2.1 (the cache is
+// a pool of fixed-size blocks).  Token i of sequence s sits at position p = n_cached + i,
+// i.e. block block_tables[s][p / B], slot p % B.  Pure copy: HBM bound, a fraction of a
+// percent of the attention traffic.
+//
+// One workgroup per token.  A token's K row is n_kv_heads * d contiguous elements in
+// k_new; in the cache head h of that row is a contiguous d-element run at
+// [blk][h][slot][:].  Threads move 16-byte (or 4-byte) units, so each head run is written
+// with whole-wave coalesced stores.
+#include "fsf_internal.h"
+
+namespace fsf {
+namespace {
+
+template <typename Unit>
+__global__ __launch_bounds__(256) void kv_append_kernel(Pass p, const Unit* __restrict__ k_new,
+                                                        const Unit* __restrict__ v_new,
+                                                        Unit* __restrict__ k_cache,
+                                                        Unit* __restrict__ v_cache,
+                                                        int units_per_head) {
+  const int t = blockIdx.x;
+  const int s = find_seq(p.descs, p.n_seqs, t);
+  const fsf_seq_desc d = p.descs[s];
+  const int pos = d.n_cached + (t - d.q_offset);
+  const int64_t blk = p.block_tables[(int64_t)s * p.max_blocks + pos / p.block_size];
+  const int slot = pos % p.block_size;
+
+  const int row_units = p.n_kv_heads * units_per_head;
+  const int64_t src = (int64_t)t * row_units;
+  // cache element [blk][h][slot][0] in units
+  const int64_t blk_base = blk * p.n_kv_heads * (int64_t)p.block_size * units_per_head;
+  for (int u = threadIdx.x; u < row_units; u += blockDim.x) {
+    const int h = u / units_per_head;
+    const int w = u - h * units_per_head;
+    const int64_t dst = blk_base + ((int64_t)h * p.block_size + slot) * units_per_head + w;
+    k_cache[dst] = k_new[src + u];
+    v_cache[dst] = v_new[src + u];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
+                            void* v_cache, hipStream_t stream) {
+  if (p.n_tokens == 0 || p.n_seqs == 0) return hipSuccess;
+  const int esize = p.dtype == FSF_F32 ? 4 : 2;
+  const int head_bytes = p.head_dim * esize;
+  if (head_bytes % 16 == 0) {
+    kv_append_kernel<uint4><<<p.n_tokens, 256, 0, stream>>>(
+        p, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache, (uint4*)v_cache,
+        head_bytes / 16);
+  } else {
+    kv_append_kernel<uint32_t><<<p.n_tokens, 256, 0, stream>>>(
+        p, (const uint32_t*)k_new, (const uint32_t*)v_new, (uint32_t*)k_cache,
+        (uint32_t*)v_cache, head_bytes / 4);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace fsf

@@ -1,0 +1,90 @@
+"""The library's host composer (fsf_compose_batch) against the oracle composer: equal schedules."""
+import numpy as np
+import pytest
+
+from oracle.composer import NoBlocksError, SplitFuseComposer
+from paper_2401_08671_amd import fsf
+from paper_2401_08671_amd import workloads as wl
+
+
+def run_both(budget, max_seqs, B, num_blocks, arrivals, n_steps, free_order=None, max_blocks=None):
+    if max_blocks is None:
+        max_blocks = num_blocks
+    ref = SplitFuseComposer(budget, max_seqs, B, num_blocks, free_order)
+    nat = fsf.Scheduler(budget, max_seqs, B, num_blocks, max_blocks, free_order)
+    steps = 0
+    for step in range(n_steps):
+        for sid, plen, gen in arrivals.get(step, []):
+            ref.add_request(sid, plen, gen)
+            nat.add_request(sid, plen, gen)
+        try:
+            descs, tables, emits = ref.compose()
+        except NoBlocksError:
+            with pytest.raises(fsf.FsfError) as ei:
+                nat.compose_batch()
+            assert ei.value.status == fsf.FSF_ERR_NO_BLOCKS
+            return steps
+        nd, nt, ne = nat.compose_batch()
+        assert nd.tolist() == [list(d) for d in descs], f"step {step}"
+        assert ne.tolist() == emits
+        for row, tab in zip(nt, tables):
+            assert row[:len(tab)].tolist() == tab and np.all(row[len(tab):] == -1)
+        ref.step_done()
+        nat.step_done()
+        assert nat.free_blocks() == ref.n_free_blocks() and nat.live_seqs() == ref.n_live()
+        steps += 1
+        if step > max(arrivals, default=0) and ref.n_live() == 0:
+            break
+    return steps
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_equal_schedules_random_streams(seed):
+    rng = np.random.default_rng(100 + seed)
+    budget = int(rng.integers(4, 300))
+    B = int(rng.choice([1, 2, 16, 64]))
+    max_seqs = int(rng.integers(2, 80))
+    arrivals, sid, tot = {}, 0, 0
+    for step in range(120):
+        for _ in range(rng.poisson(0.5)):
+            plen, gen = int(rng.integers(1, 5 * budget)), int(rng.integers(1, 50))
+            arrivals.setdefault(step, []).append((sid, plen, gen))
+            tot += -(-(plen + gen) // B)
+            sid += 1
+    # seeds alternate between a roomy pool and a tight one (exercises shrinking/skipping)
+    num_blocks = max(tot, 1) if seed % 2 == 0 else max(tot // 6, 8)
+    order = rng.permutation(num_blocks)
+    run_both(budget, max_seqs, B, num_blocks, arrivals, 20000, order)
+
+
+def test_long_prompt_stream_shape_200_steps():
+    """The benchmark's stream: 13B-shaped budget 4096, block 64, 200 passes."""
+    reqs = wl.stream_requests(200, 1.0)
+    arrivals = {}
+    for step, sid, plen, gen in reqs:
+        arrivals.setdefault(step, []).append((sid, plen, gen))
+    need = sum(-(-(p + g) // 64) for _, _, p, g in reqs)
+    steps = run_both(4096, 4096, 64, need, arrivals, 200, max_blocks=-(-(32768 + 600) // 64))
+    assert steps == 200
+
+
+def test_error_paths():
+    s = fsf.Scheduler(8, 4, 4, 4, max_blocks=2)
+    with pytest.raises(fsf.FsfError):
+        s.add_request(0, 0, 1)
+    with pytest.raises(fsf.FsfError):
+        s.step_done()                                   # nothing composed
+    assert s.compose_batch()[0].shape == (0, 4)          # no requests: empty pass
+    s.step_done()
+    s.add_request(7, 12, 1)                              # needs 3 blocks > max_blocks=2 in pass 2
+    d, t, e = s.compose_batch()
+    assert d.tolist() == [[8, 0, 0, 7]]
+    with pytest.raises(fsf.FsfError):
+        s.compose_batch()                                # pass still pending
+    s.step_done()
+    with pytest.raises(fsf.FsfError) as ei:
+        s.compose_batch()                                # third block does not fit the table
+    assert ei.value.status == fsf.FSF_ERR_INVALID_ARG
+    assert s.free_blocks() == 2                          # state untouched by the failed call
+    with pytest.raises(fsf.FsfError):
+        fsf.Scheduler(8, 4, 4, 4, 2, free_list_order=[0, 1, 1, 3])   # not a permutation

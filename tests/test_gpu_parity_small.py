@@ -1,0 +1,134 @@
+"""HIP path vs the fp64 oracle, element by element, at sizes the oracle finishes in seconds.
+
+KV cache contents: bit-exact.  Outputs: max-abs <= 2e-2 and mean-abs <= 2e-3 for bf16/f16
+(the stated bar), max-abs <= 1e-4 and mean-abs <= 1e-5 for fp32.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2401_08671_amd import fsf
+from paper_2401_08671_amd import workloads as wl
+from tests.gpu_util import assert_cache_bit_exact, assert_outputs_close, run_hip
+from tests.helpers import Step
+
+pytestmark = pytest.mark.gpu
+
+
+def check_step(step, flags=0, what=""):
+    kc_o, vc_o, out_o = step.oracle()
+    kc_h, vc_h, out_h = run_hip(step, flags=flags)
+    assert_cache_bit_exact(kc_h, kc_o, what + " K")
+    assert_cache_bit_exact(vc_h, vc_o, what + " V")
+    return assert_outputs_close(out_h, out_o, step.spec.dtype, what)
+
+
+# ------------------------------------------------------------------ benchmark shape 1 (tiny fp32)
+@pytest.mark.parametrize("poison", [None, "nan", "inf", "big"])
+def test_config1_full_parity(poison):
+    check_step(Step(wl.config(1), num_blocks=128, poison=poison), what=f"cfg1 poison={poison}")
+
+
+def test_config1_chunking_replay_on_device():
+    """384-token prompt as 128+64+192 vs one shot: same KV bits, outputs within tolerance of the oracle's one shot."""
+    L, Hq, Hkv, d, B, nb = 384, 4, 4, 64, 16, 64
+    q = wl.randn((L, Hq, d), "f32", 1.0, 41, "cuda")
+    k = wl.randn((L, Hkv, d), "f32", 1.0, 42, "cuda")
+    v = wl.randn((L, Hkv, d), "f32", 1.0, 43, "cuda")
+    perm = np.random.default_rng(1).permutation(nb).astype(np.int32)
+    bt = perm[:L // B][None, :]
+    cfg = fsf.make_cfg(Hq, Hkv, d, B, "f32", nb)
+
+    def run(chunks):
+        kc = torch.zeros((nb, Hkv, B, d), device="cuda")
+        vc = torch.zeros_like(kc)
+        outs, c = [], 0
+        for n in chunks:
+            batch = fsf.DeviceBatch(np.array([[n, c, 0, 0]], np.int32), bt)
+            out = torch.empty((n, Hq, d), device="cuda")
+            ws = fsf.alloc_workspace(cfg, 1, n, bt.shape[1])
+            fsf.kv_append(cfg, k[c:c + n].contiguous(), v[c:c + n].contiguous(), kc, vc, batch)
+            fsf.ragged_attention(cfg, q[c:c + n].contiguous(), kc, vc, batch, out, ws)
+            outs.append(out)
+            c += n
+        torch.cuda.synchronize()
+        return torch.cat(outs).double().cpu().numpy(), kc.cpu().numpy(), vc.cpu().numpy()
+
+    one, kc1, vc1 = run([L])
+    split, kc3, vc3 = run([128, 64, 192])
+    assert np.array_equal(kc1, kc3) and np.array_equal(vc1, vc3)
+    # oracle one-shot
+    kco = np.zeros((nb, Hkv, B, d), np.float32)
+    vco = np.zeros_like(kco)
+    descs = np.array([[L, 0, 0, 0]], np.int32)
+    oa.kv_append(kco, vco, k.cpu().numpy(), v.cpu().numpy(), descs, bt, B)
+    ref = oa.ragged_attention(q.cpu().numpy(), kco, vco, descs, bt, block_size=B, scale=d ** -0.5, dtype="f32")
+    assert np.array_equal(kc1, kco) and np.array_equal(vc1, vco)
+    assert_outputs_close(one, ref, "f32", "one shot")
+    assert_outputs_close(split, ref, "f32", "128+64+192")
+
+
+# ------------------------------------------------------------------ generic kernel, other shapes and dtypes
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("shape", [
+    # Hq, Hkv, d, B, window, seqs
+    (4, 2, 32, 8, 0, [(9, 0), (5, 11), (1, 13), (1, 0), (70, 3)]),
+    (8, 2, 128, 64, 50, [(33, 100), (1, 63), (1, 64), (1, 65), (130, 0)]),
+    (3, 3, 80, 16, 0, [(17, 5), (1, 300)]),
+    (2, 1, 256, 4, 7, [(6, 6), (1, 1)]),
+])
+def test_generic_kernel_shapes(dtype, shape):
+    Hq, Hkv, d, B, W, seqs = shape
+    spec = wl.BatchSpec("g", Hq, Hkv, d, B, dtype, seqs, window=W, seed=77)
+    check_step(Step(spec, poison="nan"), flags=fsf.FSF_FLAG_FORCE_GENERIC, what=f"generic {dtype} {shape[:5]}")
+
+
+def test_append_is_idempotent_and_leaves_other_slots():
+    spec = wl.BatchSpec("app", 8, 8, 128, 64, "bf16", [(200, 0), (3, 61), (1, 63), (1, 64), (1, 1000)], seed=5)
+    st = Step(spec, poison="nan")
+    kc_o, vc_o, _ = st.oracle(seq_subset=[])
+    kc_h, vc_h, _ = run_hip(st, repeat_append=3)
+    assert_cache_bit_exact(kc_h, kc_o, "K")
+    assert_cache_bit_exact(vc_h, vc_o, "V")
+
+
+# ------------------------------------------------------------------ argument errors reported, nothing launched
+def test_bad_descriptors_are_rejected():
+    spec = wl.BatchSpec("bad", 2, 2, 64, 16, "f32", [(4, 0), (1, 9)], seed=1)
+    st = Step(spec)
+    cfg = fsf.make_cfg(2, 2, 64, 16, "f32", st.num_blocks)
+    q = torch.zeros((5, 2, 64), device="cuda")
+    kc = torch.zeros((st.num_blocks, 2, 16, 64), device="cuda")
+    out = torch.zeros_like(q)
+    ws = fsf.alloc_workspace(cfg, 2, 5, st.block_tables.shape[1])
+    for mutate in ("n_new0", "offset", "blocks", "total"):
+        descs = st.descs.copy()
+        bt = st.block_tables
+        if mutate == "n_new0":
+            descs[1, 0] = 0
+        elif mutate == "offset":
+            descs[1, 2] = 3
+        elif mutate == "blocks":
+            descs[1, 1] = 16 * bt.shape[1]
+        elif mutate == "total":
+            descs[0, 0] = 3
+            descs[1, 2] = 3
+        batch = fsf.DeviceBatch(descs, bt)
+        batch.n_tokens = 5
+        with pytest.raises(fsf.FsfError) as ei:
+            fsf.ragged_attention(cfg, q, kc, kc, batch, out, ws)
+        assert ei.value.status == fsf.FSF_ERR_INVALID_ARG, mutate
+    batch = fsf.DeviceBatch(st.descs, st.block_tables)
+    with pytest.raises(fsf.FsfError) as ei:
+        fsf.ragged_attention(cfg, q, kc, kc, batch, out, None)
+    assert ei.value.status == fsf.FSF_ERR_WORKSPACE
+    torch.cuda.synchronize()
+
+
+def test_empty_pass_is_a_noop():
+    cfg = fsf.make_cfg(2, 2, 64, 16, "f32", 4)
+    batch = fsf.DeviceBatch(np.zeros((0, 4), np.int32), np.zeros((0, 1), np.int32))
+    fsf.kv_append(cfg, None, None, None, None, batch)
+    fsf.ragged_attention(cfg, None, None, None, batch, None, None)
+    torch.cuda.synchronize()
