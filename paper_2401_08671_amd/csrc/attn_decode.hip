@@ -1,0 +1,230 @@
+// Generation rows (n_new == 1): split-KV attention streaming the blocked cache once.
+//
+// A generation pass adds one token and attends to the whole cached history (paper Sec. 2),
+// so every visible K/V byte is used exactly once per KV head: the kernel is bound by HBM
+// bandwidth.  One wavefront handles one (sequence, KV head, run of cache blocks); the
+// query heads that share the KV head (GQA group, up to 16) sit side by side in the N
+// dimension of the matrix-core tiles, so K/V are read once for the whole group.
+//
+// Per step of 32 keys (two 16-key tiles a, b), with lane = (n = lane%16, kg = lane/16):
+//   S^T[key, head] = K[key, :] . Q[head, :]    8x mfma 16x16x32; A = K rows straight from
+//                                              global memory (16 B per lane), B = Q
+//   lane then owns 8 scores of ONE head n: keys 4kg+r (tile a) and 16+4kg+r (tile b);
+//   running softmax in registers; the max/sum across kg = lanes n, n+16, n+32, n+48 is a
+//   two-step xor shuffle
+//   O^T[d, head] += V^T[d, keys] . P^T[keys, head]   8x mfma 16x16x32; the 8 probabilities a
+//                                              lane owns are exactly its B-operand slots;
+//                                              A = V^T is built in-lane: the lane loads the
+//                                              same 8 d-columns (16 B) of its 8 keys and
+//                                              transposes 8x8 with byte permutes.
+// Loads for the next step are issued before the current step is computed (two register
+// buffers).  Rows outside [lo, hi] are masked with selects, never multiplied: stale or
+// poisoned cache slots cannot leak; V rows of masked keys are zeroed.
+#include <math.h>
+
+#include "fsf_internal.h"
+#include "mma.h"
+#include "numeric.h"
+
+namespace fsf {
+namespace {
+
+struct StepBuf {
+  frag8 k[2][4];  // [tile][k-step]: K[key = tile*16 + n][d = (4t + kg)*8 ..+8]
+  frag8 v[8];     // [e]: V[key = (e/4)*16 + 4kg + e%4][d = n*8 ..+8]
+};
+
+template <typename T>
+__device__ __forceinline__ void load_step(StepBuf& b, const T* __restrict__ kc,
+                                          const T* __restrict__ vc, const int32_t* bt, int key0,
+                                          int B, int n_kv_heads, int hk, int n, int kg) {
+  const int blk = key0 / B;                      // uniform
+  const int64_t phys = bt[blk];                  // scalar load
+  const int slot0 = key0 - blk * B;
+  const int64_t base = ((phys * n_kv_heads + hk) * B + slot0) * kHeadDim;
+  const T* kb = kc + base;
+  const T* vb = vc + base;
+#pragma unroll
+  for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      b.k[tile][t] = load_frag8(kb + (tile * 16 + n) * kHeadDim + (4 * t + kg) * 8);
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    b.v[e] = load_frag8(vb + ((e >> 2) * 16 + 4 * kg + (e & 3)) * kHeadDim + n * 8);
+}
+
+template <int DT>
+__device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f32x4_t (&acc)[8],
+                                             float& m, float& l, float sl2, int key0, int lo,
+                                             int hi, int kg) {
+  using M = Mma<DT>;
+  f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    sa = M::mfma16(b.k[0][t], qf[t], sa);
+    sb = M::mfma16(b.k[1][t], qf[t], sb);
+  }
+  float s[8];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    s[r] = sa[r] * sl2;
+    s[4 + r] = sb[r] * sl2;
+  }
+  const bool boundary = key0 < lo || key0 + 31 > hi;  // uniform
+  if (boundary) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int key = key0 + (e >> 2) * 16 + 4 * kg + (e & 3);
+      const bool vis = key >= lo && key <= hi;
+      if (!vis) {
+        s[e] = -INFINITY;
+        b.v[e] = zero_frag8();
+      }
+    }
+  }
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx);  // m starts finite, so m_new is finite
+  const float corr = fast_exp2(m - m_new);
+  m = m_new;
+  float pr[8], sum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    pr[e] = fast_exp2(s[e] - m_new);
+    sum += pr[e];
+  }
+  l = l * corr + sum;  // per-lane partial; the four kg lanes are added at the end
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[c][r] *= corr;
+  frag8 pf;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) pf.w[j] = M::pack2(pr[2 * j], pr[2 * j + 1]);
+  // V^T fragments: column c of the lane's 8 d-columns, over its 8 keys
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    frag8 a;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t w0 = b.v[2 * j].w[c >> 1], w1 = b.v[2 * j + 1].w[c >> 1];
+      a.w[j] = (c & 1) ? pack_hi16(w0, w1) : pack_lo16(w0, w1);
+    }
+    acc[c] = M::mfma16(a, pf, acc[c]);
+  }
+}
+
+template <int DT, typename T>
+__global__ __launch_bounds__(64) void attn_decode_kernel(Pass p, FastPlan f, const T* __restrict__ q,
+                                                         const T* __restrict__ kc,
+                                                         const T* __restrict__ vc,
+                                                         T* __restrict__ out) {
+  const int lane = threadIdx.x;
+  const int n = lane & 15, kg = lane >> 4;
+  const int item = blockIdx.x / p.n_kv_heads;
+  const int hk = blockIdx.x - item * p.n_kv_heads;
+  // sequence owning this item: largest s with dec_item_start[s] <= item
+  int s;
+  {
+    int a = 0, b = p.n_seqs - 1;
+    while (a < b) {
+      const int mid = (a + b + 1) >> 1;
+      if (f.dec_item_start[mid] <= item) a = mid; else b = mid - 1;
+    }
+    s = a;
+  }
+  const int split = item - f.dec_item_start[s];
+  const fsf_seq_desc sd = p.descs[s];
+  const int B = p.block_size;
+  int lo, hi;
+  visible_range(sd.n_cached, p.window, lo, hi);
+  const int b_lo = lo / B, b_hi = hi / B;
+  const int n_splits = (b_hi - b_lo + f.split_blocks) / f.split_blocks;
+  const int blk0 = b_lo + split * f.split_blocks;
+  const int blk1 = min(blk0 + f.split_blocks - 1, b_hi);
+  const int key_begin = max(blk0 * B, lo & ~31);
+  const int key_end = min((blk1 + 1) * B - 1, hi);  // inclusive
+  const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
+
+  const int g = p.group;
+  const int hq = hk * g + n;
+  const bool col_live = n < g;
+  frag8 qf[4];
+  {
+    const T* qrow = q + ((int64_t)sd.q_offset * p.n_q_heads + (col_live ? hq : hk * g)) * kHeadDim;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) qf[t] = col_live ? load_frag8(qrow + (4 * t + kg) * 8) : zero_frag8();
+  }
+  f32x4_t acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m = -1e30f, l = 0.f;
+  const float sl2 = p.scale * 1.4426950408889634f;
+
+  StepBuf b0, b1;
+  int key0 = key_begin;
+  load_step(b0, kc, vc, bt, key0, B, p.n_kv_heads, hk, n, kg);
+  while (true) {
+    bool more = key0 + 32 <= key_end;
+    if (more) load_step(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
+    compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
+    if (!more) break;
+    key0 += 32;
+    more = key0 + 32 <= key_end;
+    if (more) load_step(b0, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
+    compute_step<DT>(b1, qf, acc, m, l, sl2, key0, lo, hi, kg);
+    if (!more) break;
+    key0 += 32;
+  }
+
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (!col_live) return;
+  // acc[c][r] is output column d = (4kg + r)*8 + c of head n
+  if (n_splits == 1) {
+    const float inv = 1.f / l;
+    T* orow = out + ((int64_t)sd.q_offset * p.n_q_heads + hq) * kHeadDim;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      uint4 w;
+      w.x = Mma<DT>::pack2(acc[0][r] * inv, acc[1][r] * inv);
+      w.y = Mma<DT>::pack2(acc[2][r] * inv, acc[3][r] * inv);
+      w.z = Mma<DT>::pack2(acc[4][r] * inv, acc[5][r] * inv);
+      w.w = Mma<DT>::pack2(acc[6][r] * inv, acc[7][r] * inv);
+      *reinterpret_cast<uint4*>(orow + (4 * kg + r) * 8) = w;
+    }
+  } else {
+    const int64_t pi = (int64_t)item * p.n_q_heads + hq;
+    if (kg == 0) {
+      f.part_ml[pi * 2] = m;
+      f.part_ml[pi * 2 + 1] = l;
+    }
+    float* prow = f.part_acc + pi * kHeadDim;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float4 lo4 = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+      float4 hi4 = {acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
+      *reinterpret_cast<float4*>(prow + (4 * kg + r) * 8) = lo4;
+      *reinterpret_cast<float4*>(prow + (4 * kg + r) * 8 + 4) = hi4;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, hipStream_t stream) {
+  if (f.n_dec_items == 0) return hipSuccess;
+  const unsigned grid = (unsigned)f.n_dec_items * p.n_kv_heads;
+  if (p.dtype == FSF_BF16)
+    attn_decode_kernel<FSF_BF16, bf16_t><<<grid, 64, 0, stream>>>(
+        p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out);
+  else
+    attn_decode_kernel<FSF_F16, f16_t><<<grid, 64, 0, stream>>>(
+        p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
+  return hipGetLastError();
+}
+
+}  // namespace fsf

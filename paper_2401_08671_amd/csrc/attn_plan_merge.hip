@@ -1,0 +1,108 @@
+// Work planning and split merging for the matrix-core attention path.
+//
+// A pass mixes one-row generations with prompt chunks of any length (paper Sec. 3.2), so
+// work per sequence is ragged.  plan_kernel turns the descriptors into two exclusive
+// prefix arrays (decode items, prefill tiles) that let every workgroup of the compute
+// kernels find its sequence with a binary search; no host-to-device copy is needed.
+//
+// merge_kernel combines the partial results of a generation row whose visible keys were
+// split across several workgroups: with per-split running maximum m_k (log2 domain),
+// sum l_k and unnormalised output a_k,
+//     m = max_k m_k,  l = sum_k l_k 2^(m_k - m),  out = sum_k a_k 2^(m_k - m) / l.
+#include "fsf_internal.h"
+#include "mma.h"
+#include "numeric.h"
+
+namespace fsf {
+namespace {
+
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) {
+  __shared__ int s_dec[kPlanThreads];
+  __shared__ int s_pre[kPlanThreads];
+  const int tid = threadIdx.x;
+  const int per = (p.n_seqs + kPlanThreads - 1) / kPlanThreads;
+  const int s0 = tid * per;
+  const int s1 = min(s0 + per, p.n_seqs);
+  int dec = 0, pre = 0;
+  for (int s = s0; s < s1; ++s) {
+    int d, t;
+    seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, d, t);
+    dec += d;
+    pre += t;
+  }
+  s_dec[tid] = dec;
+  s_pre[tid] = pre;
+  __syncthreads();
+  // inclusive scan over the per-thread sums
+  for (int off = 1; off < kPlanThreads; off <<= 1) {
+    int a = 0, b = 0;
+    if (tid >= off) {
+      a = s_dec[tid - off];
+      b = s_pre[tid - off];
+    }
+    __syncthreads();
+    s_dec[tid] += a;
+    s_pre[tid] += b;
+    __syncthreads();
+  }
+  int dec_run = s_dec[tid] - dec, pre_run = s_pre[tid] - pre;  // exclusive
+  for (int s = s0; s < s1; ++s) {
+    f.dec_item_start[s] = dec_run;
+    f.pre_tile_start[s] = pre_run;
+    int d, t;
+    seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, d, t);
+    dec_run += d;
+    pre_run += t;
+  }
+  if (tid == kPlanThreads - 1) {
+    f.dec_item_start[p.n_seqs] = s_dec[tid];
+    f.pre_tile_start[p.n_seqs] = s_pre[tid];
+  }
+}
+
+// One wave per (sequence, query head); lanes own two output columns each.
+template <typename T>
+__global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __restrict__ out) {
+  const int s = blockIdx.x / p.n_q_heads;
+  const int hq = blockIdx.x - s * p.n_q_heads;
+  const int item0 = f.dec_item_start[s];
+  const int n_splits = f.dec_item_start[s + 1] - item0;
+  if (n_splits < 2) return;  // prompt chunk, or a generation handled by a single item
+  const int lane = threadIdx.x;
+  float m = -INFINITY;
+  for (int k = 0; k < n_splits; ++k)
+    m = fmaxf(m, f.part_ml[((int64_t)(item0 + k) * p.n_q_heads + hq) * 2]);
+  float l = 0.f, a0 = 0.f, a1 = 0.f;
+  for (int k = 0; k < n_splits; ++k) {
+    const int64_t pi = (int64_t)(item0 + k) * p.n_q_heads + hq;
+    const float w = fast_exp2(f.part_ml[pi * 2] - m);
+    l += f.part_ml[pi * 2 + 1] * w;
+    const float2 a = *reinterpret_cast<const float2*>(f.part_acc + pi * kHeadDim + lane * 2);
+    a0 += a.x * w;
+    a1 += a.y * w;
+  }
+  const float inv = 1.f / l;
+  T* orow = out + ((int64_t)p.descs[s].q_offset * p.n_q_heads + hq) * kHeadDim;
+  orow[lane * 2] = from_float<T>(a0 * inv);
+  orow[lane * 2 + 1] = from_float<T>(a1 * inv);
+}
+
+}  // namespace
+
+hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream) {
+  plan_kernel<<<1, kPlanThreads, 0, stream>>>(p, f);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream) {
+  const unsigned grid = (unsigned)p.n_seqs * p.n_q_heads;
+  if (p.dtype == FSF_BF16)
+    merge_kernel<bf16_t><<<grid, 64, 0, stream>>>(p, f, (bf16_t*)out);
+  else
+    merge_kernel<f16_t><<<grid, 64, 0, stream>>>(p, f, (f16_t*)out);
+  return hipGetLastError();
+}
+
+}  // namespace fsf

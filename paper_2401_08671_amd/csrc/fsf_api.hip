@@ -2,6 +2,7 @@
 //
 // The entry points follow the paper's statement of the problem: a pass is a list of
 // (tokens now, tokens cached) per sequence (Sec. 2) over a blocked cache (Sec. 2.1).
+#include <stdlib.h>
 #include <string.h>
 
 #include "fsf_internal.h"
@@ -52,6 +53,42 @@ bool descs_ok(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs, int3
   return off == n_tokens;
 }
 
+bool fast_path_ok(const fsf_attn_cfg* c) {
+  return !(c->flags & FSF_FLAG_FORCE_GENERIC) && (c->dtype == FSF_BF16 || c->dtype == FSF_F16) &&
+         c->head_dim == fsf::kHeadDim && c->block_size % 64 == 0 &&
+         c->n_q_heads / c->n_kv_heads <= 16 && c->scale > 0.f;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Workspace sections of the matrix-core path, in order.
+struct WsLayout {
+  size_t dec_item_start, pre_tile_start, part_ml, part_acc, total;
+};
+
+WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs) {
+  const size_t items_cap = (size_t)n_seqs + fsf::kMaxDecodeItemsExtra;
+  WsLayout w;
+  size_t off = 0;
+  w.dec_item_start = off;
+  off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
+  w.pre_tile_start = off;
+  off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
+  w.part_ml = off;
+  off += align256(items_cap * c->n_q_heads * 2 * sizeof(float));
+  w.part_acc = off;
+  off += align256(items_cap * c->n_q_heads * fsf::kHeadDim * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  if (!v || !*v) return dflt;
+  const int x = atoi(v);
+  return x > 0 ? x : dflt;
+}
+
 }  // namespace
 
 extern "C" const char* fsf_strerror(int status) {
@@ -86,7 +123,8 @@ extern "C" int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const v
 extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_seqs,
                                                        int32_t n_tokens, int32_t max_blocks) {
   if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return 0;
-  return 256;
+  if (!fast_path_ok(cfg)) return 256;
+  return ws_layout(cfg, n_seqs).total;
 }
 
 extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
@@ -105,7 +143,55 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   if (!workspace || workspace_bytes < need) return FSF_ERR_WORKSPACE;
 
   const Pass p = make_pass(cfg, descs_dev, block_tables_dev, n_seqs, max_blocks, n_tokens);
-  const hipError_t e =
-      fsf::launch_attn_generic(p, q, k_cache, v_cache, out, (hipStream_t)hip_stream);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (!fast_path_ok(cfg)) {
+    const hipError_t e = fsf::launch_attn_generic(p, q, k_cache, v_cache, out, stream);
+    return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+  }
+  if (((uintptr_t)workspace & 255) != 0) return FSF_ERR_WORKSPACE;
+
+  // ---- size the decode splits: enough items to fill the chip a few times over, few enough
+  // that the partial results stay small next to the K/V traffic
+  int64_t dec_blocks = 0;
+  for (int32_t s = 0; s < n_seqs; ++s) {
+    if (descs_host[s].n_new != 1) continue;
+    int lo, hi;
+    fsf::visible_range(descs_host[s].n_cached, cfg->window, lo, hi);
+    dec_blocks += hi / cfg->block_size - lo / cfg->block_size + 1;
+  }
+  const int target_waves = env_int("FSF_DECODE_TARGET_WAVES", 16384);
+  const int min_split = env_int("FSF_DECODE_MIN_SPLIT", 4);
+  int64_t target_items = target_waves / cfg->n_kv_heads;
+  if (target_items < 1) target_items = 1;
+  if (target_items > fsf::kMaxDecodeItemsExtra) target_items = fsf::kMaxDecodeItemsExtra;
+  int64_t sb = (dec_blocks + target_items - 1) / target_items;
+  if (sb < min_split) sb = min_split;
+
+  const WsLayout w = ws_layout(cfg, n_seqs);
+  char* ws = (char*)workspace;
+  fsf::FastPlan f;
+  f.dec_item_start = (int32_t*)(ws + w.dec_item_start);
+  f.pre_tile_start = (int32_t*)(ws + w.pre_tile_start);
+  f.part_ml = (float*)(ws + w.part_ml);
+  f.part_acc = (float*)(ws + w.part_acc);
+  f.split_blocks = (int32_t)sb;
+  int64_t n_dec = 0, n_pre = 0;
+  bool any_split = false;
+  for (int32_t s = 0; s < n_seqs; ++s) {
+    int d, t;
+    fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
+                  f.split_blocks, d, t);
+    n_dec += d;
+    n_pre += t;
+    any_split |= d > 1;
+  }
+  if (n_dec > (int64_t)n_seqs + fsf::kMaxDecodeItemsExtra) return FSF_ERR_WORKSPACE;  // cannot happen
+  f.n_dec_items = (int32_t)n_dec;
+  f.n_pre_tiles = (int32_t)n_pre;
+
+  hipError_t e = fsf::launch_plan(p, f, stream);
+  if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
+  if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
+  if (e == hipSuccess && any_split) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }

@@ -32,6 +32,55 @@ __device__ __forceinline__ int find_seq(const fsf_seq_desc* descs, int n_seqs, i
   return lo;
 }
 
+// ---------------------------------------------------------------------------------------
+// Matrix-core path (bf16/f16, head_dim 128, block_size % 64 == 0, group <= 16).
+//
+// Work is cut on the device by a one-workgroup planning kernel; the host evaluates the
+// same formulas on its copy of the descriptors to size the grids.
+//   generation rows (n_new == 1): "items" = (sequence, run of split_blocks cache blocks)
+//   prompt chunks   (n_new  > 1): "tiles" = (sequence, kPrefillTileM consecutive rows)
+// ---------------------------------------------------------------------------------------
+constexpr int kHeadDim = 128;
+constexpr int kPrefillTileM = 128;   // query rows per prefill workgroup
+constexpr int kMaxDecodeItemsExtra = 8192;  // items beyond one per sequence (bounds the workspace)
+
+// Visible key range of the row at position pos.
+__host__ __device__ inline void visible_range(int pos, int window, int& lo, int& hi) {
+  hi = pos;
+  lo = (window > 0 && pos - window + 1 > 0) ? pos - window + 1 : 0;
+}
+
+// Number of decode items / prefill tiles a sequence contributes.
+__host__ __device__ inline void seq_work(int n_new, int n_cached, int window, int block_size,
+                                         int split_blocks, int& dec_items, int& pre_tiles) {
+  if (n_new == 1) {
+    int lo, hi;
+    visible_range(n_cached, window, lo, hi);
+    const int nblk = hi / block_size - lo / block_size + 1;
+    dec_items = (nblk + split_blocks - 1) / split_blocks;
+    pre_tiles = 0;
+  } else {
+    dec_items = 0;
+    pre_tiles = (n_new + kPrefillTileM - 1) / kPrefillTileM;
+  }
+}
+
+struct FastPlan {
+  int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of decode items per sequence
+  int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
+  float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
+  float* part_acc;          // [items, n_q_heads, 128] unnormalised outputs per split
+  int32_t split_blocks;
+  int32_t n_dec_items, n_pre_tiles;  // host-side totals (grid sizes)
+};
+
+hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);
+hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, hipStream_t stream);
+hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream);
+hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                               const void* v_cache, void* out, hipStream_t stream);
+
 hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
                             void* v_cache, hipStream_t stream);
 

@@ -1,0 +1,116 @@
+"""Matrix-core path (bf16/f16, head_dim 128, block 64/128) vs the fp64 oracle.
+
+Element-by-element on shapes that span several tiles and ragged tails: generation rows
+with and without KV splitting, prompt chunks with partial tiles and cached prefixes, GQA
+groups 1..16, sliding windows cutting blocks, poisoned unwritten slots.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2401_08671_amd import fsf
+from paper_2401_08671_amd import workloads as wl
+from tests.gpu_util import assert_cache_bit_exact, assert_outputs_close, run_hip
+from tests.helpers import Step
+
+pytestmark = pytest.mark.gpu
+
+
+def check_step(step, what="", flags=0):
+    kc_o, vc_o, out_o = step.oracle()
+    kc_h, vc_h, out_h = run_hip(step, flags=flags)
+    assert_cache_bit_exact(kc_h, kc_o, what + " K")
+    assert_cache_bit_exact(vc_h, vc_o, what + " V")
+    return assert_outputs_close(out_h, out_o, step.spec.dtype, what)
+
+
+@pytest.fixture
+def split_env():
+    """Force fine KV splits so the merge path runs even on short sequences."""
+    old = {k: os.environ.get(k) for k in ("FSF_DECODE_TARGET_WAVES", "FSF_DECODE_MIN_SPLIT")}
+    yield lambda waves, mins: os.environ.update(FSF_DECODE_TARGET_WAVES=str(waves), FSF_DECODE_MIN_SPLIT=str(mins))
+    for k, v in old.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
+
+
+DECODE_LENS = [0, 1, 30, 31, 32, 33, 63, 64, 65, 127, 128, 200, 511, 512, 513, 1000, 2049]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("heads", [(4, 4), (8, 2), (8, 1), (16, 1)])
+@pytest.mark.parametrize("poison", ["nan", None])
+def test_decode_rows(dtype, heads, poison):
+    Hq, Hkv = heads
+    spec = wl.BatchSpec("dec", Hq, Hkv, 128, 64, dtype, [(1, c) for c in DECODE_LENS], seed=9)
+    check_step(Step(spec, poison=poison), f"decode {dtype} {heads} poison={poison}")
+
+
+@pytest.mark.parametrize("split", [(1 << 20, 1), (1 << 20, 2), (64, 4)])
+@pytest.mark.parametrize("window", [0, 100, 128, 1000])
+def test_decode_rows_split_and_window(split_env, split, window):
+    split_env(*split)
+    spec = wl.BatchSpec("decw", 8, 2, 128, 64, "bf16", [(1, c) for c in DECODE_LENS], window=window, seed=10)
+    check_step(Step(spec, poison="nan"), f"decode split={split} window={window}")
+
+
+def test_decode_block_128():
+    spec = wl.BatchSpec("dec128", 4, 2, 128, 128, "bf16", [(1, c) for c in (5, 127, 128, 300, 1025)],
+                        seed=12)
+    check_step(Step(spec, poison="inf"), "decode B=128")
+
+
+PREFILL_SEQS = [(1, 5), (2, 0), (33, 0), (64, 64), (127, 1), (128, 0), (129, 63), (300, 200), (5, 1000)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("heads", [(2, 2), (8, 2)])
+@pytest.mark.parametrize("window", [0, 70, 256])
+def test_prefill_chunks(dtype, heads, window):
+    Hq, Hkv = heads
+    spec = wl.BatchSpec("pre", Hq, Hkv, 128, 64, dtype, PREFILL_SEQS, window=window, seed=13)
+    check_step(Step(spec, poison="nan"), f"prefill {dtype} {heads} window={window}")
+
+
+def test_prefill_long_chunk_over_long_prefix():
+    spec = wl.BatchSpec("prelong", 2, 1, 128, 64, "bf16", [(700, 1500), (1, 2199)], seed=14)
+    check_step(Step(spec, poison="nan"), "prefill 700 rows over 1500 cached")
+
+
+def test_mixed_batch_order_independent():
+    """Chunks and generations interleaved in any order (the kernels may not assume chunks come first)."""
+    seqs = [(1, 77), (150, 10), (1, 640), (3, 0), (1, 0), (260, 300), (1, 129)]
+    spec = wl.BatchSpec("mix", 8, 8, 128, 64, "bf16", seqs, seed=15)
+    check_step(Step(spec, poison="nan"), "mixed order")
+
+
+def test_fast_path_matches_generic_kernel_within_tolerance():
+    """Two independent device paths agree (both are also checked against the oracle above)."""
+    spec = wl.BatchSpec("xchk", 8, 2, 128, 64, "bf16", [(100, 30), (1, 500), (1, 64)], seed=16)
+    st = Step(spec)
+    _, _, fast = run_hip(st)
+    _, _, gen = run_hip(st, flags=fsf.FSF_FLAG_FORCE_GENERIC)
+    assert np.abs(fast - gen).max() <= 2e-2
+
+
+def test_results_are_deterministic():
+    spec = wl.BatchSpec("det", 8, 2, 128, 64, "bf16", [(200, 100)] + [(1, c) for c in (900, 64, 3000)], seed=17)
+    st = Step(spec)
+    _, _, a = run_hip(st)
+    _, _, b = run_hip(st)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("k,nd", [(2, 24), (3, 48), (4, 40)])
+def test_benchmark_shapes_reduced(k, nd):
+    """Benchmark shapes 2-4 with fewer generation rows: full element-wise parity."""
+    spec = wl.config(k, n_decodes=nd)
+    if k == 3:      # keep the oracle's dense score matrices small: shorter prefixes, same window logic
+        spec.seqs = [(256, 2048), (256, 6144)] + spec.seqs[2:]
+    if k == 2:
+        spec.seqs = [(448, 0)] + spec.seqs[1:]
+    check_step(Step(spec), f"cfg{k} reduced")
