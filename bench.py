@@ -1,0 +1,210 @@
+"""Benchmark: one Dynamic SplitFuse forward step (KV append + ragged attention) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A "step" is one pass of the whole hot path over one ragged batch of synthetic input:
+fsf_kv_append followed by fsf_ragged_attention for one layer.  The default workload is the
+Llama-2-7B-shaped batch with a 2048-token budget (one 1792-token prompt chunk plus 256
+generation rows).  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is tokens/s of the whole step.  `roofline` prices the
+dominant kernel (generation-row attention, HBM bound) by its algorithmic bytes and its
+average duration measured with HIP events on the launch stream inside the timed region.
+`cpu_baseline` times the fp64 oracle on the host cores for a bounded sample of the batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2401_08671_amd import fsf  # noqa: E402
+from paper_2401_08671_amd import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+
+
+def algorithmic_work(spec: wl.BatchSpec):
+    """Bytes and flops the method must move/compute, per kernel class, from the descriptors."""
+    e = wl.DTYPE_BYTES[spec.dtype]
+    d, Hq, Hkv = spec.head_dim, spec.n_q_heads, spec.n_kv_heads
+    dec_bytes = pre_bytes = 0
+    dec_flops = pre_flops = 0
+    for n, c in spec.seqs:
+        ps = np.arange(c, c + n, dtype=np.int64) + 1          # keys visible to each row without a window
+        pairs = int(np.minimum(ps, spec.window).sum() if spec.window else ps.sum())
+        vis_tokens = (c + n) if not spec.window else min(c + n, spec.window + n - 1)
+        kv = 2 * Hkv * d * e * vis_tokens           # K+V read once per step
+        qo = 2 * Hq * d * e * n                     # Q in, O out
+        fl = 4 * d * pairs * Hq
+        if n == 1:
+            dec_bytes += kv + qo
+            dec_flops += fl
+        else:
+            pre_bytes += kv + qo
+            pre_flops += fl
+    append_bytes = 4 * Hkv * d * e * spec.n_tokens   # read new K/V, write them to the cache
+    return dict(decode_bytes=dec_bytes, prefill_bytes=pre_bytes, append_bytes=append_bytes,
+                decode_flops=dec_flops, prefill_flops=pre_flops,
+                total_bytes=dec_bytes + pre_bytes + append_bytes)
+
+
+class DeviceStep:
+    """All device buffers of one step, generated on the GPU with seeded generators."""
+
+    def __init__(self, spec: wl.BatchSpec, device="cuda"):
+        self.spec = spec
+        B, Hq, Hkv, d = spec.block_size, spec.n_q_heads, spec.n_kv_heads, spec.head_dim
+        need = spec.blocks_needed()
+        self.num_blocks = need + max(16, need // 50)
+        rng = np.random.default_rng(spec.seed)
+        self.descs = wl.make_descs(spec.seqs)
+        self.block_tables = wl.make_block_tables(spec.seqs, B, self.num_blocks, rng)
+        self.batch = fsf.DeviceBatch(self.descs, self.block_tables, device)
+        T = spec.n_tokens
+        tdt = wl.TORCH_DTYPE[spec.dtype]
+        self.q = wl.randn((T, Hq, d), spec.dtype, spec.value_mult, spec.seed * 7 + 1, device)
+        self.k_new = wl.randn((T, Hkv, d), spec.dtype, spec.value_mult, spec.seed * 7 + 2, device)
+        self.v_new = wl.randn((T, Hkv, d), spec.dtype, spec.value_mult, spec.seed * 7 + 3, device)
+        self.k_cache = torch.empty((self.num_blocks, Hkv, B, d), dtype=tdt, device=device)
+        self.v_cache = torch.empty_like(self.k_cache)
+        wl.fill_pool_(self.k_cache, spec.value_mult, spec.seed * 7 + 4)
+        wl.fill_pool_(self.v_cache, spec.value_mult, spec.seed * 7 + 5)
+        self.out = torch.zeros((T, Hq, d), dtype=tdt, device=device)
+        self.cfg = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window, scale=spec.scale)
+        self.ws = fsf.alloc_workspace(self.cfg, self.batch.n_seqs, self.batch.n_tokens, self.batch.max_blocks, device)
+
+    def step(self):
+        fsf.kv_append(self.cfg, self.k_new, self.v_new, self.k_cache, self.v_cache, self.batch)
+        fsf.ragged_attention(self.cfg, self.q, self.k_cache, self.v_cache, self.batch, self.out, self.ws)
+
+
+def cpu_baseline(ds: DeviceStep, k_cache0: np.ndarray, v_cache0: np.ndarray, n_decode_sample: int = 48):
+    """Time the fp64 oracle (as it stands) on every prompt chunk plus a seeded sample of generation rows."""
+    from oracle import attention as oa
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    spec = ds.spec
+    rng = np.random.default_rng(spec.seed + 99)
+    dec = [s for s, (n, _) in enumerate(spec.seqs) if n == 1]
+    pre = [s for s, (n, _) in enumerate(spec.seqs) if n > 1]
+    sample = sorted(rng.choice(dec, size=min(n_decode_sample, len(dec)), replace=False).tolist()) if dec else []
+    q = wl.to_numpy_storage(ds.q)
+    k_new, v_new = wl.to_numpy_storage(ds.k_new), wl.to_numpy_storage(ds.v_new)
+    t0 = time.perf_counter()
+    oa.kv_append(k_cache0, v_cache0, k_new, v_new, ds.descs, ds.block_tables, spec.block_size)
+    t_app = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    out_pre = oa.ragged_attention(q, k_cache0, v_cache0, ds.descs, ds.block_tables, block_size=spec.block_size,
+                                  scale=spec.scale, window=spec.window, dtype=spec.dtype, seq_subset=pre)
+    t_pre = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    out_dec = oa.ragged_attention(q, k_cache0, v_cache0, ds.descs, ds.block_tables, block_size=spec.block_size,
+                                  scale=spec.scale, window=spec.window, dtype=spec.dtype, seq_subset=sample)
+    t_dec = time.perf_counter() - t0
+    # generation rows cost in proportion to the keys they read
+    keys = lambda idx: sum(min(spec.seqs[s][1] + 1, spec.window) if spec.window else spec.seqs[s][1] + 1 for s in idx)
+    t_dec_full = t_dec * keys(dec) / max(keys(sample), 1) if sample else 0.0
+    t_full = t_app + t_pre + t_dec_full
+    ref = np.where(np.isnan(out_pre), out_dec, out_pre)
+    return dict(value=spec.n_tokens / t_full, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=(f"append of all {spec.n_tokens} tokens ({t_app:.2f}s) + all {len(pre)} prompt chunks ({t_pre:.2f}s) + "
+                        f"{len(sample)} of {len(dec)} generation rows ({t_dec:.2f}s), generation time scaled to the "
+                        f"full batch by visible keys; numpy fp64")), ref
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the attention step shards by KV head with no "
+              "exchange inside it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    spec = wl.config(args.config)
+    ds = DeviceStep(spec)
+    work = algorithmic_work(spec)
+    torch.cuda.synchronize()
+    k0 = v0 = None
+    if not args.no_cpu_baseline:
+        k0, v0 = wl.to_numpy_storage(ds.k_cache), wl.to_numpy_storage(ds.v_cache)
+
+    for _ in range(args.warmup):
+        ds.step()
+    torch.cuda.synchronize()
+
+    fsf.profile_enable(True)
+    fsf.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ds.step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = fsf.profile_read()
+    fsf.profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = spec.n_tokens / (ms_per_step * 1e-3)
+    phase_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
+    dec_ms = phase_ms["decode"]
+    achieved = work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"decode_traffic_cfg{args.config}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("hbm_bytes_per_launch")
+    line = {
+        "metric": "ragged SplitFuse attn tokens/s per step + % HBM/MFMA roofline, 1 GPU",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": f"{spec.name}: Hq={spec.n_q_heads} Hkv={spec.n_kv_heads} d={spec.head_dim} "
+                               f"block={spec.block_size} window={spec.window} budget={spec.n_tokens} "
+                               f"({sum(1 for n, _ in spec.seqs if n > 1)} prompt chunks, "
+                               f"{sum(1 for n, _ in spec.seqs if n == 1)} generation rows), one layer",
+                   "n_seqs": spec.n_seqs, "n_tokens": spec.n_tokens, "kv_pool_blocks": ds.num_blocks},
+        "roofline": {"bound": "hbm", "kernel": "attn_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": work["decode_bytes"], "avg_launch_ms": dec_ms},
+        "phases_ms": phase_ms,
+        "step_roofline": {"algorithmic_bytes": work["total_bytes"],
+                          "achieved_GBs": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9,
+                          "frac_hbm": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "prefill_mfma": {"algorithmic_flops": work["prefill_flops"],
+                         "achieved_TFLOPs": (work["prefill_flops"] / (phase_ms["prefill"] * 1e-3) / 1e12) if phase_ms["prefill"] else 0.0,
+                         "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS},
+    }
+    line["prefill_mfma"]["frac"] = line["prefill_mfma"]["achieved_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+    if not args.no_cpu_baseline:
+        base, ref = cpu_baseline(ds, k0, v0)
+        line["cpu_baseline"] = base
+        got = ds.out.to(torch.float64).cpu().numpy()
+        m = ~np.isnan(ref)
+        err = np.abs(got[m] - ref[m])
+        line["check_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()), "elements": int(m.sum())}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -180,6 +180,26 @@ int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t* block_tabl
  * retire sequences that emitted max_new_tokens and free their blocks. */
 int fsf_sched_step_done(fsf_sched* s);
 
+/*
+ * Profiling aid (host state, not thread safe; off by default).  While enabled, every
+ * kernel the library launches is bracketed by a pair of HIP events on the caller's
+ * stream.  fsf_profile_read() waits for the recorded events, adds the elapsed
+ * milliseconds and launch counts per phase into ms_out[FSF_N_PHASES] /
+ * launches_out[FSF_N_PHASES] (host arrays, overwritten), and clears the record.
+ * Events are ordinary host-side HIP objects; no device memory is allocated.
+ */
+typedef enum {
+  FSF_PHASE_APPEND = 0,  /* fsf_kv_append kernel                                  */
+  FSF_PHASE_PLAN = 1,    /* work planning (prefix sums over the descriptors)      */
+  FSF_PHASE_PREFILL = 2, /* prompt-chunk attention (matrix cores)                 */
+  FSF_PHASE_DECODE = 3,  /* generation-row split-KV attention                     */
+  FSF_PHASE_MERGE = 4,   /* merge of split partial results                        */
+  FSF_PHASE_GENERIC = 5, /* generic fp32 attention kernel                         */
+  FSF_N_PHASES = 6
+} fsf_phase;
+int fsf_profile_enable(int on);
+int fsf_profile_read(double* ms_out, int64_t* launches_out);
+
 /* Introspection (host): free blocks, live sequences (waiting prompts + generations). */
 int64_t fsf_sched_free_blocks(const fsf_sched* s);
 int32_t fsf_sched_live_seqs(const fsf_sched* s);

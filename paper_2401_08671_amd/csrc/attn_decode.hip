@@ -217,6 +217,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(Pass p, FastPlan f, con
 hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                               const void* v_cache, void* out, hipStream_t stream) {
   if (f.n_dec_items == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_DECODE, stream);
   const unsigned grid = (unsigned)f.n_dec_items * p.n_kv_heads;
   if (p.dtype == FSF_BF16)
     attn_decode_kernel<FSF_BF16, bf16_t><<<grid, 64, 0, stream>>>(

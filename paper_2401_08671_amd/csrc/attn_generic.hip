@@ -110,6 +110,7 @@ hipError_t launch_attn_generic(const Pass& p, const void* q, const void* k_cache
                                const void* v_cache, void* out, hipStream_t stream) {
   const int64_t n_items = (int64_t)p.n_tokens * p.n_q_heads;
   if (n_items == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_GENERIC, stream);
   const unsigned grid = (unsigned)((n_items + kWaves - 1) / kWaves);
   switch (p.dtype) {
     case FSF_F32:

@@ -92,11 +92,13 @@ __global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __rest
 }  // namespace
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream) {
+  PhaseTimer timer(FSF_PHASE_PLAN, stream);
   plan_kernel<<<1, kPlanThreads, 0, stream>>>(p, f);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream) {
+  PhaseTimer timer(FSF_PHASE_MERGE, stream);
   const unsigned grid = (unsigned)p.n_seqs * p.n_q_heads;
   if (p.dtype == FSF_BF16)
     merge_kernel<bf16_t><<<grid, 64, 0, stream>>>(p, f, (bf16_t*)out);

@@ -294,6 +294,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(Pass p, FastPlan f,
 hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                                const void* v_cache, void* out, hipStream_t stream) {
   if (f.n_pre_tiles == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_PREFILL, stream);
   const unsigned grid = (unsigned)f.n_pre_tiles * p.n_q_heads;
   if (p.dtype == FSF_BF16)
     attn_prefill_kernel<FSF_BF16, bf16_t><<<grid, 256, 0, stream>>>(

@@ -81,6 +81,16 @@ hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStr
 hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                                const void* v_cache, void* out, hipStream_t stream);
 
+// Optional per-kernel timing (see fsf_profile_enable): brackets a launch with HIP events.
+struct PhaseTimer {
+  PhaseTimer(int phase, hipStream_t stream);
+  ~PhaseTimer();
+  int phase_;
+  hipStream_t stream_;
+  hipEvent_t start_;
+  bool on_;
+};
+
 hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
                             void* v_cache, hipStream_t stream);
 

@@ -45,6 +45,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(Pass p, const Unit* __re
 hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
                             void* v_cache, hipStream_t stream) {
   if (p.n_tokens == 0 || p.n_seqs == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_APPEND, stream);
   const int esize = p.dtype == FSF_F32 ? 4 : 2;
   const int head_bytes = p.head_dim * esize;
   if (head_bytes % 16 == 0) {

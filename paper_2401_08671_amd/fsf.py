@@ -196,3 +196,25 @@ class Scheduler:
             self.close()
         except Exception:
             pass
+
+
+# ------------------------------------------------------------------ per-kernel timing aid
+PHASES = ("append", "plan", "prefill", "decode", "merge", "generic")
+
+
+def profile_enable(on: bool) -> None:
+    L = lib()
+    L.fsf_profile_enable.restype = C.c_int
+    L.fsf_profile_enable.argtypes = [C.c_int]
+    _check(L.fsf_profile_enable(1 if on else 0), "fsf_profile_enable")
+
+
+def profile_read():
+    """{phase: (total_ms, launches)} since the last read; waits for the recorded events."""
+    L = lib()
+    L.fsf_profile_read.restype = C.c_int
+    L.fsf_profile_read.argtypes = [C.c_void_p, C.c_void_p]
+    ms = (C.c_double * len(PHASES))()
+    n = (C.c_int64 * len(PHASES))()
+    _check(L.fsf_profile_read(C.cast(ms, C.c_void_p), C.cast(n, C.c_void_p)), "fsf_profile_read")
+    return {name: (ms[i], n[i]) for i, name in enumerate(PHASES)}
