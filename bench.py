@@ -169,11 +169,13 @@ def main():
     phase_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
     dec_ms = phase_ms["decode"]
     achieved = work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms > 0 else 0.0
+    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"decode_traffic_cfg{args.config}.json")
+    tpath = os.path.join(ROOT, "profiles", f"bench_cfg{args.config}_hbm_traffic.md")
     if os.path.exists(tpath):
-        with open(tpath) as fh:
-            traffic = json.load(fh).get("hbm_bytes_per_launch")
+        for ln in open(tpath):
+            if ln.startswith("hbm_bytes_per_launch:"):
+                traffic = float(ln.split(":")[1])
     line = {
         "metric": "ragged SplitFuse attn tokens/s per step + % HBM/MFMA roofline, 1 GPU",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
