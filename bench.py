@@ -131,7 +131,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 6])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -167,8 +167,12 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = spec.n_tokens / (ms_per_step * 1e-3)
     phase_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
-    dec_ms = phase_ms["decode"]
-    achieved = work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms > 0 else 0.0
+    dec_ms, pre_ms = phase_ms["decode"], phase_ms["prefill"]
+    hbm_bound = dec_ms >= pre_ms          # which kernel dominates this batch
+    if hbm_bound:
+        achieved = work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms > 0 else 0.0
+    else:
+        achieved = work["prefill_flops"] / (pre_ms * 1e-3) / 1e12
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"bench_cfg{args.config}_hbm_traffic.md")
@@ -186,9 +190,12 @@ def main():
                                f"({sum(1 for n, _ in spec.seqs if n > 1)} prompt chunks, "
                                f"{sum(1 for n, _ in spec.seqs if n == 1)} generation rows), one layer",
                    "n_seqs": spec.n_seqs, "n_tokens": spec.n_tokens, "kv_pool_blocks": ds.num_blocks},
-        "roofline": {"bound": "hbm", "kernel": "attn_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": work["decode_bytes"], "avg_launch_ms": dec_ms},
+        "roofline": ({"bound": "hbm", "kernel": "attn_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                      "algorithmic_bytes_per_launch": work["decode_bytes"], "avg_launch_ms": dec_ms} if hbm_bound else
+                     {"bound": "mfma", "kernel": "attn_prefill_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                      "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                      "algorithmic_flops_per_launch": work["prefill_flops"], "avg_launch_ms": pre_ms}),
         "phases_ms": phase_ms,
         "step_roofline": {"algorithmic_bytes": work["total_bytes"],
                           "achieved_GBs": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9,

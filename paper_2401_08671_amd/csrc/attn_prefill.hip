@@ -31,6 +31,7 @@ namespace {
 
 constexpr int NQ = kPrefillTileM / 128;  // 32-row q-tiles per wave
 constexpr int kKeysPerStep = 64;
+constexpr float kLazyLog2 = 8.f;  // running-max slack before accumulators are rescaled
 
 struct Prefetch {
   frag8 k[4];
@@ -101,7 +102,7 @@ __device__ __forceinline__ void store_step(const Prefetch& pf, char* k_lds, char
 }
 
 template <int DT, typename T>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(Pass p, FastPlan f,
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f,
                                                            const T* __restrict__ q,
                                                            const T* __restrict__ kc,
                                                            const T* __restrict__ vc,
@@ -231,23 +232,33 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(Pass p, FastPlan f,
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kt][qt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[qt], mx * sl2);
-      const float corr = fast_exp2(m_run[qt] - m_new);
-      m_run[qt] = m_new;
+      // Lazy rescale: the running reference m_run only has to bound the scores from above
+      // loosely.  It is raised (and acc, l rescaled) only when a row's maximum outgrows it by
+      // more than 2^kLazyLog2, so probabilities stay <= 2^kLazyLog2 and the rescale of the
+      // 64 accumulator registers per q-tile leaves the steady-state loop.
+      const float m_cand = fmaxf(m_run[qt], mx * sl2);
+      const bool raise = m_cand - m_run[qt] > kLazyLog2;
+      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        const float m_new = raise ? m_cand : m_run[qt];
+        const float corr = fast_exp2(m_run[qt] - m_new);
+        m_run[qt] = m_new;
+        l_run[qt] *= corr;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[mt][qt][r] *= corr;
+      }
+      const float m_ref = m_run[qt];
       float sum = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float pr = fast_exp2(fmaf(sc[kt][qt][r], sl2, -m_new));
+          const float pr = fast_exp2(fmaf(sc[kt][qt][r], sl2, -m_ref));
           sc[kt][qt][r] = pr;
           sum += pr;
         }
-      l_run[qt] = l_run[qt] * corr + sum;
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][qt][r] *= corr;
+      l_run[qt] += sum;
       // k-step u of the second product covers keys 16u..16u+15: registers 8(u%2)..+7 of tile u/2
 #pragma unroll
       for (int u = 0; u < 4; ++u)

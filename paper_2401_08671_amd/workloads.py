@@ -80,7 +80,10 @@ def config(k: int, n_decodes: int | None = None) -> BatchSpec:
         c = rng.integers(512, 2049, size=nd)
         return BatchSpec("cfg4-llama2-70b-share", 64, 8, 128, 64, "bf16",
                          [(1, int(x)) for x in c] + [(64, 3000)], seed=seed)
-    raise ValueError("config index must be 1..4 (config 5 is a request stream, see stream_requests)")
+    if k == 6:
+        # the heaviest kind of step of the long-prompt stream: a full-budget chunk deep into a long prompt
+        return BatchSpec("cfg5-step-13b-chunk4096-at-8192", 40, 40, 128, 64, "bf16", [(4096, 8192)], seed=seed)
+    raise ValueError("config index must be 1..4 or 6 (config 5 is a request stream, see stream_requests)")
 
 
 def stream_shape() -> dict:
