@@ -31,6 +31,10 @@ namespace {
 
 constexpr int NQ = kPrefillTileM / 128;  // 32-row q-tiles per wave
 constexpr int kKeysPerStep = 64;
+constexpr int kKTileBytes = 64 * 256;            // K tile [64 keys][128 d]
+constexpr int kStageBytes = kKTileBytes + 128 * 128;  // + V^T tile [128 d][64 keys]
+constexpr int kFragAhead = 4;                     // K fragments in flight from LDS (k-steps)
+constexpr int kVAhead = 4;                        // V^T fragments in flight from LDS
 constexpr float kLazyLog2 = 8.f;  // running-max slack before accumulators are rescaled
 
 struct Prefetch {
@@ -108,8 +112,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
                                                            const T* __restrict__ vc,
                                                            T* __restrict__ out) {
   using M = Mma<DT>;
-  __shared__ __attribute__((aligned(16))) char k_lds[64 * 256];
-  __shared__ __attribute__((aligned(16))) char vt_lds[128 * 128];
+  __shared__ __attribute__((aligned(16))) char lds[2 * kStageBytes];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -179,20 +182,28 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
   }
   const float sl2 = p.scale * 1.4426950408889634f;
 
+  // Two LDS stages: while step j is computed from stage j&1, step j+1 sits in registers on its
+  // way to stage (j+1)&1 and step j+2 is in flight from HBM/L2.  One barrier per step.
   Prefetch pre;
   prefetch_step(pre, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, tid, kv_last);
+  store_step(pre, lds, lds + kKTileBytes, tid);
+  if (key_begin + kKeysPerStep <= hi_t)
+    prefetch_step(pre, kc, vc, bt, key_begin + kKeysPerStep, B, p.n_kv_heads, hk, tid, kv_last);
 
-  for (int key0 = key_begin; key0 <= hi_t; key0 += kKeysPerStep) {
-    __syncthreads();  // everyone finished reading the previous tiles
-    store_step(pre, k_lds, vt_lds, tid);
-    __syncthreads();
-    if (key0 + kKeysPerStep <= hi_t)
-      prefetch_step(pre, kc, vc, bt, key0 + kKeysPerStep, B, p.n_kv_heads, hk, tid, kv_last);
-
+  int stage = 0;
+  for (int key0 = key_begin; key0 <= hi_t; key0 += kKeysPerStep, stage ^= 1) {
+    __syncthreads();  // stage `stage` is complete; everyone is done reading stage^1
+    if (key0 + kKeysPerStep <= hi_t) {
+      store_step(pre, lds + (stage ^ 1) * kStageBytes, lds + (stage ^ 1) * kStageBytes + kKTileBytes, tid);
+      if (key0 + 2 * kKeysPerStep <= hi_t)
+        prefetch_step(pre, kc, vc, bt, key0 + 2 * kKeysPerStep, B, p.n_kv_heads, hk, tid, kv_last);
+    }
     // hidden from every row of this wave?
     if (!wave_live || key0 > w_hi_max || key0 + kKeysPerStep - 1 < w_lo_min) continue;
+    const char* kl = lds + stage * kStageBytes;
+    const char* vl = kl + kKTileBytes;
 
-    // ---- S^T = K . Q^T
+    // ---- S^T = K . Q^T ; K fragments are fetched from LDS kFragAhead k-steps ahead of their use
     f32x16_t sc[2][NQ];
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
@@ -200,22 +211,39 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
       for (int qt = 0; qt < NQ; ++qt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc[kt][qt][r] = 0.f;
+    {
+      frag8 kf[kFragAhead][2];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+      for (int t = 0; t < kFragAhead; ++t)
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        const frag8 a = load_frag8(k_lds + k_lds_off(kt * 32 + l32, 2 * t + hg));
+        for (int kt = 0; kt < 2; ++kt) kf[t][kt] = load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * t + hg));
 #pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) sc[kt][qt] = M::mfma32(a, qf[qt][t], sc[kt][qt]);
+      for (int t = 0; t < 8; ++t) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+          for (int qt = 0; qt < NQ; ++qt)
+            sc[kt][qt] = M::mfma32(kf[t % kFragAhead][kt], qf[qt][t], sc[kt][qt]);
+          if (t + kFragAhead < 8)
+            kf[t % kFragAhead][kt] = load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * (t + kFragAhead) + hg));
+        }
       }
+      // pin the issue order: kFragAhead k-steps of LDS reads up front, then reads and MFMAs in turn
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragAhead, 0);
+#pragma unroll
+      for (int t = 0; t < 8 - kFragAhead; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ * kFragAhead, 0);
     }
 
-    // ---- mask + running softmax; P^T fragments
+
+    // ---- mask, row maxima, and the (rare) raise of the running reference
     const bool need_mask = key0 + kKeysPerStep - 1 > w_hi_min || key0 < w_lo_max || w_i1 - w_i0 < 32 * NQ;
-    frag8 pfr[NQ][4];
+    if (need_mask) {
 #pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      if (need_mask) {
+      for (int qt = 0; qt < NQ; ++qt) {
         int rlo, rhi;
         visible_range(row_pos[qt], p.window, rlo, rhi);  // dead rows: rhi = -1, nothing visible
 #pragma unroll
@@ -226,20 +254,28 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
             if (key < rlo || key > rhi) sc[kt][qt][r] = -INFINITY;
           }
       }
+    }
+    // Lazy rescale: the running reference m_run only has to bound the scores from above
+    // loosely.  It is raised (and acc, l rescaled) only when a row's maximum outgrows it by
+    // more than 2^kLazyLog2, so probabilities stay <= 2^kLazyLog2 and the rescale of the
+    // accumulator registers leaves the steady-state loop.
+    float m_cand[NQ];
+    bool raise = false;
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt) {
       float mx = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kt][qt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // Lazy rescale: the running reference m_run only has to bound the scores from above
-      // loosely.  It is raised (and acc, l rescaled) only when a row's maximum outgrows it by
-      // more than 2^kLazyLog2, so probabilities stay <= 2^kLazyLog2 and the rescale of the
-      // 64 accumulator registers per q-tile leaves the steady-state loop.
-      const float m_cand = fmaxf(m_run[qt], mx * sl2);
-      const bool raise = m_cand - m_run[qt] > kLazyLog2;
-      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-        const float m_new = raise ? m_cand : m_run[qt];
+      m_cand[qt] = fmaxf(m_run[qt], mx * sl2);
+      raise |= m_cand[qt] - m_run[qt] > kLazyLog2;
+    }
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+#pragma unroll
+      for (int qt = 0; qt < NQ; ++qt) {
+        const float m_new = (m_cand[qt] - m_run[qt] > kLazyLog2) ? m_cand[qt] : m_run[qt];
         const float corr = fast_exp2(m_run[qt] - m_new);
         m_run[qt] = m_new;
         l_run[qt] *= corr;
@@ -248,6 +284,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[mt][qt][r] *= corr;
       }
+    }
+
+    // ---- probabilities and P^T fragments
+    frag8 pfr[NQ][4];
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt) {
       const float m_ref = m_run[qt];
       float sum = 0.f;
 #pragma unroll
@@ -267,16 +309,25 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
           pfr[qt][u].w[jj] = M::pack2(sc[u >> 1][qt][8 * (u & 1) + 2 * jj], sc[u >> 1][qt][8 * (u & 1) + 2 * jj + 1]);
     }
 
-    // ---- O^T += V^T . P^T
+    // ---- O^T += V^T . P^T ; V^T fragments come from LDS kVAhead MFMAs ahead of their use
+    frag8 vf[kVAhead];  // rolling window over i = u*4 + mt
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int i = 0; i < kVAhead; ++i) vf[i] = load_frag8(vl + vt_lds_off((i & 3) * 32 + l32, 2 * (i >> 2) + hg));
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const frag8 a = load_frag8(vt_lds + vt_lds_off(mt * 32 + l32, 2 * u + hg));
+    for (int i = 0; i < 16; ++i) {
+      const int u = i >> 2, mt = i & 3;
 #pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) acc[mt][qt] = M::mfma32(a, pfr[qt][u], acc[mt][qt]);
-      }
+      for (int qt = 0; qt < NQ; ++qt) acc[mt][qt] = M::mfma32(vf[i % kVAhead], pfr[qt][u], acc[mt][qt]);
+      if (i + kVAhead < 16)
+        vf[i % kVAhead] = load_frag8(vl + vt_lds_off(((i + kVAhead) & 3) * 32 + l32, 2 * ((i + kVAhead) >> 2) + hg));
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, kVAhead, 1);
+#pragma unroll
+    for (int i = 0; i < 16 - kVAhead; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, NQ, 1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, NQ * kVAhead, 1);
   }
 
   // ---- normalise and store: acc[mt][qt][r] is column d = 32mt + 8(r/4) + 4hg + r%4 of the lane's row
