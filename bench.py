@@ -113,19 +113,39 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = spec.n_tokens / (ms_per_step * 1e-3)
     phase_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
-    dec_ms, pre_ms = phase_ms["decode"], phase_ms["prefill"]
-    hbm_bound = dec_ms >= pre_ms          # which kernel dominates this batch
-    if hbm_bound:
-        achieved = work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms > 0 else 0.0
-    else:
-        achieved = work["prefill_flops"] / (pre_ms * 1e-3) / 1e12
-    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary
+
+    # per-kind timings: the same pass with prompt-chunk and generation-row work as two kernels
+    fsf.profile_enable(True)
+    for _ in range(max(3, args.steps // 5)):
+        ds.step(separate=True)
+    torch.cuda.synchronize()
+    sep = fsf.profile_read()
+    fsf.profile_enable(False)
+    sep_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in sep.items()}
+
+    # Dominant kernel of the timed region: the fused attention launch.  Its bound is whichever
+    # of (algorithmic bytes / HBM peak) and (algorithmic flops / MFMA peak) takes longer.
+    att_ms = phase_ms["fused"]
+    att_bytes = work["decode_bytes"] + work["prefill_bytes"]
+    att_flops = work["decode_flops"] + work["prefill_flops"]
+    hbm_bound = att_bytes / (HBM_PEAK_GBS * 1e9) >= att_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"bench_cfg{args.config}_hbm_traffic.md")
     if os.path.exists(tpath):
         for ln in open(tpath):
             if ln.startswith("hbm_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
+    if hbm_bound:
+        achieved = att_bytes / (att_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "attn_fused_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "algorithmic_bytes_per_launch": att_bytes, "avg_launch_ms": att_ms}
+    else:
+        achieved = att_flops / (att_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "attn_fused_kernel", "achieved": achieved,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": traffic, "algorithmic_flops_per_launch": att_flops, "avg_launch_ms": att_ms}
+    dec_ms, pre_ms = sep_ms["decode"], sep_ms["prefill"]
     line = {
         "metric": "ragged SplitFuse attn tokens/s per step + % HBM/MFMA roofline, 1 GPU",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -136,21 +156,20 @@ def main():
                                f"({sum(1 for n, _ in spec.seqs if n > 1)} prompt chunks, "
                                f"{sum(1 for n, _ in spec.seqs if n == 1)} generation rows), one layer",
                    "n_seqs": spec.n_seqs, "n_tokens": spec.n_tokens, "kv_pool_blocks": ds.num_blocks},
-        "roofline": ({"bound": "hbm", "kernel": "attn_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                      "algorithmic_bytes_per_launch": work["decode_bytes"], "avg_launch_ms": dec_ms} if hbm_bound else
-                     {"bound": "mfma", "kernel": "attn_prefill_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                      "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
-                      "algorithmic_flops_per_launch": work["prefill_flops"], "avg_launch_ms": pre_ms}),
+        "roofline": roofline,
         "phases_ms": phase_ms,
         "step_roofline": {"algorithmic_bytes": work["total_bytes"],
                           "achieved_GBs": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9,
                           "frac_hbm": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "prefill_mfma": {"algorithmic_flops": work["prefill_flops"],
-                         "achieved_TFLOPs": (work["prefill_flops"] / (phase_ms["prefill"] * 1e-3) / 1e12) if phase_ms["prefill"] else 0.0,
-                         "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS},
+        "separate_kernels": {
+            "phases_ms": sep_ms,
+            "decode_only": {"bytes": work["decode_bytes"], "ms": dec_ms,
+                            "GBs": work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms else 0.0,
+                            "frac_hbm": work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if dec_ms else 0.0},
+            "prefill_only": {"flops": work["prefill_flops"], "ms": pre_ms,
+                             "TFLOPs": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 if pre_ms else 0.0,
+                             "frac_mfma": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if pre_ms else 0.0}},
     }
-    line["prefill_mfma"]["frac"] = line["prefill_mfma"]["achieved_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(ds, k0, v0)
         line["cpu_baseline"] = base

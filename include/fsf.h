@@ -58,7 +58,9 @@ typedef enum {
 typedef enum { FSF_F32 = 0, FSF_BF16 = 1, FSF_F16 = 2 } fsf_dtype;
 
 /* fsf_attn_cfg.flags */
-#define FSF_FLAG_FORCE_GENERIC 1 /* run the generic fp32 kernel even where a fast path exists */
+#define FSF_FLAG_FORCE_GENERIC 1    /* run the generic fp32 kernel even where a fast path exists     */
+#define FSF_FLAG_SEPARATE_KERNELS 2 /* matrix-core path: launch prompt-chunk and generation-row work  */
+                                    /* as two kernels instead of one fused launch (for profiling)     */
 
 /* One sequence of the pass (paper Sec. 2: tokens processed now vs tokens in the cache). */
 typedef struct {
@@ -195,7 +197,8 @@ typedef enum {
   FSF_PHASE_DECODE = 3,  /* generation-row split-KV attention                     */
   FSF_PHASE_MERGE = 4,   /* merge of split partial results                        */
   FSF_PHASE_GENERIC = 5, /* generic fp32 attention kernel                         */
-  FSF_N_PHASES = 6
+  FSF_PHASE_FUSED = 6,   /* prompt-chunk + generation-row attention in one launch  */
+  FSF_N_PHASES = 7
 } fsf_phase;
 int fsf_profile_enable(int on);
 int fsf_profile_read(double* ms_out, int64_t* launches_out);

@@ -1,4 +1,4 @@
-// Generation rows (n_new == 1): split-KV attention streaming the blocked cache once.
+// Device code for generation rows (n_new == 1): split-KV attention streaming the blocked cache once.
 //
 // A generation pass adds one token and attends to the whole cached history (paper Sec. 2),
 // so every visible K/V byte is used exactly once per KV head: the kernel is bound by HBM
@@ -20,6 +20,8 @@
 // Loads for the next step are issued before the current step is computed (two register
 // buffers).  Rows outside [lo, hi] are masked with selects, never multiplied: stale or
 // poisoned cache slots cannot leak; V rows of masked keys are zeroed.
+#pragma once
+
 #include <math.h>
 
 #include "fsf_internal.h"
@@ -27,7 +29,6 @@
 #include "numeric.h"
 
 namespace fsf {
-namespace {
 
 struct StepBuf {
   frag8 k[2][4];  // [tile][k-step]: K[key = tile*16 + n][d = (4t + kg)*8 ..+8]
@@ -116,34 +117,26 @@ __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f
   }
 }
 
+// One wavefront: unit = item * n_kv_heads + kv head (item = a sequence's run of cache blocks).
 template <int DT, typename T>
-__global__ __launch_bounds__(64) void attn_decode_kernel(Pass p, FastPlan f, const T* __restrict__ q,
-                                                         const T* __restrict__ kc,
-                                                         const T* __restrict__ vc,
-                                                         T* __restrict__ out) {
-  const int lane = threadIdx.x;
+__device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
+                                            const T* __restrict__ kc, const T* __restrict__ vc,
+                                            T* __restrict__ out, int unit, int lane) {
   const int n = lane & 15, kg = lane >> 4;
-  const int item = blockIdx.x / p.n_kv_heads;
-  const int hk = blockIdx.x - item * p.n_kv_heads;
-  // sequence owning this item: largest s with dec_item_start[s] <= item
-  int s;
-  {
-    int a = 0, b = p.n_seqs - 1;
-    while (a < b) {
-      const int mid = (a + b + 1) >> 1;
-      if (f.dec_item_start[mid] <= item) a = mid; else b = mid - 1;
-    }
-    s = a;
-  }
+  const int item = unit / p.n_kv_heads;
+  const int hk = unit - item * p.n_kv_heads;
+  const int s = f.dec_item_seq[item];  // written by the planning kernel
   const int split = item - f.dec_item_start[s];
   const fsf_seq_desc sd = p.descs[s];
   const int B = p.block_size;
   int lo, hi;
   visible_range(sd.n_cached, p.window, lo, hi);
   const int b_lo = lo / B, b_hi = hi / B;
-  const int n_splits = (b_hi - b_lo + f.split_blocks) / f.split_blocks;
-  const int blk0 = b_lo + split * f.split_blocks;
-  const int blk1 = min(blk0 + f.split_blocks - 1, b_hi);
+  const int nblk = b_hi - b_lo + 1;
+  const int n_splits = (nblk + f.split_blocks - 1) / f.split_blocks;
+  // even cut: split k owns blocks [k*nblk/n_splits, (k+1)*nblk/n_splits), never empty
+  const int blk0 = b_lo + (int)((int64_t)split * nblk / n_splits);
+  const int blk1 = b_lo + (int)((int64_t)(split + 1) * nblk / n_splits) - 1;
   const int key_begin = max(blk0 * B, lo & ~31);
   const int key_end = min((blk1 + 1) * B - 1, hi);  // inclusive
   const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
@@ -212,20 +205,5 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(Pass p, FastPlan f, con
   }
 }
 
-}  // namespace
-
-hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
-                              const void* v_cache, void* out, hipStream_t stream) {
-  if (f.n_dec_items == 0) return hipSuccess;
-  PhaseTimer timer(FSF_PHASE_DECODE, stream);
-  const unsigned grid = (unsigned)f.n_dec_items * p.n_kv_heads;
-  if (p.dtype == FSF_BF16)
-    attn_decode_kernel<FSF_BF16, bf16_t><<<grid, 64, 0, stream>>>(
-        p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out);
-  else
-    attn_decode_kernel<FSF_F16, f16_t><<<grid, 64, 0, stream>>>(
-        p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
-  return hipGetLastError();
-}
 
 }  // namespace fsf

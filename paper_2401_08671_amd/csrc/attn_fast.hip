@@ -1,0 +1,127 @@
+// Kernels of the matrix-core attention path and their launchers.
+//
+// A Dynamic SplitFuse pass mixes prompt chunks (dense, matrix-core bound) with one-token
+// generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  The two
+// kinds of work stress different parts of the chip, so the default launch puts both in
+// ONE grid: the first workgroups take prompt-chunk tiles, the rest take four
+// generation-row units each (one per wave), and the hardware overlaps them.  Separate
+// kernels for each kind exist for profiling.
+#include "attn_decode_body.h"
+#include "attn_prefill_body.h"
+
+namespace fsf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnitsPerGroup = kThreads / 64;  // generation-row units (waves) per workgroup
+
+// Prefill workgroups are numbered so that the tiles with the most keys to visit (the last
+// rows of a chunk) start first.
+__device__ __forceinline__ void prefill_block_to_work(const Pass& p, const FastPlan& f, int block,
+                                                      int& tile, int& hq) {
+  const int t = block / p.n_q_heads;
+  hq = block - t * p.n_q_heads;
+  tile = f.n_pre_tiles - 1 - t;
+}
+
+template <int DT, typename T>
+__global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastPlan f,
+                                                                 const T* __restrict__ q,
+                                                                 const T* __restrict__ kc,
+                                                                 const T* __restrict__ vc,
+                                                                 T* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) char lds[kPrefillLdsBytes];
+  int tile, hq;
+  prefill_block_to_work(p, f, blockIdx.x, tile, hq);
+  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, lds);
+}
+
+template <int DT, typename T>
+__global__ __launch_bounds__(kThreads, 2) void attn_decode_kernel(Pass p, FastPlan f,
+                                                                const T* __restrict__ q,
+                                                                const T* __restrict__ kc,
+                                                                const T* __restrict__ vc,
+                                                                T* __restrict__ out) {
+  const int unit = blockIdx.x * kUnitsPerGroup + (threadIdx.x >> 6);
+  if (unit >= f.n_dec_items * p.n_kv_heads) return;
+  decode_unit<DT, T>(p, f, q, kc, vc, out, unit, threadIdx.x & 63);
+}
+
+template <int DT, typename T>
+__global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPlan f,
+                                                               const T* __restrict__ q,
+                                                               const T* __restrict__ kc,
+                                                               const T* __restrict__ vc,
+                                                               T* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) char lds[kPrefillLdsBytes];
+  // Workgroup numbering alternates the two kinds of work for as long as both last, so that a
+  // compute unit tends to hold one matrix-core-bound and one HBM-bound workgroup at a time.
+  const int n_pre = f.n_pre_tiles * p.n_q_heads;
+  const int n_dec = (f.n_dec_items * p.n_kv_heads + kUnitsPerGroup - 1) / kUnitsPerGroup;
+  const int n_mix = min(n_pre, n_dec);
+  const int b = blockIdx.x;
+  bool is_prefill;
+  int idx;
+  if (b < 2 * n_mix) {
+    is_prefill = (b & 1) == 0;
+    idx = b >> 1;
+  } else {
+    is_prefill = n_pre > n_dec;
+    idx = b - n_mix;
+  }
+  if (is_prefill) {  // uniform per workgroup
+    int tile, hq;
+    prefill_block_to_work(p, f, idx, tile, hq);
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, lds);
+  } else {
+    const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
+    if (unit >= f.n_dec_items * p.n_kv_heads) return;
+    decode_unit<DT, T>(p, f, q, kc, vc, out, unit, threadIdx.x & 63);
+  }
+}
+
+unsigned decode_groups(const Pass& p, const FastPlan& f) {
+  const int64_t units = (int64_t)f.n_dec_items * p.n_kv_heads;
+  return (unsigned)((units + kUnitsPerGroup - 1) / kUnitsPerGroup);
+}
+
+}  // namespace
+
+#define FSF_LAUNCH(KERNEL, GRID)                                                                   \
+  if (p.dtype == FSF_BF16)                                                                         \
+    KERNEL<FSF_BF16, bf16_t><<<GRID, kThreads, 0, stream>>>(                                       \
+        p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out);     \
+  else                                                                                             \
+    KERNEL<FSF_F16, f16_t><<<GRID, kThreads, 0, stream>>>(                                         \
+        p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
+
+hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                               const void* v_cache, void* out, hipStream_t stream) {
+  if (f.n_pre_tiles == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_PREFILL, stream);
+  const unsigned grid = (unsigned)f.n_pre_tiles * p.n_q_heads;
+  FSF_LAUNCH(attn_prefill_kernel, grid)
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, hipStream_t stream) {
+  if (f.n_dec_items == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_DECODE, stream);
+  const unsigned grid = decode_groups(p, f);
+  FSF_LAUNCH(attn_decode_kernel, grid)
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                             const void* v_cache, void* out, hipStream_t stream) {
+  const unsigned grid = (unsigned)f.n_pre_tiles * p.n_q_heads + decode_groups(p, f);
+  if (grid == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_FUSED, stream);
+  FSF_LAUNCH(attn_fused_kernel, grid)
+  return hipGetLastError();
+}
+
+#undef FSF_LAUNCH
+
+}  // namespace fsf

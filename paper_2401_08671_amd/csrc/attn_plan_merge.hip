@@ -2,8 +2,9 @@
 //
 // A pass mixes one-row generations with prompt chunks of any length (paper Sec. 3.2), so
 // work per sequence is ragged.  plan_kernel turns the descriptors into two exclusive
-// prefix arrays (decode items, prefill tiles) that let every workgroup of the compute
-// kernels find its sequence with a binary search; no host-to-device copy is needed.
+// prefix arrays (decode items, prefill tiles) plus item->sequence and tile->sequence
+// tables, so every wave of the compute kernels finds its work with one load; no
+// host-to-device copy is needed.
 //
 // merge_kernel combines the partial results of a generation row whose visible keys were
 // split across several workgroups: with per-split running maximum m_k (log2 domain),
@@ -53,6 +54,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
     f.pre_tile_start[s] = pre_run;
     int d, t;
     seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, d, t);
+    for (int k = 0; k < d; ++k) f.dec_item_seq[dec_run + k] = s;
+    for (int k = 0; k < t; ++k) f.pre_tile_seq[pre_run + k] = s;
     dec_run += d;
     pre_run += t;
   }

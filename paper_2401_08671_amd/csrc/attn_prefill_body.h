@@ -1,4 +1,4 @@
-// Prompt chunks (n_new > 1): tiled matrix-core attention over the blocked cache.
+// Device code for prompt chunks (n_new > 1): tiled matrix-core attention over the blocked cache.
 //
 // A chunk of a split prompt attends causally to its own rows and to every chunk cached by
 // earlier passes (paper Sec. 3.2 rule 1; Sec. 2 prompt processing).  Work is dense
@@ -20,6 +20,8 @@
 //                                    no cross-lane movement)
 // Masking (causal diagonal, window edge, rows past the chunk end) uses selects on the
 // scores; wave-level tests skip steps that are entirely hidden from the wave's rows.
+#pragma once
+
 #include <math.h>
 
 #include "fsf_internal.h"
@@ -27,7 +29,6 @@
 #include "numeric.h"
 
 namespace fsf {
-namespace {
 
 constexpr int NQ = kPrefillTileM / 128;  // 32-row q-tiles per wave
 constexpr int kKeysPerStep = 64;
@@ -35,6 +36,7 @@ constexpr int kKTileBytes = 64 * 256;            // K tile [64 keys][128 d]
 constexpr int kStageBytes = kKTileBytes + 128 * 128;  // + V^T tile [128 d][64 keys]
 constexpr int kFragAhead = 4;                     // K fragments in flight from LDS (k-steps)
 constexpr int kVAhead = 4;                        // V^T fragments in flight from LDS
+constexpr int kPrefillLdsBytes = 2 * kStageBytes;
 constexpr float kLazyLog2 = 8.f;  // running-max slack before accumulators are rescaled
 
 struct Prefetch {
@@ -105,30 +107,18 @@ __device__ __forceinline__ void store_step(const Prefetch& pf, char* k_lds, char
   }
 }
 
+// One workgroup of 256 threads: tile = index into the pass's prefill tiles, hq = query head.
+// lds: kPrefillLdsBytes of workgroup-shared memory.
 template <int DT, typename T>
-__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f,
-                                                           const T* __restrict__ q,
-                                                           const T* __restrict__ kc,
-                                                           const T* __restrict__ vc,
-                                                           T* __restrict__ out) {
+__device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f, const T* __restrict__ q,
+                                             const T* __restrict__ kc, const T* __restrict__ vc,
+                                             T* __restrict__ out, int tile, int hq, char* lds) {
   using M = Mma<DT>;
-  __shared__ __attribute__((aligned(16))) char lds[2 * kStageBytes];
-
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, hg = lane >> 5;
-  const int tile = blockIdx.x / p.n_q_heads;
-  const int hq = blockIdx.x - tile * p.n_q_heads;
   const int hk = hq / p.group;
-  int s;
-  {
-    int a = 0, b = p.n_seqs - 1;
-    while (a < b) {
-      const int mid = (a + b + 1) >> 1;
-      if (f.pre_tile_start[mid] <= tile) a = mid; else b = mid - 1;
-    }
-    s = a;
-  }
+  const int s = f.pre_tile_seq[tile];  // written by the planning kernel
   const fsf_seq_desc sd = p.descs[s];
   const int B = p.block_size;
   const int n_new = sd.n_new, c = sd.n_cached;
@@ -351,20 +341,5 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(Pass p, FastPlan f
   }
 }
 
-}  // namespace
-
-hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
-                               const void* v_cache, void* out, hipStream_t stream) {
-  if (f.n_pre_tiles == 0) return hipSuccess;
-  PhaseTimer timer(FSF_PHASE_PREFILL, stream);
-  const unsigned grid = (unsigned)f.n_pre_tiles * p.n_q_heads;
-  if (p.dtype == FSF_BF16)
-    attn_prefill_kernel<FSF_BF16, bf16_t><<<grid, 256, 0, stream>>>(
-        p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out);
-  else
-    attn_prefill_kernel<FSF_F16, f16_t><<<grid, 256, 0, stream>>>(
-        p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
-  return hipGetLastError();
-}
 
 }  // namespace fsf

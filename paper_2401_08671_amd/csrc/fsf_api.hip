@@ -63,17 +63,22 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace sections of the matrix-core path, in order.
 struct WsLayout {
-  size_t dec_item_start, pre_tile_start, part_ml, part_acc, total;
+  size_t dec_item_start, pre_tile_start, dec_item_seq, pre_tile_seq, part_ml, part_acc, total;
 };
 
-WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs) {
+WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
   const size_t items_cap = (size_t)n_seqs + fsf::kMaxDecodeItemsExtra;
+  const size_t tiles_cap = (size_t)n_seqs + (size_t)n_tokens / fsf::kPrefillTileM;
   WsLayout w;
   size_t off = 0;
   w.dec_item_start = off;
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
   w.pre_tile_start = off;
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
+  w.dec_item_seq = off;
+  off += align256(items_cap * sizeof(int32_t));
+  w.pre_tile_seq = off;
+  off += align256(tiles_cap * sizeof(int32_t));
   w.part_ml = off;
   off += align256(items_cap * c->n_q_heads * 2 * sizeof(float));
   w.part_acc = off;
@@ -124,7 +129,7 @@ extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, 
                                                        int32_t n_tokens, int32_t max_blocks) {
   if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return 0;
   if (!fast_path_ok(cfg)) return 256;
-  return ws_layout(cfg, n_seqs).total;
+  return ws_layout(cfg, n_seqs, n_tokens).total;
 }
 
 extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
@@ -167,11 +172,13 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   int64_t sb = (dec_blocks + target_items - 1) / target_items;
   if (sb < min_split) sb = min_split;
 
-  const WsLayout w = ws_layout(cfg, n_seqs);
+  const WsLayout w = ws_layout(cfg, n_seqs, n_tokens);
   char* ws = (char*)workspace;
   fsf::FastPlan f;
   f.dec_item_start = (int32_t*)(ws + w.dec_item_start);
   f.pre_tile_start = (int32_t*)(ws + w.pre_tile_start);
+  f.dec_item_seq = (int32_t*)(ws + w.dec_item_seq);
+  f.pre_tile_seq = (int32_t*)(ws + w.pre_tile_seq);
   f.part_ml = (float*)(ws + w.part_ml);
   f.part_acc = (float*)(ws + w.part_acc);
   f.split_blocks = (int32_t)sb;
@@ -190,8 +197,12 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.n_pre_tiles = (int32_t)n_pre;
 
   hipError_t e = fsf::launch_plan(p, f, stream);
-  if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
-  if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
+  if (cfg->flags & FSF_FLAG_SEPARATE_KERNELS) {
+    if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
+    if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
+  } else {
+    if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
+  }
   if (e == hipSuccess && any_split) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }

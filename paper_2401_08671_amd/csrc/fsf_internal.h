@@ -68,6 +68,8 @@ __host__ __device__ inline void seq_work(int n_new, int n_cached, int window, in
 struct FastPlan {
   int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of decode items per sequence
   int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
+  int32_t* dec_item_seq;    // [items]  sequence index of every decode item
+  int32_t* pre_tile_seq;    // [tiles]  sequence index of every prefill tile
   float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
   float* part_acc;          // [items, n_q_heads, 128] unnormalised outputs per split
   int32_t split_blocks;
@@ -80,6 +82,9 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
 hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream);
 hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                                const void* v_cache, void* out, hipStream_t stream);
+// prompt-chunk tiles and generation-row items in ONE launch, so the two kinds of work overlap
+hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
+                             const void* v_cache, void* out, hipStream_t stream);
 
 // Optional per-kernel timing (see fsf_profile_enable): brackets a launch with HIP events.
 struct PhaseTimer {

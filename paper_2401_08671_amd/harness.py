@@ -61,8 +61,12 @@ class DeviceStep:
         wl.fill_pool_(self.v_cache, spec.value_mult, spec.seed * 7 + 5)
         self.out = torch.zeros((T, Hq, d), dtype=tdt, device=device)
         self.cfg = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window, scale=spec.scale)
+        # same pass with prompt-chunk and generation-row work launched as two kernels (for per-kind timings)
+        self.cfg_separate = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window,
+                                         scale=spec.scale, flags=fsf.FSF_FLAG_SEPARATE_KERNELS)
         self.ws = fsf.alloc_workspace(self.cfg, self.batch.n_seqs, self.batch.n_tokens, self.batch.max_blocks, device)
 
-    def step(self):
-        fsf.kv_append(self.cfg, self.k_new, self.v_new, self.k_cache, self.v_cache, self.batch)
-        fsf.ragged_attention(self.cfg, self.q, self.k_cache, self.v_cache, self.batch, self.out, self.ws)
+    def step(self, separate: bool = False):
+        cfg = self.cfg_separate if separate else self.cfg
+        fsf.kv_append(cfg, self.k_new, self.v_new, self.k_cache, self.v_cache, self.batch)
+        fsf.ragged_attention(cfg, self.q, self.k_cache, self.v_cache, self.batch, self.out, self.ws)
