@@ -129,6 +129,10 @@ size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_s
  *                       contents are scratch, not preserved, no initialisation needed
  * Validation (host side): n_new >= 1, n_cached >= 0, q_offsets are the running sum of
  * n_new and end at n_tokens, ceil((n_cached+n_new)/block_size) <= max_blocks.
+ * Tuning knobs (environment, read per call; defaults suit MI355X): FSF_DECODE_TARGET_WAVES
+ * (about how many generation-row wave units a pass is cut into, default 16384) and
+ * FSF_DECODE_MIN_ITEM_BLOCKS (no KV split leaves fewer cache blocks than this per unit,
+ * default 16).
  * Fast paths: bf16/f16 with head_dim 128 and block_size a multiple of 32; every other
  * supported shape (any dtype, head_dim <= 256 and a multiple of 4/sizeof-ratio, any
  * block_size) runs a generic fp32 kernel.

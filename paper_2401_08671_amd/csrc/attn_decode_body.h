@@ -133,7 +133,7 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   visible_range(sd.n_cached, p.window, lo, hi);
   const int b_lo = lo / B, b_hi = hi / B;
   const int nblk = b_hi - b_lo + 1;
-  const int n_splits = (nblk + f.split_blocks - 1) / f.split_blocks;
+  const int n_splits = decode_splits(nblk, f.split_blocks, f.min_item_blocks);
   // even cut: split k owns blocks [k*nblk/n_splits, (k+1)*nblk/n_splits), never empty
   const int blk0 = b_lo + (int)((int64_t)split * nblk / n_splits);
   const int blk1 = b_lo + (int)((int64_t)(split + 1) * nblk / n_splits) - 1;

@@ -22,40 +22,46 @@ constexpr int kPlanThreads = 1024;
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) {
   __shared__ int s_dec[kPlanThreads];
   __shared__ int s_pre[kPlanThreads];
+  __shared__ int s_spl[kPlanThreads];
   const int tid = threadIdx.x;
   const int per = (p.n_seqs + kPlanThreads - 1) / kPlanThreads;
   const int s0 = tid * per;
   const int s1 = min(s0 + per, p.n_seqs);
-  int dec = 0, pre = 0;
+  int dec = 0, pre = 0, spl = 0;
   for (int s = s0; s < s1; ++s) {
     int d, t;
-    seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, d, t);
+    seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, f.min_item_blocks, d, t);
     dec += d;
     pre += t;
+    spl += d > 1;
   }
   s_dec[tid] = dec;
   s_pre[tid] = pre;
+  s_spl[tid] = spl;
   __syncthreads();
   // inclusive scan over the per-thread sums
   for (int off = 1; off < kPlanThreads; off <<= 1) {
-    int a = 0, b = 0;
+    int a = 0, b = 0, c = 0;
     if (tid >= off) {
       a = s_dec[tid - off];
       b = s_pre[tid - off];
+      c = s_spl[tid - off];
     }
     __syncthreads();
     s_dec[tid] += a;
     s_pre[tid] += b;
+    s_spl[tid] += c;
     __syncthreads();
   }
-  int dec_run = s_dec[tid] - dec, pre_run = s_pre[tid] - pre;  // exclusive
+  int dec_run = s_dec[tid] - dec, pre_run = s_pre[tid] - pre, spl_run = s_spl[tid] - spl;  // exclusive
   for (int s = s0; s < s1; ++s) {
     f.dec_item_start[s] = dec_run;
     f.pre_tile_start[s] = pre_run;
     int d, t;
-    seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, d, t);
+    seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, f.min_item_blocks, d, t);
     for (int k = 0; k < d; ++k) f.dec_item_seq[dec_run + k] = s;
     for (int k = 0; k < t; ++k) f.pre_tile_seq[pre_run + k] = s;
+    if (d > 1) f.split_seqs[spl_run++] = s;
     dec_run += d;
     pre_run += t;
   }
@@ -65,14 +71,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
   }
 }
 
-// One wave per (sequence, query head); lanes own two output columns each.
+// One wave per (split sequence, query head); lanes own two output columns each.
 template <typename T>
 __global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __restrict__ out) {
-  const int s = blockIdx.x / p.n_q_heads;
-  const int hq = blockIdx.x - s * p.n_q_heads;
+  const int s = f.split_seqs[blockIdx.x / p.n_q_heads];
+  const int hq = blockIdx.x % p.n_q_heads;
   const int item0 = f.dec_item_start[s];
   const int n_splits = f.dec_item_start[s + 1] - item0;
-  if (n_splits < 2) return;  // prompt chunk, or a generation handled by a single item
   const int lane = threadIdx.x;
   float m = -INFINITY;
   for (int k = 0; k < n_splits; ++k)
@@ -101,8 +106,9 @@ hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream) {
 }
 
 hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream) {
+  if (f.n_split_seqs == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_MERGE, stream);
-  const unsigned grid = (unsigned)p.n_seqs * p.n_q_heads;
+  const unsigned grid = (unsigned)f.n_split_seqs * p.n_q_heads;
   if (p.dtype == FSF_BF16)
     merge_kernel<bf16_t><<<grid, 64, 0, stream>>>(p, f, (bf16_t*)out);
   else

@@ -63,7 +63,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace sections of the matrix-core path, in order.
 struct WsLayout {
-  size_t dec_item_start, pre_tile_start, dec_item_seq, pre_tile_seq, part_ml, part_acc, total;
+  size_t dec_item_start, pre_tile_start, dec_item_seq, pre_tile_seq, split_seqs, part_ml, part_acc, total;
 };
 
 WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
@@ -79,6 +79,8 @@ WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
   off += align256(items_cap * sizeof(int32_t));
   w.pre_tile_seq = off;
   off += align256(tiles_cap * sizeof(int32_t));
+  w.split_seqs = off;
+  off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
   w.part_ml = off;
   off += align256(items_cap * c->n_q_heads * 2 * sizeof(float));
   w.part_acc = off;
@@ -165,12 +167,12 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
     dec_blocks += hi / cfg->block_size - lo / cfg->block_size + 1;
   }
   const int target_waves = env_int("FSF_DECODE_TARGET_WAVES", 16384);
-  const int min_split = env_int("FSF_DECODE_MIN_SPLIT", 4);
+  const int min_item_blocks = env_int("FSF_DECODE_MIN_ITEM_BLOCKS", 16);
   int64_t target_items = target_waves / cfg->n_kv_heads;
   if (target_items < 1) target_items = 1;
   if (target_items > fsf::kMaxDecodeItemsExtra) target_items = fsf::kMaxDecodeItemsExtra;
   int64_t sb = (dec_blocks + target_items - 1) / target_items;
-  if (sb < min_split) sb = min_split;
+  if (sb < 1) sb = 1;
 
   const WsLayout w = ws_layout(cfg, n_seqs, n_tokens);
   char* ws = (char*)workspace;
@@ -179,22 +181,25 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.pre_tile_start = (int32_t*)(ws + w.pre_tile_start);
   f.dec_item_seq = (int32_t*)(ws + w.dec_item_seq);
   f.pre_tile_seq = (int32_t*)(ws + w.pre_tile_seq);
+  f.split_seqs = (int32_t*)(ws + w.split_seqs);
   f.part_ml = (float*)(ws + w.part_ml);
   f.part_acc = (float*)(ws + w.part_acc);
   f.split_blocks = (int32_t)sb;
+  f.min_item_blocks = min_item_blocks;
   int64_t n_dec = 0, n_pre = 0;
-  bool any_split = false;
+  int32_t n_split = 0;
   for (int32_t s = 0; s < n_seqs; ++s) {
     int d, t;
     fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
-                  f.split_blocks, d, t);
+                  f.split_blocks, f.min_item_blocks, d, t);
     n_dec += d;
     n_pre += t;
-    any_split |= d > 1;
+    n_split += d > 1;
   }
   if (n_dec > (int64_t)n_seqs + fsf::kMaxDecodeItemsExtra) return FSF_ERR_WORKSPACE;  // cannot happen
   f.n_dec_items = (int32_t)n_dec;
   f.n_pre_tiles = (int32_t)n_pre;
+  f.n_split_seqs = n_split;
 
   hipError_t e = fsf::launch_plan(p, f, stream);
   if (cfg->flags & FSF_FLAG_SEPARATE_KERNELS) {
@@ -203,6 +208,6 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   } else {
     if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
   }
-  if (e == hipSuccess && any_split) e = fsf::launch_attn_merge(p, f, out, stream);
+  if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }

@@ -50,14 +50,24 @@ __host__ __device__ inline void visible_range(int pos, int window, int& lo, int&
   lo = (window > 0 && pos - window + 1 > 0) ? pos - window + 1 : 0;
 }
 
+// Number of items a generation row over nblk cache blocks is cut into: about split_blocks
+// blocks each, but never so fine that an item holds fewer than min_item_blocks blocks
+// (short items pay more for their start-up and merge than the better balance returns).
+__host__ __device__ inline int decode_splits(int nblk, int split_blocks, int min_item_blocks) {
+  const int want = (nblk + split_blocks - 1) / split_blocks;
+  const int cap = nblk / min_item_blocks > 1 ? nblk / min_item_blocks : 1;
+  return want < cap ? want : cap;
+}
+
 // Number of decode items / prefill tiles a sequence contributes.
 __host__ __device__ inline void seq_work(int n_new, int n_cached, int window, int block_size,
-                                         int split_blocks, int& dec_items, int& pre_tiles) {
+                                         int split_blocks, int min_item_blocks, int& dec_items,
+                                         int& pre_tiles) {
   if (n_new == 1) {
     int lo, hi;
     visible_range(n_cached, window, lo, hi);
     const int nblk = hi / block_size - lo / block_size + 1;
-    dec_items = (nblk + split_blocks - 1) / split_blocks;
+    dec_items = decode_splits(nblk, split_blocks, min_item_blocks);
     pre_tiles = 0;
   } else {
     dec_items = 0;
@@ -70,10 +80,12 @@ struct FastPlan {
   int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
   int32_t* dec_item_seq;    // [items]  sequence index of every decode item
   int32_t* pre_tile_seq;    // [tiles]  sequence index of every prefill tile
+  int32_t* split_seqs;      // [n_split_seqs] sequences whose generation row was cut into > 1 item
   float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
   float* part_acc;          // [items, n_q_heads, 128] unnormalised outputs per split
-  int32_t split_blocks;
-  int32_t n_dec_items, n_pre_tiles;  // host-side totals (grid sizes)
+  int32_t split_blocks;     // target cache blocks per decode item
+  int32_t min_item_blocks;  // no split leaves an item with fewer blocks than this
+  int32_t n_dec_items, n_pre_tiles, n_split_seqs;  // host-side totals (grid sizes)
 };
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);

@@ -29,8 +29,8 @@ def check_step(step, what="", flags=0):
 @pytest.fixture
 def split_env():
     """Force fine KV splits so the merge path runs even on short sequences."""
-    old = {k: os.environ.get(k) for k in ("FSF_DECODE_TARGET_WAVES", "FSF_DECODE_MIN_SPLIT")}
-    yield lambda waves, mins: os.environ.update(FSF_DECODE_TARGET_WAVES=str(waves), FSF_DECODE_MIN_SPLIT=str(mins))
+    old = {k: os.environ.get(k) for k in ("FSF_DECODE_TARGET_WAVES", "FSF_DECODE_MIN_ITEM_BLOCKS")}
+    yield lambda waves, mins: os.environ.update(FSF_DECODE_TARGET_WAVES=str(waves), FSF_DECODE_MIN_ITEM_BLOCKS=str(mins))
     for k, v in old.items():
         if v is None:
             os.environ.pop(k, None)
