@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 
 from paper_2401_08671_amd import fsf  # noqa: E402
 from paper_2401_08671_amd import workloads as wl  # noqa: E402
-from paper_2401_08671_amd.harness import DeviceStep, algorithmic_work  # noqa: E402
+from paper_2401_08671_amd.harness import DeviceStep, StreamRunner, algorithmic_work  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
@@ -72,12 +72,85 @@ def cpu_baseline(ds: DeviceStep, k_cache0: np.ndarray, v_cache0: np.ndarray, n_d
                         f"full batch by visible keys; numpy fp64")), ref
 
 
+def stream_bench(args):
+    """Benchmark shape 5: 200 consecutive passes of the long-prompt stream, batches from fsf_compose_batch."""
+    n_steps = 200
+    run = StreamRunner(n_steps=n_steps, rate=1.0)
+    # one fixed set of new-token tensors, sliced per pass (values do not affect timing)
+    q_all, k_all, v_all = run.new_tokens(0, run.budget)
+    warm = DeviceStep(wl.config(2, n_decodes=8))          # load the kernels before timing
+    for _ in range(max(1, args.warmup)):
+        warm.step()
+    torch.cuda.synchronize()
+    del warm
+    fsf.profile_enable(True)
+    fsf.profile_read()
+    per_step = []
+    t_compose = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for step in range(n_steps):
+        tc = time.perf_counter()
+        descs, tables, _ = run.compose()
+        t_compose += time.perf_counter() - tc
+        T = int(descs[:, 0].sum()) if len(descs) else 0
+        run.run_pass(descs, tables, q_all[:T], k_all[:T], v_all[:T])
+        run.commit()
+        spec = wl.BatchSpec(f"pass{step}", run.Hq, run.Hkv, run.d, run.B, run.dtype,
+                            [(int(n), int(c)) for n, c, _, _ in descs])
+        per_step.append((T, algorithmic_work(spec) if T else None))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = fsf.profile_read()
+    fsf.profile_enable(False)
+    total_tokens = sum(t for t, _ in per_step)
+    gpu_ms = sum(v[0] for v in prof.values())
+    fused_ms = prof["fused"][0]
+    bytes_ = sum(w["decode_bytes"] + w["prefill_bytes"] for _, w in per_step if w)
+    flops = sum(w["decode_flops"] + w["prefill_flops"] for _, w in per_step if w)
+    t_hbm = sum((w["decode_bytes"] + w["prefill_bytes"]) / (HBM_PEAK_GBS * 1e9) for _, w in per_step if w)
+    t_mfma = sum((w["decode_flops"] + w["prefill_flops"]) / (MFMA_BF16_PEAK_TFLOPS * 1e12) for _, w in per_step if w)
+    # ideal time of the stream = sum over passes of max(bytes / HBM peak, flops / MFMA peak)
+    t_ideal = sum(max((w["decode_bytes"] + w["prefill_bytes"]) / (HBM_PEAK_GBS * 1e9),
+                      (w["decode_flops"] + w["prefill_flops"]) / (MFMA_BF16_PEAK_TFLOPS * 1e12)) for _, w in per_step if w)
+    hbm_bound = t_hbm >= t_mfma
+    wall_ms = (t1 - t0) * 1e3
+    line = {
+        "metric": "ragged SplitFuse attn tokens/s per step + % HBM/MFMA roofline, 1 GPU",
+        "value": total_tokens / (t1 - t0), "unit": "tokens/s", "n_gpus": 1, "steps": n_steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms / n_steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": run.dtype, "data": "synthetic",
+        "config": {"workload": f"cfg5-13b-stream: Hq={run.Hq} Hkv={run.Hkv} d={run.d} block={run.B} budget={run.budget}, "
+                               f"{n_steps} consecutive passes composed by fsf_compose_batch, {len(run.requests)} requests "
+                               "(log-normal prompts, Poisson(1.0) arrivals per pass), one layer; wall clock includes "
+                               "host composition and descriptor upload",
+                   "total_tokens": total_tokens, "kv_pool_blocks": run.num_blocks},
+        "roofline": ({"bound": "hbm", "kernel": "attn_fused_kernel", "achieved": bytes_ / (fused_ms * 1e-3) / 1e9,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_ / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "traffic": None, "algorithmic_bytes_all_launches": bytes_, "total_launch_ms": fused_ms}
+                     if hbm_bound else
+                     {"bound": "mfma", "kernel": "attn_fused_kernel", "achieved": flops / (fused_ms * 1e-3) / 1e12,
+                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": flops / (fused_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                      "algorithmic_flops_all_launches": flops, "total_launch_ms": fused_ms}),
+        "stream": {"gpu_kernel_ms_total": gpu_ms, "gpu_tokens_per_s": total_tokens / (gpu_ms * 1e-3),
+                   "host_compose_ms_total": t_compose * 1e3, "wall_ms_total": wall_ms,
+                   "ideal_ms_total_max_of_rooflines": t_ideal * 1e3,
+                   "frac_of_per_pass_roofline": t_ideal * 1e3 / fused_ms,
+                   "phases_ms_total": {k: v[0] for k, v in prof.items()},
+                   "tokens_per_pass_min_median_max": [int(np.min([t for t, _ in per_step])),
+                                                      int(np.median([t for t, _ in per_step])),
+                                                      int(np.max([t for t, _ in per_step]))]},
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 6])
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5, 6])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -87,6 +160,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.config == 5:
+        return stream_bench(args)
     spec = wl.config(args.config)
     ds = DeviceStep(spec)
     work = algorithmic_work(spec)

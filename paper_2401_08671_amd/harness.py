@@ -70,3 +70,63 @@ class DeviceStep:
         cfg = self.cfg_separate if separate else self.cfg
         fsf.kv_append(cfg, self.k_new, self.v_new, self.k_cache, self.v_cache, self.batch)
         fsf.ragged_attention(cfg, self.q, self.k_cache, self.v_cache, self.batch, self.out, self.ws)
+
+
+class StreamRunner:
+    """The long-prompt stream: requests arrive step by step, fsf_compose_batch builds every pass.
+
+    Each pass: arrivals -> compose (host) -> descriptors and block tables to the device ->
+    fsf_kv_append + fsf_ragged_attention -> step_done.  New-token tensors are drawn per pass
+    from a seeded generator (there is no model: the "generated token" is just a counter).
+    """
+
+    def __init__(self, n_steps: int = 200, rate: float = 1.0, seed: int = 1005, device="cuda"):
+        shp = wl.stream_shape()
+        self.Hq, self.Hkv, self.d, self.B = shp["n_q_heads"], shp["n_kv_heads"], shp["head_dim"], shp["block_size"]
+        self.dtype, self.budget, self.n_steps = shp["dtype"], shp["token_budget"], n_steps
+        self.device = device
+        self.requests = wl.stream_requests(n_steps, rate, seed)
+        self.arrivals = {}
+        for step, sid, plen, gen in self.requests:
+            self.arrivals.setdefault(step, []).append((sid, plen, gen))
+        need = sum(-(-(p + g) // self.B) for _, _, p, g in self.requests)
+        self.num_blocks = need + 64
+        self.max_blocks = -(-(32768 + 600) // self.B)
+        self.max_seqs = self.budget
+        rng = np.random.default_rng(seed)
+        self.sched = fsf.Scheduler(self.budget, self.max_seqs, self.B, self.num_blocks, self.max_blocks,
+                                   rng.permutation(self.num_blocks))
+        tdt = wl.TORCH_DTYPE[self.dtype]
+        self.k_cache = torch.zeros((self.num_blocks, self.Hkv, self.B, self.d), dtype=tdt, device=device)
+        self.v_cache = torch.zeros_like(self.k_cache)
+        self.cfg = fsf.make_cfg(self.Hq, self.Hkv, self.d, self.B, self.dtype, self.num_blocks)
+        self.ws = fsf.alloc_workspace(self.cfg, self.max_seqs, self.budget, self.max_blocks, device)
+        self.out = torch.zeros((self.budget, self.Hq, self.d), dtype=tdt, device=device)
+        self.step_index = 0
+
+    def new_tokens(self, step: int, n_tokens: int):
+        """Q, K, V rows of this pass (seeded by the step index)."""
+        q = wl.randn((n_tokens, self.Hq, self.d), self.dtype, 1.0, 50_000 + 3 * step, self.device)
+        k = wl.randn((n_tokens, self.Hkv, self.d), self.dtype, 1.0, 50_001 + 3 * step, self.device)
+        v = wl.randn((n_tokens, self.Hkv, self.d), self.dtype, 1.0, 50_002 + 3 * step, self.device)
+        return q, k, v
+
+    def compose(self):
+        """Arrivals + fsf_compose_batch for the next pass; returns (descs, block_tables, emits)."""
+        for sid, plen, gen in self.arrivals.get(self.step_index, []):
+            self.sched.add_request(sid, plen, gen)
+        return self.sched.compose_batch()
+
+    def run_pass(self, descs, tables, q, k_new, v_new):
+        """Enqueue append + attention for a composed pass; returns the output view [T, Hq, d]."""
+        batch = fsf.DeviceBatch(descs, tables, self.device)
+        if batch.n_seqs == 0:
+            return self.out[:0]
+        out = self.out[:batch.n_tokens]
+        fsf.kv_append(self.cfg, k_new, v_new, self.k_cache, self.v_cache, batch)
+        fsf.ragged_attention(self.cfg, q, self.k_cache, self.v_cache, batch, out, self.ws)
+        return out
+
+    def commit(self):
+        self.sched.step_done()
+        self.step_index += 1
