@@ -30,10 +30,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastP
                                                                  const T* __restrict__ kc,
                                                                  const T* __restrict__ vc,
                                                                  T* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) char lds[kPrefillLdsBytes];
+  __shared__ __attribute__((aligned(1024))) char lds0[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
   int tile, hq;
   prefill_block_to_work(p, f, blockIdx.x, tile, hq);
-  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, lds);
+  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1);
 }
 
 template <int DT, typename T>
@@ -53,7 +54,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
                                                                const T* __restrict__ kc,
                                                                const T* __restrict__ vc,
                                                                T* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) char lds[kPrefillLdsBytes];
+  __shared__ __attribute__((aligned(1024))) char lds0[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
   // Workgroup numbering alternates the two kinds of work for as long as both last, so that a
   // compute unit tends to hold one matrix-core-bound and one HBM-bound workgroup at a time.
   const int n_pre = f.n_pre_tiles * p.n_q_heads;
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
   if (is_prefill) {  // uniform per workgroup
     int tile, hq;
     prefill_block_to_work(p, f, idx, tile, hq);
-    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, lds);
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1);
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;

@@ -7,19 +7,25 @@
 // One workgroup (4 waves) owns a tile of 4*32*NQ consecutive rows of one sequence and one
 // query head; wave w owns 32*NQ of them.  Keys are taken 64 at a time (never straddling a
 // cache block since block_size % 64 == 0), gathered through the block table:
-//   global -> registers (prefetched one step ahead) -> LDS
-//     K   [64 keys][128 d], 16-byte chunks XOR-swizzled by key so that the 32x32x16
-//         A-operand reads (32 consecutive keys, one chunk) spread over all banks
-//     V^T [128 d][64 key slots]: transposed in registers (byte permutes) on the way in, with
-//         the key order inside each 16 permuted so that the 8 keys a lane owns after the
-//         first product are 16 contiguous bytes
-//   S^T[key, row] = K . Q^T          (A = K from LDS, B = Q^T held in registers)
-//   running softmax per row: a lane owns 32 scores of one row per q-tile, max/sum across
-//   the two half-waves by one xor-32 shuffle
-//   O^T[d, row] += V^T . P^T         (A = V^T from LDS, B = P^T = the lane's own scores,
-//                                    no cross-lane movement)
-// Masking (causal diagonal, window edge, rows past the chunk end) uses selects on the
-// scores; wave-level tests skip steps that are entirely hidden from the wave's rows.
+//   HBM/L2 -> LDS directly (global_load_lds, 16 bytes per lane, no registers, no VALU).
+//     Both tiles stay row-major [64 keys][128 d]; the lane -> global chunk mapping applies an
+//     XOR swizzle so the later reads are bank-conflict free:
+//       K: 16-byte chunk c of key row r sits at chunk c ^ (r & 7)
+//       V: 32-byte segment s of key row r sits at segment s ^ (r & 7)
+//     Rows past the sequence's last token are fetched from its last token instead: their
+//     scores are masked, and a finite stand-in keeps 0 * garbage out of the second product.
+//   S^T[key, row] = K . Q^T     A = K rows (ds_read_b128), B = Q^T held in registers
+//   running softmax per row in registers: a lane owns 32 scores of one row per q-tile, the
+//   max across the two half-waves is one xor-32 shuffle; the running reference is only
+//   raised when a maximum outgrows it by 2^8 (lazy rescale), so the accumulators are not
+//   touched by VALU code in the steady state
+//   O^T[d, row] += V^T . P^T    A = V^T read from the row-major V tile with the transposing
+//                               LDS read (ds_read_b64_tr_b16: a 16-lane group reads 4 keys x
+//                               16 d and each lane receives 4 keys of one d); B = P^T = the
+//                               lane's own probabilities, no cross-lane movement
+// Two LDS stages (separate arrays, so the compiler can tell the stage being filled from the
+// stage being read): the copy for step j+1 is in flight while step j is computed; one
+// barrier per step.
 #pragma once
 
 #include <math.h>
@@ -32,43 +38,42 @@ namespace fsf {
 
 constexpr int NQ = kPrefillTileM / 128;  // 32-row q-tiles per wave
 constexpr int kKeysPerStep = 64;
-constexpr int kKTileBytes = 64 * 256;            // K tile [64 keys][128 d]
-constexpr int kStageBytes = kKTileBytes + 128 * 128;  // + V^T tile [128 d][64 keys]
-constexpr int kFragAhead = 4;                     // K fragments in flight from LDS (k-steps)
-constexpr int kVAhead = 4;                        // V^T fragments in flight from LDS
-constexpr int kPrefillLdsBytes = 2 * kStageBytes;
-constexpr float kLazyLog2 = 8.f;  // running-max slack before accumulators are rescaled
+constexpr int kTileBytes = 64 * 256;         // one K or V tile: [64 keys][128 d] of 2-byte elements
+constexpr int kStageBytes = 2 * kTileBytes;  // K tile + V tile
+constexpr int kFragAhead = 4;                // K fragments in flight from LDS (k-steps)
+constexpr int kVAhead = 4;                   // V^T fragments in flight from LDS
+constexpr float kLazyLog2 = 8.f;             // running-max slack before accumulators are rescaled
 
-struct Prefetch {
-  frag8 k[4];
-  frag8 v[4];
-};
+typedef __attribute__((address_space(3))) char lds_char;
+typedef short v4s16 __attribute__((ext_vector_type(4)));
 
+// Start the asynchronous copy of one 64-key step (K and V tiles) into an LDS stage.
+// Each of the 4 waves copies 16 key rows: 4 instructions x (4 rows x 256 B) per tile.
 template <typename T>
-__device__ __forceinline__ void prefetch_step(Prefetch& pf, const T* __restrict__ kc,
-                                              const T* __restrict__ vc, const int32_t* bt,
-                                              int key0, int B, int n_kv_heads, int hk, int tid,
-                                              int kv_last) {
+__device__ __forceinline__ void stage_step(lds_char* stage, const T* __restrict__ kc,
+                                           const T* __restrict__ vc, const int32_t* bt, int key0,
+                                           int B, int n_kv_heads, int hk, int wave, int lane,
+                                           int kv_last) {
   const int blk = key0 / B;
   const int64_t phys = bt[blk];
   const int64_t base = ((phys * n_kv_heads + hk) * B + (key0 - blk * B)) * kHeadDim;
-  const T* kb = kc + base;
-  const T* vb = vc + base;
-  const int dchunk = tid & 15;
+  const char* kb = reinterpret_cast<const char*>(kc + base);
+  const char* vb = reinterpret_cast<const char*>(vc + base);
+  const int max_row = kv_last - key0;  // >= 0: last row of this step that holds a written token
+  const int pc = lane & 15;            // physical 16-byte chunk this lane fills
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int row = (tid >> 4) + 16 * i;
-    pf.k[i] = load_frag8(kb + row * kHeadDim + dchunk * 8);
-  }
-  const int j = tid >> 4;  // keys 4j .. 4j+3
-#pragma unroll
-  for (int i = 0; i < 4; ++i) pf.v[i] = load_frag8(vb + (4 * j + i) * kHeadDim + dchunk * 8);
-  // slots past the sequence's last token were never written: their V must not meet a
-  // zero probability as NaN or Inf, so they are cleared (their scores are masked anyway)
-  if (key0 + kKeysPerStep - 1 > kv_last) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (key0 + 4 * j + i > kv_last) pf.v[i] = zero_frag8();
+    const int row0 = wave * 16 + i * 4;  // first of the 4 rows this instruction fills (uniform)
+    const int row = row0 + (lane >> 4);
+    const int src_row = row < max_row ? row : max_row;
+    const char* ksrc = kb + src_row * 256 + ((pc ^ (row & 7)) << 4);
+    const char* vsrc = vb + src_row * 256 + ((pc ^ ((row & 7) << 1)) << 4);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ksrc,
+                                     (__attribute__((address_space(3))) void*)(stage + row0 * 256),
+                                     16, 0, 0);
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)vsrc,
+        (__attribute__((address_space(3))) void*)(stage + kTileBytes + row0 * 256), 16, 0, 0);
   }
 }
 
@@ -76,43 +81,189 @@ __device__ __forceinline__ void prefetch_step(Prefetch& pf, const T* __restrict_
 __device__ __forceinline__ int k_lds_off(int key, int chunk) {
   return key * 256 + ((chunk ^ (key & 7)) << 4);
 }
-// byte offset of 16-byte chunk `chunk` (8 key slots) of row d in the V^T tile
-__device__ __forceinline__ int vt_lds_off(int d, int chunk) {
-  return d * 128 + ((chunk ^ ((d ^ (d >> 3)) & 7)) << 4);
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ frag8 lds_load_frag8(const lds_char* ptr) {
+  const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(ptr);
+  return frag8{{v[0], v[1], v[2], v[3]}};
 }
 
-__device__ __forceinline__ void store_step(const Prefetch& pf, char* k_lds, char* vt_lds, int tid) {
-  const int dchunk = tid & 15;
+// 8 storage elements V[keys][d] for the A operand of O^T += V^T P^T: lane (d = mt*32 + l32,
+// k-group hg), k-step u.  Slots 0..3 are keys 16u + 4hg + 0..3, slots 4..7 keys 16u + 8 + 4hg
+// + 0..3 (the order in which the first product leaves the probabilities in registers).
+// ds_read_b64_tr_b16 works on 16-lane groups: the group's lanes point at 4 key rows x 4
+// 8-byte units (lane s: row s/4, unit s%4) and lane i receives, for d = unit_base + i, the
+// 4 keys.  Group g of the wave covers d half (g & 1) and k-group g >> 1.
+__device__ __forceinline__ frag8 load_vt_frag(const lds_char* vtile, int u, int mt, int lane) {
+  const int s = lane & 15, g = lane >> 4;
+  const int hg = g >> 1, dhalf = g & 1;
+  const int seg = 2 * mt + dhalf;  // logical 32-byte segment of the row
+  frag8 f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (tid >> 4) + 16 * i;
-    *reinterpret_cast<uint4*>(k_lds + k_lds_off(row, dchunk)) =
-        uint4{pf.k[i].w[0], pf.k[i].w[1], pf.k[i].w[2], pf.k[i].w[3]};
+  for (int r = 0; r < 2; ++r) {
+    const int row = 16 * u + 8 * r + 4 * hg + (s >> 2);
+    const int off = row * 256 + ((seg ^ (row & 7)) << 5) + ((s & 3) << 3);
+    const v4s16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (v4s16 __attribute__((address_space(3)))*)(vtile + off));
+    const uint2 w = __builtin_bit_cast(uint2, v);
+    f.w[2 * r] = w.x;
+    f.w[2 * r + 1] = w.y;
   }
-  // V: this thread holds keys 4j..4j+3 x 8 d-columns; write 8 rows of 4 keys (8 bytes each)
-  const int j = tid >> 4;
-  const int key16 = (4 * j) & 15;
-  const int b3 = (key16 >> 3) & 1, b2 = (key16 >> 2) & 1;
-  const int chunk = 2 * (j >> 2) + b2;  // (16-key group)*2 + half
-  const int sub = b3 * 8;               // byte offset inside the 16-byte chunk
+  return f;
+}
+
+struct PrefillState {
+  f32x16_t acc[4][NQ];
+  float m_run[NQ], l_run[NQ];
+};
+
+// One 64-key step for one wave, reading the tiles of `stage`.
+template <int DT>
+__device__ __forceinline__ void prefill_compute_step(PrefillState& st, const lds_char* stage,
+                                                     const frag8 (&qf)[NQ][8],
+                                                     const int (&row_pos)[NQ], int key0, int window,
+                                                     float sl2, bool need_mask, int l32, int hg,
+                                                     int lane) {
+  using M = Mma<DT>;
+  const lds_char* kl = stage;
+  const lds_char* vl = stage + kTileBytes;
+
+  // ---- S^T = K . Q^T ; K fragments are fetched from LDS kFragAhead k-steps ahead of their use
+  f32x16_t sc[2][NQ];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    const uint32_t a0 = pf.v[0].w[c >> 1], a1 = pf.v[1].w[c >> 1];
-    const uint32_t a2 = pf.v[2].w[c >> 1], a3 = pf.v[3].w[c >> 1];
-    uint2 w;
-    w.x = (c & 1) ? pack_hi16(a0, a1) : pack_lo16(a0, a1);
-    w.y = (c & 1) ? pack_hi16(a2, a3) : pack_lo16(a2, a3);
-    const int d = dchunk * 8 + c;
-    *reinterpret_cast<uint2*>(vt_lds + vt_lds_off(d, chunk) + sub) = w;
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[kt][qt][r] = 0.f;
+  {
+    frag8 kf[kFragAhead][2];
+#pragma unroll
+    for (int t = 0; t < kFragAhead; ++t)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+        kf[t][kt] = lds_load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * t + hg));
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt)
+          sc[kt][qt] = M::mfma32(kf[t % kFragAhead][kt], qf[qt][t], sc[kt][qt]);
+        if (t + kFragAhead < 8)
+          kf[t % kFragAhead][kt] =
+              lds_load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * (t + kFragAhead) + hg));
+      }
+    }
+    // pin the issue order: kFragAhead k-steps of LDS reads up front, then reads and MFMAs in turn
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragAhead, 0);
+#pragma unroll
+    for (int t = 0; t < 8 - kFragAhead; ++t) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ * kFragAhead, 0);
   }
+
+  // ---- mask, row maxima, and the (rare) raise of the running reference
+  if (need_mask) {
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt) {
+      int rlo, rhi;
+      visible_range(row_pos[qt], window, rlo, rhi);  // rows past the tile: rhi = -1, nothing visible
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * hg + (r & 3);
+          if (key < rlo || key > rhi) sc[kt][qt][r] = -INFINITY;
+        }
+    }
+  }
+  // Lazy rescale: the running reference m_run only has to bound the scores from above
+  // loosely.  It is raised (and acc, l rescaled) only when a row's maximum outgrows it by
+  // more than 2^kLazyLog2, so probabilities stay <= 2^kLazyLog2.
+  float m_cand[NQ];
+  bool raise = false;
+#pragma unroll
+  for (int qt = 0; qt < NQ; ++qt) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kt][qt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    m_cand[qt] = fmaxf(st.m_run[qt], mx * sl2);
+    raise |= m_cand[qt] - st.m_run[qt] > kLazyLog2;
+  }
+  if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt) {
+      const float m_new = (m_cand[qt] - st.m_run[qt] > kLazyLog2) ? m_cand[qt] : st.m_run[qt];
+      const float corr = fast_exp2(st.m_run[qt] - m_new);
+      st.m_run[qt] = m_new;
+      st.l_run[qt] *= corr;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.acc[mt][qt][r] *= corr;
+    }
+  }
+
+  // ---- probabilities and P^T fragments
+  frag8 pfr[NQ][4];
+#pragma unroll
+  for (int qt = 0; qt < NQ; ++qt) {
+    const float m_ref = st.m_run[qt];
+    float sum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pr = fast_exp2(fmaf(sc[kt][qt][r], sl2, -m_ref));
+        sc[kt][qt][r] = pr;
+        sum += pr;
+      }
+    st.l_run[qt] += sum;
+    // k-step u of the second product covers keys 16u..16u+15: registers 8(u%2)..+7 of tile u/2
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj)
+        pfr[qt][u].w[jj] = M::pack2(sc[u >> 1][qt][8 * (u & 1) + 2 * jj],
+                                    sc[u >> 1][qt][8 * (u & 1) + 2 * jj + 1]);
+  }
+
+  // ---- O^T += V^T . P^T ; V^T fragments come from LDS kVAhead MFMAs ahead of their use
+  frag8 vf[kVAhead];  // rolling window over i = u*4 + mt
+#pragma unroll
+  for (int i = 0; i < kVAhead; ++i) vf[i] = load_vt_frag(vl, i >> 2, i & 3, lane);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int u = i >> 2, mt = i & 3;
+#pragma unroll
+    for (int qt = 0; qt < NQ; ++qt)
+      st.acc[mt][qt] = M::mfma32(vf[i % kVAhead], pfr[qt][u], st.acc[mt][qt]);
+    if (i + kVAhead < 16)
+      vf[i % kVAhead] = load_vt_frag(vl, (i + kVAhead) >> 2, (i + kVAhead) & 3, lane);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x100, 2 * kVAhead, 1);
+#pragma unroll
+  for (int i = 0; i < 16 - kVAhead; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, NQ, 1);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, NQ * kVAhead, 1);
 }
 
 // One workgroup of 256 threads: tile = index into the pass's prefill tiles, hq = query head.
-// lds: kPrefillLdsBytes of workgroup-shared memory.
+// lds0, lds1: two LDS stages of kStageBytes each (distinct arrays).
 template <int DT, typename T>
-__device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f, const T* __restrict__ q,
-                                             const T* __restrict__ kc, const T* __restrict__ vc,
-                                             T* __restrict__ out, int tile, int hq, char* lds) {
+__device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
+                                             const T* __restrict__ q, const T* __restrict__ kc,
+                                             const T* __restrict__ vc, T* __restrict__ out, int tile,
+                                             int hq, lds_char* lds0, lds_char* lds1) {
   using M = Mma<DT>;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -143,9 +294,12 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f, c
     visible_range(c + w_i1 - 1, p.window, w_lo_max, w_hi_max);
   }
 
+  // the first copy goes out before anything else
+  stage_step(lds0, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, wave, lane, kv_last);
+
   // Q^T fragments (B operand): lane = (row l32 of q-tile, k-group hg), k-step t -> d chunk 2t+hg
   frag8 qf[NQ][8];
-  int row_pos[NQ];  // absolute position of the lane's row per q-tile (clamped rows: -1)
+  int row_pos[NQ];  // absolute position of the lane's row per q-tile (rows past the tile: -1)
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
     const int i = w_i0 + qt * 32 + l32;
@@ -157,173 +311,45 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f, c
     for (int t = 0; t < 8; ++t) qf[qt][t] = load_frag8(qrow + (2 * t + hg) * 8);
   }
 
-  f32x16_t acc[4][NQ];
+  PrefillState st;
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mt][qt][r] = 0.f;
-  float m_run[NQ], l_run[NQ];
+      for (int r = 0; r < 16; ++r) st.acc[mt][qt][r] = 0.f;
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
-    m_run[qt] = -1e30f;
-    l_run[qt] = 0.f;
+    st.m_run[qt] = -1e30f;
+    st.l_run[qt] = 0.f;
   }
   const float sl2 = p.scale * 1.4426950408889634f;
 
-  // Two LDS stages: while step j is computed from stage j&1, step j+1 sits in registers on its
-  // way to stage (j+1)&1 and step j+2 is in flight from HBM/L2.  One barrier per step.
-  Prefetch pre;
-  prefetch_step(pre, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, tid, kv_last);
-  store_step(pre, lds, lds + kKTileBytes, tid);
-  if (key_begin + kKeysPerStep <= hi_t)
-    prefetch_step(pre, kc, vc, bt, key_begin + kKeysPerStep, B, p.n_kv_heads, hk, tid, kv_last);
-
-  int stage = 0;
-  for (int key0 = key_begin; key0 <= hi_t; key0 += kKeysPerStep, stage ^= 1) {
-    __syncthreads();  // stage `stage` is complete; everyone is done reading stage^1
-    if (key0 + kKeysPerStep <= hi_t) {
-      store_step(pre, lds + (stage ^ 1) * kStageBytes, lds + (stage ^ 1) * kStageBytes + kKTileBytes, tid);
-      if (key0 + 2 * kKeysPerStep <= hi_t)
-        prefetch_step(pre, kc, vc, bt, key0 + 2 * kKeysPerStep, B, p.n_kv_heads, hk, tid, kv_last);
+  // Steps alternate between the two stages; the loop is unrolled by two so that each half
+  // names its stage statically.
+  for (int key0 = key_begin; key0 <= hi_t; key0 += 2 * kKeysPerStep) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int k0 = key0 + half * kKeysPerStep;
+      if (k0 > hi_t) break;
+      lds_char* cur = half ? lds1 : lds0;
+      lds_char* nxt = half ? lds0 : lds1;
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of step k0 has landed
+      __syncthreads();                     // ... and everyone's; everyone is done reading `nxt`
+      if (k0 + kKeysPerStep <= hi_t)
+        stage_step(nxt, kc, vc, bt, k0 + kKeysPerStep, B, p.n_kv_heads, hk, wave, lane, kv_last);
+      // hidden from every row of this wave?
+      if (!wave_live || k0 > w_hi_max || k0 + kKeysPerStep - 1 < w_lo_min) continue;
+      const bool need_mask =
+          k0 + kKeysPerStep - 1 > w_hi_min || k0 < w_lo_max || w_i1 - w_i0 < 32 * NQ;
+      prefill_compute_step<DT>(st, cur, qf, row_pos, k0, p.window, sl2, need_mask, l32, hg, lane);
     }
-    // hidden from every row of this wave?
-    if (!wave_live || key0 > w_hi_max || key0 + kKeysPerStep - 1 < w_lo_min) continue;
-    const char* kl = lds + stage * kStageBytes;
-    const char* vl = kl + kKTileBytes;
-
-    // ---- S^T = K . Q^T ; K fragments are fetched from LDS kFragAhead k-steps ahead of their use
-    f32x16_t sc[2][NQ];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sc[kt][qt][r] = 0.f;
-    {
-      frag8 kf[kFragAhead][2];
-#pragma unroll
-      for (int t = 0; t < kFragAhead; ++t)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) kf[t][kt] = load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * t + hg));
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-          for (int qt = 0; qt < NQ; ++qt)
-            sc[kt][qt] = M::mfma32(kf[t % kFragAhead][kt], qf[qt][t], sc[kt][qt]);
-          if (t + kFragAhead < 8)
-            kf[t % kFragAhead][kt] = load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * (t + kFragAhead) + hg));
-        }
-      }
-      // pin the issue order: kFragAhead k-steps of LDS reads up front, then reads and MFMAs in turn
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragAhead, 0);
-#pragma unroll
-      for (int t = 0; t < 8 - kFragAhead; ++t) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ * kFragAhead, 0);
-    }
-
-
-    // ---- mask, row maxima, and the (rare) raise of the running reference
-    const bool need_mask = key0 + kKeysPerStep - 1 > w_hi_min || key0 < w_lo_max || w_i1 - w_i0 < 32 * NQ;
-    if (need_mask) {
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        int rlo, rhi;
-        visible_range(row_pos[qt], p.window, rlo, rhi);  // dead rows: rhi = -1, nothing visible
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * hg + (r & 3);
-            if (key < rlo || key > rhi) sc[kt][qt][r] = -INFINITY;
-          }
-      }
-    }
-    // Lazy rescale: the running reference m_run only has to bound the scores from above
-    // loosely.  It is raised (and acc, l rescaled) only when a row's maximum outgrows it by
-    // more than 2^kLazyLog2, so probabilities stay <= 2^kLazyLog2 and the rescale of the
-    // accumulator registers leaves the steady-state loop.
-    float m_cand[NQ];
-    bool raise = false;
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kt][qt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      m_cand[qt] = fmaxf(m_run[qt], mx * sl2);
-      raise |= m_cand[qt] - m_run[qt] > kLazyLog2;
-    }
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) {
-        const float m_new = (m_cand[qt] - m_run[qt] > kLazyLog2) ? m_cand[qt] : m_run[qt];
-        const float corr = fast_exp2(m_run[qt] - m_new);
-        m_run[qt] = m_new;
-        l_run[qt] *= corr;
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[mt][qt][r] *= corr;
-      }
-    }
-
-    // ---- probabilities and P^T fragments
-    frag8 pfr[NQ][4];
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      const float m_ref = m_run[qt];
-      float sum = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float pr = fast_exp2(fmaf(sc[kt][qt][r], sl2, -m_ref));
-          sc[kt][qt][r] = pr;
-          sum += pr;
-        }
-      l_run[qt] += sum;
-      // k-step u of the second product covers keys 16u..16u+15: registers 8(u%2)..+7 of tile u/2
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-          pfr[qt][u].w[jj] = M::pack2(sc[u >> 1][qt][8 * (u & 1) + 2 * jj], sc[u >> 1][qt][8 * (u & 1) + 2 * jj + 1]);
-    }
-
-    // ---- O^T += V^T . P^T ; V^T fragments come from LDS kVAhead MFMAs ahead of their use
-    frag8 vf[kVAhead];  // rolling window over i = u*4 + mt
-#pragma unroll
-    for (int i = 0; i < kVAhead; ++i) vf[i] = load_frag8(vl + vt_lds_off((i & 3) * 32 + l32, 2 * (i >> 2) + hg));
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int u = i >> 2, mt = i & 3;
-#pragma unroll
-      for (int qt = 0; qt < NQ; ++qt) acc[mt][qt] = M::mfma32(vf[i % kVAhead], pfr[qt][u], acc[mt][qt]);
-      if (i + kVAhead < 16)
-        vf[i % kVAhead] = load_frag8(vl + vt_lds_off(((i + kVAhead) & 3) * 32 + l32, 2 * ((i + kVAhead) >> 2) + hg));
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, kVAhead, 1);
-#pragma unroll
-    for (int i = 0; i < 16 - kVAhead; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, NQ, 1);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, NQ * kVAhead, 1);
   }
 
   // ---- normalise and store: acc[mt][qt][r] is column d = 32mt + 8(r/4) + 4hg + r%4 of the lane's row
 #pragma unroll
   for (int qt = 0; qt < NQ; ++qt) {
-    float l = l_run[qt];
+    float l = st.l_run[qt];
     l += __shfl_xor(l, 32);
     if (row_pos[qt] < 0) continue;
     const float inv = 1.f / l;
@@ -334,12 +360,11 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f, c
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
         uint2 w;
-        w.x = M::pack2(acc[mt][qt][4 * rq] * inv, acc[mt][qt][4 * rq + 1] * inv);
-        w.y = M::pack2(acc[mt][qt][4 * rq + 2] * inv, acc[mt][qt][4 * rq + 3] * inv);
+        w.x = M::pack2(st.acc[mt][qt][4 * rq] * inv, st.acc[mt][qt][4 * rq + 1] * inv);
+        w.y = M::pack2(st.acc[mt][qt][4 * rq + 2] * inv, st.acc[mt][qt][4 * rq + 3] * inv);
         *reinterpret_cast<uint2*>(orow + 32 * mt + 8 * rq + 4 * hg) = w;
       }
   }
 }
-
 
 }  // namespace fsf

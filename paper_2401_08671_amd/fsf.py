@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfsf.so")
+LIB_PATH = os.environ.get("FSF_LIB_PATH", os.path.join(_HERE, "libfsf.so"))
 
 FSF_OK, FSF_ERR_INVALID_ARG, FSF_ERR_UNSUPPORTED, FSF_ERR_WORKSPACE, FSF_ERR_NO_BLOCKS, FSF_ERR_HIP = 0, -1, -2, -3, -4, -5
 FSF_F32, FSF_BF16, FSF_F16 = 0, 1, 2
