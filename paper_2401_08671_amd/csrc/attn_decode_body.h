@@ -40,7 +40,7 @@ __device__ __forceinline__ void load_step(StepBuf& b, const T* __restrict__ kc,
                                           const T* __restrict__ vc, const int32_t* bt, int key0,
                                           int B, int n_kv_heads, int hk, int n, int kg) {
   const int blk = key0 / B;                      // uniform
-  const int64_t phys = bt[blk];                  // scalar load
+  const int64_t phys = load_uniform_i32(bt + blk);
   const int slot0 = key0 - blk * B;
   const int64_t base = ((phys * n_kv_heads + hk) * B + slot0) * kHeadDim;
   const T* kb = kc + base;
@@ -156,20 +156,28 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   float m = -1e30f, l = 0.f;
   const float sl2 = p.scale * 1.4426950408889634f;
 
+  // Two register buffers.  The steady-state loop issues every load unconditionally, so the
+  // compiler's in-order wait counts let step i compute while all of step i+1 is in flight.
   StepBuf b0, b1;
-  int key0 = key_begin;
-  load_step(b0, kc, vc, bt, key0, B, p.n_kv_heads, hk, n, kg);
-  while (true) {
-    bool more = key0 + 32 <= key_end;
-    if (more) load_step(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
+  const int n_steps = (key_end - key_begin) / 32 + 1;
+  int i = 0;
+  load_step(b0, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, n, kg);
+  for (; i + 2 < n_steps; i += 2) {
+    const int key0 = key_begin + 32 * i;
+    load_step(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
     compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
-    if (!more) break;
-    key0 += 32;
-    more = key0 + 32 <= key_end;
-    if (more) load_step(b0, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
-    compute_step<DT>(b1, qf, acc, m, l, sl2, key0, lo, hi, kg);
-    if (!more) break;
-    key0 += 32;
+    load_step(b0, kc, vc, bt, key0 + 64, B, p.n_kv_heads, hk, n, kg);
+    compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, lo, hi, kg);
+  }
+  {
+    const int key0 = key_begin + 32 * i;
+    if (n_steps - i == 2) {
+      load_step(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
+      compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, lo, hi, kg);
+    } else {
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
+    }
   }
 
   l += __shfl_xor(l, 16);

@@ -3,8 +3,8 @@
 // A Dynamic SplitFuse pass mixes prompt chunks (dense, matrix-core bound) with one-token
 // generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  The two
 // kinds of work stress different parts of the chip, so the default launch puts both in
-// ONE grid: the first workgroups take prompt-chunk tiles, the rest take four
-// generation-row units each (one per wave), and the hardware overlaps them.  Separate
+// ONE grid: workgroups take either a prompt-chunk tile or eight generation-row units
+// (one per wave), and the hardware overlaps them.  Separate
 // kernels for each kind exist for profiling.
 #include "attn_decode_body.h"
 #include "attn_prefill_body.h"
@@ -12,7 +12,7 @@
 namespace fsf {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 64 * kPrefillWaves;
 constexpr int kUnitsPerGroup = kThreads / 64;  // generation-row units (waves) per workgroup
 
 // Prefill workgroups are numbered so that the tiles with the most keys to visit (the last
@@ -32,9 +32,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastP
                                                                  T* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) char lds0[kStageBytes];
   __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds2[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds3[kStageBytes];
   int tile, hq;
   prefill_block_to_work(p, f, blockIdx.x, tile, hq);
-  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1);
+  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1, (lds_char*)lds2,
+                        (lds_char*)lds3);
 }
 
 template <int DT, typename T>
@@ -56,6 +59,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
                                                                T* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) char lds0[kStageBytes];
   __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds2[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds3[kStageBytes];
   // Workgroup numbering alternates the two kinds of work for as long as both last, so that a
   // compute unit tends to hold one matrix-core-bound and one HBM-bound workgroup at a time.
   const int n_pre = f.n_pre_tiles * p.n_q_heads;
@@ -74,7 +79,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
   if (is_prefill) {  // uniform per workgroup
     int tile, hq;
     prefill_block_to_work(p, f, idx, tile, hq);
-    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1);
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1, (lds_char*)lds2,
+                        (lds_char*)lds3);
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;

@@ -4,7 +4,7 @@
 // earlier passes (paper Sec. 3.2 rule 1; Sec. 2 prompt processing).  Work is dense
 // contraction: 4*d flops per (row, visible key), so it belongs on the matrix cores.
 //
-// One workgroup (4 waves) owns a tile of 4*32*NQ consecutive rows of one sequence and one
+// One workgroup (8 waves) owns a tile of 8*32*NQ consecutive rows of one sequence and one
 // query head; wave w owns 32*NQ of them.  Keys are taken 64 at a time (never straddling a
 // cache block since block_size % 64 == 0), gathered through the block table:
 //   HBM/L2 -> LDS directly (global_load_lds, 16 bytes per lane, no registers, no VALU).
@@ -23,9 +23,9 @@
 //                               LDS read (ds_read_b64_tr_b16: a 16-lane group reads 4 keys x
 //                               16 d and each lane receives 4 keys of one d); B = P^T = the
 //                               lane's own probabilities, no cross-lane movement
-// Two LDS stages (separate arrays, so the compiler can tell the stage being filled from the
-// stage being read): the copy for step j+1 is in flight while step j is computed; one
-// barrier per step.
+// Four LDS stages (separate arrays, so the compiler can tell the stages being filled from
+// the stage being read): the copies for steps j+1..j+3 are in flight while step j is
+// computed, which hides the HBM/L2 latency of a gathered block; one barrier per step.
 #pragma once
 
 #include <math.h>
@@ -36,7 +36,9 @@
 
 namespace fsf {
 
-constexpr int NQ = kPrefillTileM / 128;  // 32-row q-tiles per wave
+constexpr int kPrefillWaves = 8;
+constexpr int NQ = kPrefillTileM / (32 * kPrefillWaves);  // 32-row q-tiles per wave
+constexpr int kStages = 4;                                // LDS stages (prefetch distance kStages - 1)
 constexpr int kKeysPerStep = 64;
 constexpr int kTileBytes = 64 * 256;         // one K or V tile: [64 keys][128 d] of 2-byte elements
 constexpr int kStageBytes = 2 * kTileBytes;  // K tile + V tile
@@ -48,22 +50,23 @@ typedef __attribute__((address_space(3))) char lds_char;
 typedef short v4s16 __attribute__((ext_vector_type(4)));
 
 // Start the asynchronous copy of one 64-key step (K and V tiles) into an LDS stage.
-// Each of the 4 waves copies 16 key rows: 4 instructions x (4 rows x 256 B) per tile.
+// Each of the 8 waves copies 8 key rows: 2 instructions x (4 rows x 256 B) per tile.
+constexpr int kCopyInstrPerStep = 2 * (64 / kPrefillWaves / 4);  // per wave: K + V
 template <typename T>
 __device__ __forceinline__ void stage_step(lds_char* stage, const T* __restrict__ kc,
                                            const T* __restrict__ vc, const int32_t* bt, int key0,
                                            int B, int n_kv_heads, int hk, int wave, int lane,
                                            int kv_last) {
   const int blk = key0 / B;
-  const int64_t phys = bt[blk];
+  const int64_t phys = load_uniform_i32(bt + blk);
   const int64_t base = ((phys * n_kv_heads + hk) * B + (key0 - blk * B)) * kHeadDim;
   const char* kb = reinterpret_cast<const char*>(kc + base);
   const char* vb = reinterpret_cast<const char*>(vc + base);
   const int max_row = kv_last - key0;  // >= 0: last row of this step that holds a written token
   const int pc = lane & 15;            // physical 16-byte chunk this lane fills
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row0 = wave * 16 + i * 4;  // first of the 4 rows this instruction fills (uniform)
+  for (int i = 0; i < 64 / kPrefillWaves / 4; ++i) {
+    const int row0 = wave * (64 / kPrefillWaves) + i * 4;  // first of the 4 rows this instruction fills (uniform)
     const int row = row0 + (lane >> 4);
     const int src_row = row < max_row ? row : max_row;
     const char* ksrc = kb + src_row * 256 + ((pc ^ (row & 7)) << 4);
@@ -257,13 +260,14 @@ __device__ __forceinline__ void prefill_compute_step(PrefillState& st, const lds
   __builtin_amdgcn_sched_group_barrier(0x008, NQ * kVAhead, 1);
 }
 
-// One workgroup of 256 threads: tile = index into the pass's prefill tiles, hq = query head.
-// lds0, lds1: two LDS stages of kStageBytes each (distinct arrays).
+// One workgroup of 32*kPrefillWaves threads: tile = index into the pass's prefill tiles,
+// hq = query head.  lds0..lds3: LDS stages of kStageBytes each (distinct arrays).
 template <int DT, typename T>
 __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
                                              const T* __restrict__ q, const T* __restrict__ kc,
                                              const T* __restrict__ vc, T* __restrict__ out, int tile,
-                                             int hq, lds_char* lds0, lds_char* lds1) {
+                                             int hq, lds_char* lds0, lds_char* lds1, lds_char* lds2,
+                                             lds_char* lds3) {
   using M = Mma<DT>;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -294,9 +298,6 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
     visible_range(c + w_i1 - 1, p.window, w_lo_max, w_hi_max);
   }
 
-  // the first copy goes out before anything else
-  stage_step(lds0, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, wave, lane, kv_last);
-
   // Q^T fragments (B operand): lane = (row l32 of q-tile, k-group hg), k-step t -> d chunk 2t+hg
   frag8 qf[NQ][8];
   int row_pos[NQ];  // absolute position of the lane's row per q-tile (rows past the tile: -1)
@@ -325,24 +326,40 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
   }
   const float sl2 = p.scale * 1.4426950408889634f;
 
-  // Steps alternate between the two stages; the loop is unrolled by two so that each half
-  // names its stage statically.
-  for (int key0 = key_begin; key0 <= hi_t; key0 += 2 * kKeysPerStep) {
+  // Copies run kStages-1 steps ahead.  The loop is unrolled by kStages so that every
+  // sub-iteration names its stages statically.  A wave waits for its own part of step j with
+  // vmcnt(newer copy instructions), the barrier extends that to the whole workgroup and also
+  // says that everyone is done reading the stage that step j+3 will overwrite.
+  lds_char* const stages[kStages] = {lds0, lds1, lds2, lds3};
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int k0 = key0 + half * kKeysPerStep;
+  for (int a = 0; a < kStages - 1; ++a)
+    if (key_begin + a * kKeysPerStep <= hi_t)
+      stage_step(stages[a], kc, vc, bt, key_begin + a * kKeysPerStep, B, p.n_kv_heads, hk, wave, lane, kv_last);
+
+  for (int key0 = key_begin; key0 <= hi_t; key0 += kStages * kKeysPerStep) {
+#pragma unroll
+    for (int sub = 0; sub < kStages; ++sub) {
+      const int k0 = key0 + sub * kKeysPerStep;
       if (k0 > hi_t) break;
-      lds_char* cur = half ? lds1 : lds0;
-      lds_char* nxt = half ? lds0 : lds1;
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's part of step k0 has landed
-      __syncthreads();                     // ... and everyone's; everyone is done reading `nxt`
-      if (k0 + kKeysPerStep <= hi_t)
-        stage_step(nxt, kc, vc, bt, k0 + kKeysPerStep, B, p.n_kv_heads, hk, wave, lane, kv_last);
+      // copy instructions of this wave issued after those of step k0
+      const int newer = min(kStages - 2, (hi_t - k0) / kKeysPerStep);
+      // (0x0070 = expcnt unused, lgkmcnt(0): this wave's LDS reads of the previous step are back)
+      if (newer >= 2)
+        __builtin_amdgcn_s_waitcnt(0x0070 | (2 * kCopyInstrPerStep));
+      else if (newer == 1)
+        __builtin_amdgcn_s_waitcnt(0x0070 | kCopyInstrPerStep);
+      else
+        __builtin_amdgcn_s_waitcnt(0x0070);
+      // bare barrier: a full __syncthreads() would also wait for the copies still in flight
+      __builtin_amdgcn_s_barrier();
+      if (k0 + (kStages - 1) * kKeysPerStep <= hi_t)
+        stage_step(stages[(sub + kStages - 1) % kStages], kc, vc, bt, k0 + (kStages - 1) * kKeysPerStep, B,
+                   p.n_kv_heads, hk, wave, lane, kv_last);
       // hidden from every row of this wave?
       if (!wave_live || k0 > w_hi_max || k0 + kKeysPerStep - 1 < w_lo_min) continue;
       const bool need_mask =
           k0 + kKeysPerStep - 1 > w_hi_min || k0 < w_lo_max || w_i1 - w_i0 < 32 * NQ;
-      prefill_compute_step<DT>(st, cur, qf, row_pos, k0, p.window, sl2, need_mask, l32, hg, lane);
+      prefill_compute_step<DT>(st, stages[sub], qf, row_pos, k0, p.window, sl2, need_mask, l32, hg, lane);
     }
   }
 

@@ -32,6 +32,18 @@ __device__ __forceinline__ int find_seq(const fsf_seq_desc* descs, int n_seqs, i
   return lo;
 }
 
+// Load an int32 whose address is the same for every lane of the wave through the scalar
+// cache.  Besides saving vector registers this keeps the load out of the vector-memory
+// counter, whose in-order waits would otherwise serialise it with bulk K/V traffic in flight.
+__device__ __forceinline__ int32_t load_uniform_i32(const int32_t* ptr) {
+  const uint64_t a = reinterpret_cast<uint64_t>(ptr);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+  const auto* cp = reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(
+      (static_cast<uint64_t>(hi) << 32) | lo);
+  return *cp;
+}
+
 // ---------------------------------------------------------------------------------------
 // Matrix-core path (bf16/f16, head_dim 128, block_size % 64 == 0, group <= 16).
 //
@@ -41,7 +53,7 @@ __device__ __forceinline__ int find_seq(const fsf_seq_desc* descs, int n_seqs, i
 //   prompt chunks   (n_new  > 1): "tiles" = (sequence, kPrefillTileM consecutive rows)
 // ---------------------------------------------------------------------------------------
 constexpr int kHeadDim = 128;
-constexpr int kPrefillTileM = 128;   // query rows per prefill workgroup
+constexpr int kPrefillTileM = 256;   // query rows per prefill workgroup (8 waves x 32 rows)
 constexpr int kMaxDecodeItemsExtra = 8192;  // items beyond one per sequence (bounds the workspace)
 
 // Visible key range of the row at position pos.
