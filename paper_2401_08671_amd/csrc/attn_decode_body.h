@@ -49,10 +49,10 @@ __device__ __forceinline__ void load_step(StepBuf& b, const T* __restrict__ kc,
   for (int tile = 0; tile < 2; ++tile)
 #pragma unroll
     for (int t = 0; t < 4; ++t)
-      b.k[tile][t] = load_frag8(kb + (tile * 16 + n) * kHeadDim + (4 * t + kg) * 8);
+      b.k[tile][t] = load_frag8_stream(kb + (tile * 16 + n) * kHeadDim + (4 * t + kg) * 8);
 #pragma unroll
   for (int e = 0; e < 8; ++e)
-    b.v[e] = load_frag8(vb + ((e >> 2) * 16 + 4 * kg + (e & 3)) * kHeadDim + n * 8);
+    b.v[e] = load_frag8_stream(vb + ((e >> 2) * 16 + 4 * kg + (e & 3)) * kHeadDim + n * 8);
 }
 
 template <int DT>

