@@ -105,7 +105,7 @@ def stream_bench(args):
     fsf.profile_enable(False)
     total_tokens = sum(t for t, _ in per_step)
     gpu_ms = sum(v[0] for v in prof.values())
-    fused_ms = prof["fused"][0]
+    fused_ms = prof["decode"][0] + prof["prefill"][0]      # the two attention kernels of every pass
     bytes_ = sum(w["decode_bytes"] + w["prefill_bytes"] for _, w in per_step if w)
     flops = sum(w["decode_flops"] + w["prefill_flops"] for _, w in per_step if w)
     t_hbm = sum((w["decode_bytes"] + w["prefill_bytes"]) / (HBM_PEAK_GBS * 1e9) for _, w in per_step if w)
@@ -125,11 +125,11 @@ def stream_bench(args):
                                "(log-normal prompts, Poisson(1.0) arrivals per pass), one layer; wall clock includes "
                                "host composition and descriptor upload",
                    "total_tokens": total_tokens, "kv_pool_blocks": run.num_blocks},
-        "roofline": ({"bound": "hbm", "kernel": "attn_fused_kernel", "achieved": bytes_ / (fused_ms * 1e-3) / 1e9,
+        "roofline": ({"bound": "hbm", "kernel": "attn_decode_kernel + attn_prefill_kernel", "achieved": bytes_ / (fused_ms * 1e-3) / 1e9,
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_ / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "traffic": None, "algorithmic_bytes_all_launches": bytes_, "total_launch_ms": fused_ms}
                      if hbm_bound else
-                     {"bound": "mfma", "kernel": "attn_fused_kernel", "achieved": flops / (fused_ms * 1e-3) / 1e12,
+                     {"bound": "mfma", "kernel": "attn_decode_kernel + attn_prefill_kernel", "achieved": flops / (fused_ms * 1e-3) / 1e12,
                       "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                       "frac": flops / (fused_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                       "algorithmic_flops_all_launches": flops, "total_launch_ms": fused_ms}),
@@ -189,21 +189,10 @@ def main():
     tokens_per_s = spec.n_tokens / (ms_per_step * 1e-3)
     phase_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in prof.items()}
 
-    # per-kind timings: the same pass with prompt-chunk and generation-row work as two kernels
-    fsf.profile_enable(True)
-    for _ in range(max(3, args.steps // 5)):
-        ds.step(separate=True)
-    torch.cuda.synchronize()
-    sep = fsf.profile_read()
-    fsf.profile_enable(False)
-    sep_ms = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in sep.items()}
-
-    # Dominant kernel of the timed region: the fused attention launch.  Its bound is whichever
-    # of (algorithmic bytes / HBM peak) and (algorithmic flops / MFMA peak) takes longer.
-    att_ms = phase_ms["fused"]
-    att_bytes = work["decode_bytes"] + work["prefill_bytes"]
-    att_flops = work["decode_flops"] + work["prefill_flops"]
-    hbm_bound = att_bytes / (HBM_PEAK_GBS * 1e9) >= att_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    # Dominant kernel of the timed region: generation-row attention (HBM bound) or prompt-chunk
+    # attention (matrix-core bound), whichever ran longer.
+    dec_ms, pre_ms = phase_ms["decode"], phase_ms["prefill"]
+    hbm_bound = dec_ms >= pre_ms
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"bench_cfg{args.config}_hbm_traffic.md")
     if os.path.exists(tpath):
@@ -211,16 +200,16 @@ def main():
             if ln.startswith("hbm_bytes_per_launch:"):
                 traffic = float(ln.split(":")[1])
     if hbm_bound:
-        achieved = att_bytes / (att_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "attn_fused_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        achieved = work["decode_bytes"] / (dec_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "attn_decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                    "algorithmic_bytes_per_launch": att_bytes, "avg_launch_ms": att_ms}
+                    "algorithmic_bytes_per_launch": work["decode_bytes"], "avg_launch_ms": dec_ms}
     else:
-        achieved = att_flops / (att_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "attn_fused_kernel", "achieved": achieved,
+        achieved = work["prefill_flops"] / (pre_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "attn_prefill_kernel", "achieved": achieved,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": traffic, "algorithmic_flops_per_launch": att_flops, "avg_launch_ms": att_ms}
-    dec_ms, pre_ms = sep_ms["decode"], sep_ms["prefill"]
+                    "traffic": traffic, "algorithmic_flops_per_launch": work["prefill_flops"],
+                    "avg_launch_ms": pre_ms}
     line = {
         "metric": "ragged SplitFuse attn tokens/s per step + % HBM/MFMA roofline, 1 GPU",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -236,14 +225,12 @@ def main():
         "step_roofline": {"algorithmic_bytes": work["total_bytes"],
                           "achieved_GBs": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9,
                           "frac_hbm": work["total_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "separate_kernels": {
-            "phases_ms": sep_ms,
-            "decode_only": {"bytes": work["decode_bytes"], "ms": dec_ms,
-                            "GBs": work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms else 0.0,
-                            "frac_hbm": work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if dec_ms else 0.0},
-            "prefill_only": {"flops": work["prefill_flops"], "ms": pre_ms,
-                             "TFLOPs": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 if pre_ms else 0.0,
-                             "frac_mfma": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if pre_ms else 0.0}},
+        "decode_only": {"bytes": work["decode_bytes"], "ms": dec_ms,
+                        "GBs": work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 if dec_ms else 0.0,
+                        "frac_hbm": work["decode_bytes"] / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if dec_ms else 0.0},
+        "prefill_only": {"flops": work["prefill_flops"], "ms": pre_ms,
+                         "TFLOPs": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 if pre_ms else 0.0,
+                         "frac_mfma": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if pre_ms else 0.0},
     }
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(ds, k0, v0)

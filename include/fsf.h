@@ -59,8 +59,8 @@ typedef enum { FSF_F32 = 0, FSF_BF16 = 1, FSF_F16 = 2 } fsf_dtype;
 
 /* fsf_attn_cfg.flags */
 #define FSF_FLAG_FORCE_GENERIC 1    /* run the generic fp32 kernel even where a fast path exists     */
-#define FSF_FLAG_SEPARATE_KERNELS 2 /* matrix-core path: launch prompt-chunk and generation-row work  */
-                                    /* as two kernels instead of one fused launch (for profiling)     */
+#define FSF_FLAG_FUSED_LAUNCH 2     /* matrix-core path: launch prompt-chunk and generation-row work  */
+                                    /* as one fused grid instead of two kernels                       */
 
 /* One sequence of the pass (paper Sec. 2: tokens processed now vs tokens in the cache). */
 typedef struct {

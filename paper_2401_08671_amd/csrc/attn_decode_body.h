@@ -118,7 +118,7 @@ __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f
 }
 
 // One wavefront: unit = item * n_kv_heads + kv head (item = a sequence's run of cache blocks).
-template <int DT, typename T>
+template <int DT, typename T, bool kDouble = true>
 __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
                                             const T* __restrict__ kc, const T* __restrict__ vc,
                                             T* __restrict__ out, int unit, int lane) {
@@ -156,6 +156,7 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   float m = -1e30f, l = 0.f;
   const float sl2 = p.scale * 1.4426950408889634f;
 
+  if constexpr (kDouble) {
   // Two register buffers.  The steady-state loop issues every load unconditionally, so the
   // compiler's in-order wait counts let step i compute while all of step i+1 is in flight.
   StepBuf b0, b1;
@@ -180,6 +181,14 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
     }
   }
 
+  } else {
+    // one register buffer: latency is hidden by the other waves of the compute unit
+    StepBuf b0;
+    for (int key0 = key_begin; key0 <= key_end; key0 += 32) {
+      load_step(b0, kc, vc, bt, key0, B, p.n_kv_heads, hk, n, kg);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
+    }
+  }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
   if (!col_live) return;

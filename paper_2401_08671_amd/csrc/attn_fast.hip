@@ -1,11 +1,11 @@
 // Kernels of the matrix-core attention path and their launchers.
 //
 // A Dynamic SplitFuse pass mixes prompt chunks (dense, matrix-core bound) with one-token
-// generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  The two
-// kinds of work stress different parts of the chip, so the default launch puts both in
-// ONE grid: workgroups take either a prompt-chunk tile or eight generation-row units
-// (one per wave), and the hardware overlaps them.  Separate
-// kernels for each kind exist for profiling.
+// generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  By default
+// each kind of work gets its own launch with the workgroup shape that suits it (512-thread
+// tiles with 128 KB of LDS; 64-thread streaming units).  Both kernels fill the register
+// file at two waves per SIMD, so they cannot share a compute unit and a single fused grid
+// (kept behind a flag: it saves one launch for tiny passes) measured no faster than the sum.
 #include "attn_decode_body.h"
 #include "attn_prefill_body.h"
 
@@ -40,15 +40,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastP
                         (lds_char*)lds3);
 }
 
+// One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
+// which measured best on the short-sequence batches.
 template <int DT, typename T>
-__global__ __launch_bounds__(kThreads, 2) void attn_decode_kernel(Pass p, FastPlan f,
+__global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
                                                                 const T* __restrict__ q,
                                                                 const T* __restrict__ kc,
                                                                 const T* __restrict__ vc,
                                                                 T* __restrict__ out) {
-  const int unit = blockIdx.x * kUnitsPerGroup + (threadIdx.x >> 6);
-  if (unit >= f.n_dec_items * p.n_kv_heads) return;
-  decode_unit<DT, T>(p, f, q, kc, vc, out, unit, threadIdx.x & 63);
+  decode_unit<DT, T>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x);
 }
 
 template <int DT, typename T>
@@ -112,8 +112,13 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
                               const void* v_cache, void* out, hipStream_t stream) {
   if (f.n_dec_items == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_DECODE, stream);
-  const unsigned grid = decode_groups(p, f);
-  FSF_LAUNCH(attn_decode_kernel, grid)
+  const unsigned grid = (unsigned)f.n_dec_items * p.n_kv_heads;
+  if (p.dtype == FSF_BF16)
+    attn_decode_kernel<FSF_BF16, bf16_t><<<grid, 64, 0, stream>>>(
+        p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out);
+  else
+    attn_decode_kernel<FSF_F16, f16_t><<<grid, 64, 0, stream>>>(
+        p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
   return hipGetLastError();
 }
 

@@ -202,11 +202,11 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.n_split_seqs = n_split;
 
   hipError_t e = fsf::launch_plan(p, f, stream);
-  if (cfg->flags & FSF_FLAG_SEPARATE_KERNELS) {
+  if (cfg->flags & FSF_FLAG_FUSED_LAUNCH) {
+    if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
+  } else {
     if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
     if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
-  } else {
-    if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
   }
   if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("FSF_LIB_PATH", os.path.join(_HERE, "libfsf.so"))
 FSF_OK, FSF_ERR_INVALID_ARG, FSF_ERR_UNSUPPORTED, FSF_ERR_WORKSPACE, FSF_ERR_NO_BLOCKS, FSF_ERR_HIP = 0, -1, -2, -3, -4, -5
 FSF_F32, FSF_BF16, FSF_F16 = 0, 1, 2
 FSF_FLAG_FORCE_GENERIC = 1
-FSF_FLAG_SEPARATE_KERNELS = 2
+FSF_FLAG_FUSED_LAUNCH = 2
 DTYPE_CODE = {"f32": FSF_F32, "bf16": FSF_BF16, "f16": FSF_F16,
               torch.float32: FSF_F32, torch.bfloat16: FSF_BF16, torch.float16: FSF_F16}
 

@@ -61,13 +61,13 @@ class DeviceStep:
         wl.fill_pool_(self.v_cache, spec.value_mult, spec.seed * 7 + 5)
         self.out = torch.zeros((T, Hq, d), dtype=tdt, device=device)
         self.cfg = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window, scale=spec.scale)
-        # same pass with prompt-chunk and generation-row work launched as two kernels (for per-kind timings)
-        self.cfg_separate = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window,
-                                         scale=spec.scale, flags=fsf.FSF_FLAG_SEPARATE_KERNELS)
+        # same pass with prompt-chunk and generation-row work in one fused grid
+        self.cfg_fused = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window,
+                                      scale=spec.scale, flags=fsf.FSF_FLAG_FUSED_LAUNCH)
         self.ws = fsf.alloc_workspace(self.cfg, self.batch.n_seqs, self.batch.n_tokens, self.batch.max_blocks, device)
 
-    def step(self, separate: bool = False):
-        cfg = self.cfg_separate if separate else self.cfg
+    def step(self, fused: bool = False):
+        cfg = self.cfg_fused if fused else self.cfg
         fsf.kv_append(cfg, self.k_new, self.v_new, self.k_cache, self.v_cache, self.batch)
         fsf.ragged_attention(cfg, self.q, self.k_cache, self.v_cache, self.batch, self.out, self.ws)
 

@@ -81,11 +81,21 @@ def test_prefill_long_chunk_over_long_prefix():
     check_step(Step(spec, poison="nan"), "prefill 700 rows over 1500 cached")
 
 
-def test_mixed_batch_order_independent():
-    """Chunks and generations interleaved in any order (the kernels may not assume chunks come first)."""
-    seqs = [(1, 77), (150, 10), (1, 640), (3, 0), (1, 0), (260, 300), (1, 129)]
+@pytest.mark.parametrize("flags", [0, fsf.FSF_FLAG_FUSED_LAUNCH])
+def test_mixed_batch_order_independent(flags):
+    """Chunks and generations interleaved in any order (the kernels may not assume chunks come first);
+    also through the single fused launch."""
+    seqs = [(1, 77), (150, 10), (1, 640), (3, 0), (1, 0), (260, 300), (1, 129), (700, 40)]
     spec = wl.BatchSpec("mix", 8, 8, 128, 64, "bf16", seqs, seed=15)
-    check_step(Step(spec, poison="nan"), "mixed order")
+    check_step(Step(spec, poison="nan"), f"mixed order flags={flags}", flags=flags)
+
+
+@pytest.mark.parametrize("k,nd", [(2, 24), (4, 40)])
+def test_benchmark_shapes_reduced_fused_launch(k, nd):
+    spec = wl.config(k, n_decodes=nd)
+    if k == 2:
+        spec.seqs = [(448, 0)] + spec.seqs[1:]
+    check_step(Step(spec), f"cfg{k} reduced, fused launch", flags=fsf.FSF_FLAG_FUSED_LAUNCH)
 
 
 def test_fast_path_matches_generic_kernel_within_tolerance():
