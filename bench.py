@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 
-def cpu_baseline(ds: DeviceStep, k_cache0: np.ndarray, v_cache0: np.ndarray, n_decode_sample: int = 48):
+def cpu_baseline(ds: DeviceStep, k_cache0: np.ndarray, v_cache0: np.ndarray, n_decode_sample: int = 256):
     """Time the fp64 oracle (as it stands) on every prompt chunk plus a seeded sample of generation rows."""
     from oracle import attention as oa
     try:
