@@ -44,6 +44,10 @@ def build(verbose: bool = True) -> str:
     if shutil.which("hipcc") is None:
         raise RuntimeError("hipcc not found on PATH")
     os.makedirs(OBJ_DIR, exist_ok=True)
+    # the prefill tile's instruction sequence is a generated header
+    r = subprocess.run([sys.executable, os.path.join(CSRC, "gen_prefill_sequence.py")], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gen_prefill_sequence.py failed:\n{r.stdout}\n{r.stderr}")
     srcs = sources()
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))

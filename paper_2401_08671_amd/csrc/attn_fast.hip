@@ -2,10 +2,11 @@
 //
 // A Dynamic SplitFuse pass mixes prompt chunks (dense, matrix-core bound) with one-token
 // generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  By default
-// each kind of work gets its own launch with the workgroup shape that suits it (512-thread
-// tiles with 128 KB of LDS; 64-thread streaming units).  Both kernels fill the register
-// file at two waves per SIMD, so they cannot share a compute unit and a single fused grid
-// (kept behind a flag: it saves one launch for tiny passes) measured no faster than the sum.
+// each kind of work gets its own launch with the workgroup shape that suits it (256-thread
+// tiles with 64 KB of LDS, two to a compute unit; 64-thread streaming units).  Both kernels
+// fill the register file at two waves per SIMD, so they cannot share a compute unit and a
+// single fused grid (kept behind a flag: it saves one launch for tiny passes) measured no
+// faster than the sum.
 #include "attn_decode_body.h"
 #include "attn_prefill_body.h"
 
@@ -30,14 +31,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastP
                                                                  const T* __restrict__ kc,
                                                                  const T* __restrict__ vc,
                                                                  T* __restrict__ out) {
-  __shared__ __attribute__((aligned(1024))) char lds0[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char lds2[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char lds3[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
   int tile, hq;
   prefill_block_to_work(p, f, blockIdx.x, tile, hq);
-  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1, (lds_char*)lds2,
-                        (lds_char*)lds3);
+  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds);
 }
 
 // One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
@@ -57,10 +54,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
                                                                const T* __restrict__ kc,
                                                                const T* __restrict__ vc,
                                                                T* __restrict__ out) {
-  __shared__ __attribute__((aligned(1024))) char lds0[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char lds1[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char lds2[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char lds3[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
   // Workgroup numbering spreads the prompt-chunk tiles evenly through the generation-row
   // groups (and vice versa).  A tile workgroup fills a compute unit, so at any moment a small,
   // steady share of the chip does matrix-core work while the rest keeps HBM saturated.
@@ -75,8 +69,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPla
   if (is_prefill) {  // uniform per workgroup
     int tile, hq;
     prefill_block_to_work(p, f, idx, tile, hq);
-    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds0, (lds_char*)lds1, (lds_char*)lds2,
-                        (lds_char*)lds3);
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds);
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;

@@ -4,273 +4,191 @@
 // earlier passes (paper Sec. 3.2 rule 1; Sec. 2 prompt processing).  Work is dense
 // contraction: 4*d flops per (row, visible key), so it belongs on the matrix cores.
 //
-// One workgroup (8 waves) owns a tile of 8*32*NQ consecutive rows of one sequence and one
-// query head; wave w owns 32*NQ of them.  Keys are taken 64 at a time (never straddling a
-// cache block since block_size % 64 == 0), gathered through the block table:
+// One workgroup (4 waves, one per SIMD) owns a tile of 128 consecutive rows of one sequence
+// and one query head; wave w owns 32 of them.  Two workgroups share a compute unit, so every
+// SIMD holds two waves that belong to different workgroups and never wait for each other:
+// while one does its softmax the other keeps the matrix core busy.  (Two waves of ONE
+// workgroup on a SIMD meet at the same barrier every step, start every step together and
+// then queue for the same unit; measured, that costs a third of the throughput.)
+//
+// Keys are taken 64 at a time ("step"; never straddling a cache block since block_size % 64
+// == 0), gathered through the block table:
 //   HBM/L2 -> LDS directly (global_load_lds, 16 bytes per lane, no registers, no VALU).
 //     Both tiles stay row-major [64 keys][128 d]; the lane -> global chunk mapping applies an
-//     XOR swizzle so the later reads are bank-conflict free:
-//       K: 16-byte chunk c of key row r sits at chunk c ^ (r & 7)
-//       V: 32-byte segment s of key row r sits at segment s ^ (r & 7)
+//     XOR swizzle so the later reads are bank-conflict free (64 banks):
+//       K: 16-byte chunk c of key row r sits at chunk c ^ (r & 15)
+//       V: 32-byte segment s of key row r sits at segment s ^ 2(r & 3)
 //     Rows past the sequence's last token are fetched from its last token instead: their
 //     scores are masked, and a finite stand-in keeps 0 * garbage out of the second product.
-//   S^T[key, row] = K . Q^T     A = K rows (ds_read_b128), B = Q^T held in registers
-//   running softmax per row in registers: a lane owns 32 scores of one row per q-tile, the
-//   max across the two half-waves is one xor-32 shuffle; the running reference is only
-//   raised when a maximum outgrows it by 2^8 (lazy rescale), so the accumulators are not
-//   touched by VALU code in the steady state
-//   O^T[d, row] += V^T . P^T    A = V^T read from the row-major V tile with the transposing
-//                               LDS read (ds_read_b64_tr_b16: a 16-lane group reads 4 keys x
-//                               16 d and each lane receives 4 keys of one d); B = P^T = the
-//                               lane's own probabilities, no cross-lane movement
-// Four LDS stages (separate arrays, so the compiler can tell the stages being filled from
-// the stage being read): the copies for steps j+1..j+3 are in flight while step j is
-// computed, which hides the HBM/L2 latency of a gathered block; one barrier per step.
+//   QK:  S^T[key, row] = K . Q^T   A = K rows (ds_read_b128), B = Q^T held in registers
+//   softmax per row in registers: a lane owns 32 scores of one row, the max across the two
+//     half-waves is one lane swap; the running reference is only raised when a maximum
+//     outgrows it by 2^8 (lazy rescale), so the accumulators are rarely touched by VALU code
+//   PV:  O^T[d, row] += V^T . P^T  A = V^T read from the row-major V tile with the transposing
+//                                 LDS read (ds_read_b64_tr_b16), B = P^T = the lane's own
+//                                 probabilities, no cross-lane movement
+// Iteration b of a wave:  hand-over, QK(b), then PV(b-1) with the softmax of step b between
+// its MFMAs ("PS"), so the vector ALU works in the shadow of the wave's own matrix work too.
+//
+// LDS (64 KB): two K slots and two V slots.  Hand-over b = wait for the wave's own copies of
+// K(b) and V(b-1), workgroup barrier, start K(b+1) and V(b) in the slots that iteration b-1
+// has finished reading.  One iteration (about 1 us) covers the latency of a gathered block.
 #pragma once
 
 #include <math.h>
 
+#include <type_traits>
+
+#include "attn_prefill_sequence.h"
 #include "fsf_internal.h"
 #include "mma.h"
 #include "numeric.h"
 
 namespace fsf {
 
-constexpr int kPrefillWaves = 8;
-constexpr int NQ = kPrefillTileM / (32 * kPrefillWaves);  // 32-row q-tiles per wave
-constexpr int kStages = 4;                                // LDS stages (prefetch distance kStages - 1)
+constexpr int kPrefillWaves = 4;
+static_assert(kPrefillTileM == 32 * kPrefillWaves, "one 32-row q-tile per wave");
+constexpr int kRing = 2;                     // LDS slots per tile ring (K and V each)
 constexpr int kKeysPerStep = 64;
 constexpr int kTileBytes = 64 * 256;         // one K or V tile: [64 keys][128 d] of 2-byte elements
-constexpr int kStageBytes = 2 * kTileBytes;  // K tile + V tile
-constexpr int kFragAhead = 4;                // K fragments in flight from LDS (k-steps)
-constexpr int kVAhead = 4;                   // V^T fragments in flight from LDS
+constexpr int kPrefillLdsBytes = 2 * kRing * kTileBytes;  // K slots 0, 1, then V slots 0, 1
+constexpr int kVRingBase = kRing * kTileBytes;            // byte offset of V slot 0
 constexpr float kLazyLog2 = 8.f;             // running-max slack before accumulators are rescaled
+static_assert(kPrefillLdsBytes <= 65536, "LDS reads reach every slot with a 16-bit offset");
+static_assert(kLazyLog2 == 8.f, "the PS sequence compares against the literal 0x41000000");
 
 typedef __attribute__((address_space(3))) char lds_char;
-typedef short v4s16 __attribute__((ext_vector_type(4)));
-
-// Start the asynchronous copy of one 64-key step (K and V tiles) into an LDS stage.
-// Each of the 8 waves copies 8 key rows: 2 instructions x (4 rows x 256 B) per tile.
-constexpr int kCopyInstrPerStep = 2 * (64 / kPrefillWaves / 4);  // per wave: K + V
-template <typename T>
-__device__ __forceinline__ void stage_step(lds_char* stage, const T* __restrict__ kc,
-                                           const T* __restrict__ vc, const int32_t* bt, int key0,
-                                           int B, int n_kv_heads, int hk, int wave, int lane,
-                                           int kv_last) {
-  const int blk = key0 / B;
-  const int64_t phys = load_uniform_i32(bt + blk);
-  const int64_t base = ((phys * n_kv_heads + hk) * B + (key0 - blk * B)) * kHeadDim;
-  const char* kb = reinterpret_cast<const char*>(kc + base);
-  const char* vb = reinterpret_cast<const char*>(vc + base);
-  const int max_row = kv_last - key0;  // >= 0: last row of this step that holds a written token
-  const int pc = lane & 15;            // physical 16-byte chunk this lane fills
-#pragma unroll
-  for (int i = 0; i < 64 / kPrefillWaves / 4; ++i) {
-    const int row0 = wave * (64 / kPrefillWaves) + i * 4;  // first of the 4 rows this instruction fills (uniform)
-    const int row = row0 + (lane >> 4);
-    const int src_row = row < max_row ? row : max_row;
-    const char* ksrc = kb + src_row * 256 + ((pc ^ (row & 7)) << 4);
-    const char* vsrc = vb + src_row * 256 + ((pc ^ ((row & 7) << 1)) << 4);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ksrc,
-                                     (__attribute__((address_space(3))) void*)(stage + row0 * 256),
-                                     16, 0, 0);
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)vsrc,
-        (__attribute__((address_space(3))) void*)(stage + kTileBytes + row0 * 256), 16, 0, 0);
-  }
-}
-
-// byte offset of 16-byte chunk `chunk` of key row `key` in the K tile
-__device__ __forceinline__ int k_lds_off(int key, int chunk) {
-  return key * 256 + ((chunk ^ (key & 7)) << 4);
-}
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ frag8 lds_load_frag8(const lds_char* ptr) {
-  const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(ptr);
-  return frag8{{v[0], v[1], v[2], v[3]}};
-}
-
-// 8 storage elements V[keys][d] for the A operand of O^T += V^T P^T: lane (d = mt*32 + l32,
-// k-group hg), k-step u.  Slots 0..3 are keys 16u + 4hg + 0..3, slots 4..7 keys 16u + 8 + 4hg
-// + 0..3 (the order in which the first product leaves the probabilities in registers).
-// ds_read_b64_tr_b16 works on 16-lane groups: the group's lanes point at 4 key rows x 4
-// 8-byte units (lane s: row s/4, unit s%4) and lane i receives, for d = unit_base + i, the
-// 4 keys.  Group g of the wave covers d half (g & 1) and k-group g >> 1.
-__device__ __forceinline__ frag8 load_vt_frag(const lds_char* vtile, int u, int mt, int lane) {
-  const int s = lane & 15, g = lane >> 4;
-  const int hg = g >> 1, dhalf = g & 1;
-  const int seg = 2 * mt + dhalf;  // logical 32-byte segment of the row
-  frag8 f;
+// Asynchronous copy of the K (or V) tile of one 64-key step into an LDS slot
+// (global_load_lds: 16 bytes per lane, HBM/L2 -> LDS without passing registers).
+// Each of the 4 waves copies 16 key rows with 4 instructions (4 rows x 256 B each).  The
+// lane -> source-chunk mapping (which applies the swizzle) does not change from step to
+// step, so a lane keeps its byte offset inside a (block, head) tile in a register and a
+// copy costs a handful of scalar instructions for the tile's base address.
+constexpr int kCopyInstrPerTile = 64 / kPrefillWaves / 4;
+struct TileCopy {
+  uint32_t lane_off[kCopyInstrPerTile];  // row*256 + swizzled chunk*16 of the lane's 16 bytes
+  uint32_t lds_off[kCopyInstrPerTile];   // first byte the instruction fills inside a slot (uniform)
+  template <bool kIsV>
+  __device__ __forceinline__ void init(int wave, int lane) {
+    const int pc = lane & 15;  // physical 16-byte chunk this lane fills
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int row = 16 * u + 8 * r + 4 * hg + (s >> 2);
-    const int off = row * 256 + ((seg ^ (row & 7)) << 5) + ((s & 3) << 3);
-    const v4s16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (v4s16 __attribute__((address_space(3)))*)(vtile + off));
-    const uint2 w = __builtin_bit_cast(uint2, v);
-    f.w[2 * r] = w.x;
-    f.w[2 * r + 1] = w.y;
+    for (int i = 0; i < kCopyInstrPerTile; ++i) {
+      const int row0 = wave * (64 / kPrefillWaves) + i * 4;
+      const int row = row0 + (lane >> 4);
+      const int swz = kIsV ? ((row & 3) << 2) : (row & 15);
+      lane_off[i] = row * 256 + ((pc ^ swz) << 4);
+      lds_off[i] = row0 * 256;
+    }
   }
-  return f;
-}
-
-struct PrefillState {
-  f32x16_t acc[4][NQ];
-  float m_run[NQ], l_run[NQ];
+  // tile_base: address of key row 0 of the step in the cache; slot: LDS byte address of the slot;
+  // max_row: last row of the step that holds a written token (>= 0).  Rows past it are fetched
+  // from row max_row instead.
+  template <bool kClamp>
+  __device__ __forceinline__ void issue(const char* tile_base, uint32_t slot, int max_row) const {
+    // both are the same in all lanes; say so (the compiler cannot always tell)
+    const uint64_t tb = reinterpret_cast<uint64_t>(tile_base);
+    const uint64_t base = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(tb >> 32)) << 32) |
+                          (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)tb);
+#pragma unroll
+    for (int i = 0; i < kCopyInstrPerTile; ++i) {
+      uint32_t off = lane_off[i];
+      if (kClamp) {  // only the last step of a sequence needs it
+        const uint32_t row = off >> 8;
+        off = ((row < (uint32_t)max_row ? row : (uint32_t)max_row) << 8) | (off & 255u);
+      }
+      // M0 = LDS address of lane 0's 16 bytes; lane l lands 16*l bytes further
+      asm volatile("s_mov_b32 m0, %[m]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[v], %[s]\n\t"
+                   :
+                   : [m] "s"(__builtin_amdgcn_readfirstlane(slot + lds_off[i])), [v] "v"(off), [s] "s"(base)
+                   : "memory");
+    }
+  }
 };
 
-// One 64-key step for one wave, reading the tiles of `stage`.
-template <int DT>
-__device__ __forceinline__ void prefill_compute_step(PrefillState& st, const lds_char* stage,
-                                                     const frag8 (&qf)[NQ][8],
-                                                     const int (&row_pos)[NQ], int key0, int window,
-                                                     float sl2, bool need_mask, int l32, int hg,
-                                                     int lane) {
-  using M = Mma<DT>;
-  const lds_char* kl = stage;
-  const lds_char* vl = stage + kTileBytes;
+// ---------------------------------------------------------------------------------------
+// The whole walk of a tile over its steps is ONE fixed instruction sequence: LDS reads run a
+// few fragments ahead of the MFMAs that consume them, every wait names exactly the reads it
+// needs, the softmax of a step sits between the MFMAs of the PV before it, and a hand-over
+// costs some twenty scalar instructions.  (Left to the compiler, the same loop issues two to
+// three times as many instructions, and pinning parts of it makes its register allocation
+// spill.)  Plain code around it sets the registers up and stores the result.
+//
+// Iteration b (b = 0 .. n_steps; both P buffers and both slot pairs alternate with b & 1):
+//   hand-over b, QK(b) if step b is active for the wave, PV(b-1) if step b-1 is,
+//   softmax(b) -> P buffer (b+1) & 1, with the scores of hidden keys set to -inf first where
+//   the step needs it.
+// Steady pairs: from an even b with  fast_lo <= b, b+1 <= fast_hi  the wave runs pairs of
+// iterations without any test: both steps active, nothing masked, every copy whole.  There
+// PV(b-1) and softmax(b) are one interleaved sequence (PS): row maximum (v_max3 chains,
+// v_permlane32_swap for the other half-wave), lazy raise of the reference,
+// p = 2^(s*scale*log2e - m), row sum, P^T register r = pack(p[2r], p[2r+1]); where the
+// reference was raised the accumulators are scaled once the PV has landed.
+//
+// LDS addressing.  A read is  per-lane register + 16-bit immediate; the swizzles only touch
+// address bits a lane fixes once:
+//   K tile: lane (l32, hg) reads row kt*32 + l32, chunk 2t + hg for k-step t:
+//     ka[t] = l32*256 + ((2t + hg) ^ (l32 & 15))*16, immediate = slot + kt*8192.  A
+//     ds_read_b128 serves 16 lanes per clock from 64 banks, and 16 consecutive rows at one
+//     logical chunk land on 16 different physical chunks.
+//   V tile: ds_read_b64_tr_b16 works on 16-lane groups: the group's lanes point at 4 key rows
+//     x 4 8-byte units (lane s: row s/4, unit s%4) and lane i receives, for d = unit_base + i,
+//     the 4 keys.  Group g covers d half (g & 1) and key group hg = g >> 1.  For the A
+//     operand of O^T += V^T P^T (lane d = mt*32 + l32, k-step u) slots 0..3 are keys 16u + 4hg
+//     + 0..3 and slots 4..7 keys 16u + 8 + 4hg + 0..3 -- the order in which the first product
+//     leaves the probabilities in registers:  va[mt] = V ring + x*256 + (2(mt ^ (x&3)) +
+//     (g&1))*32 + (s&3)*8 with x = 4hg + s/4, immediate = slot + (16u + 8r)*256.  The read
+//     serves 32 lanes per clock: 4 rows x 2 segments, spread over all 64 banks.
+//
+// Registers of the sequence:
+//   v28 v29 temporaries of a clamped copy      v32 rhi - 4hg, v33 rlo - 4hg of the lane's row
+//   (visible keys [rlo, rhi]; score register j of a lane is key 32(j/16) + 8((j%16)/4) + j%4 +
+//   4hg of the step), v34 v35 the same minus the step's first key      v36..v39 V copy lane
+//   offsets   v40 m  v41 l  v42 rescale factor  v43 scale*log2e   v44..v47 K copy lane offsets
+//   v48 -inf   v50..v53 va   v54..v61 ka   v62..v93 Q^T fragments (k-step t: 4t..4t+3)
+//   v94..v157 O^T (four 32x32 accumulators)   v158..v189 S^T (two 32x32 accumulators)
+//   v190..v205, v206..v221 P^T buffers 0, 1     v222..v231 softmax temporaries
+//   v232..v255 K / V^T fragments in flight
+//   s60 n_steps   s61 s62 first, last active step of the wave   s63 s64 first, last step that
+//   needs no mask   s65 s66 fast_lo, fast_hi   s67 last step with all 64 rows written   s68 last
+//   written key - first key of the tile   s69 first key of the tile   s70 window   s71 first
+//   step's index in the sequence (key/64)   s72 steps per cache block - 1   s73 log2 of steps
+//   per block   s[74:75] block table of the sequence   s[76:77] K base of this head   s[78:79]
+//   V base   s80 bytes per cache block   s81 LDS address of the wave's first copy row
+//   s82..s89, s92, s93, s95, s96 temporaries   s[90:91] offset of step b's tiles   s94 physical
+//   block of step b+1   s97 b
+// Every block of MFMAs ends with the idle cycles the matrix core needs before vector code may
+// read what the last MFMA wrote.
+// The sequence itself (macro FSF_TILE_SEQUENCE, some 2000 instructions) is written by
+// gen_prefill_sequence.py into attn_prefill_sequence.h; the build runs the generator first.
+// ---------------------------------------------------------------------------------------
+#define FSF_FRAG_REGS                                                                          \
+  "v232", "v233", "v234", "v235", "v236", "v237", "v238", "v239", "v240", "v241", "v242",      \
+      "v243", "v244", "v245", "v246", "v247", "v248", "v249", "v250", "v251", "v252", "v253",  \
+      "v254", "v255"
+#define FSF_SOFTMAX_TMP_REGS "v222", "v223", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "v231"
 
-  // ---- S^T = K . Q^T ; K fragments are fetched from LDS kFragAhead k-steps ahead of their use
-  f32x16_t sc[2][NQ];
-#pragma unroll
-  for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sc[kt][qt][r] = 0.f;
-  {
-    frag8 kf[kFragAhead][2];
-#pragma unroll
-    for (int t = 0; t < kFragAhead; ++t)
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-        kf[t][kt] = lds_load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * t + hg));
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt)
-          sc[kt][qt] = M::mfma32(kf[t % kFragAhead][kt], qf[qt][t], sc[kt][qt]);
-        if (t + kFragAhead < 8)
-          kf[t % kFragAhead][kt] =
-              lds_load_frag8(kl + k_lds_off(kt * 32 + l32, 2 * (t + kFragAhead) + hg));
-      }
-    }
-    // pin the issue order: kFragAhead k-steps of LDS reads up front, then reads and MFMAs in turn
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragAhead, 0);
-#pragma unroll
-    for (int t = 0; t < 8 - kFragAhead; ++t) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ * kFragAhead, 0);
-  }
+typedef float f32x32_t __attribute__((ext_vector_type(32)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
 
-  // ---- mask, row maxima, and the (rare) raise of the running reference
-  if (need_mask) {
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      int rlo, rhi;
-      visible_range(row_pos[qt], window, rlo, rhi);  // rows past the tile: rhi = -1, nothing visible
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * hg + (r & 3);
-          if (key < rlo || key > rhi) sc[kt][qt][r] = -INFINITY;
-        }
-    }
-  }
-  // Lazy rescale: the running reference m_run only has to bound the scores from above
-  // loosely.  It is raised (and acc, l rescaled) only when a row's maximum outgrows it by
-  // more than 2^kLazyLog2, so probabilities stay <= 2^kLazyLog2.
-  float m_cand[NQ];
-  bool raise = false;
-#pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kt][qt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    m_cand[qt] = fmaxf(st.m_run[qt], mx * sl2);
-    raise |= m_cand[qt] - st.m_run[qt] > kLazyLog2;
-  }
-  if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-      const float m_new = (m_cand[qt] - st.m_run[qt] > kLazyLog2) ? m_cand[qt] : st.m_run[qt];
-      const float corr = fast_exp2(st.m_run[qt] - m_new);
-      st.m_run[qt] = m_new;
-      st.l_run[qt] *= corr;
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.acc[mt][qt][r] *= corr;
-    }
-  }
-
-  // ---- probabilities and P^T fragments
-  frag8 pfr[NQ][4];
-#pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    const float m_ref = st.m_run[qt];
-    float sum = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pr = fast_exp2(fmaf(sc[kt][qt][r], sl2, -m_ref));
-        sc[kt][qt][r] = pr;
-        sum += pr;
-      }
-    st.l_run[qt] += sum;
-    // k-step u of the second product covers keys 16u..16u+15: registers 8(u%2)..+7 of tile u/2
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj)
-        pfr[qt][u].w[jj] = M::pack2(sc[u >> 1][qt][8 * (u & 1) + 2 * jj],
-                                    sc[u >> 1][qt][8 * (u & 1) + 2 * jj + 1]);
-  }
-
-  // ---- O^T += V^T . P^T ; V^T fragments come from LDS kVAhead MFMAs ahead of their use
-  frag8 vf[kVAhead];  // rolling window over i = u*4 + mt
-#pragma unroll
-  for (int i = 0; i < kVAhead; ++i) vf[i] = load_vt_frag(vl, i >> 2, i & 3, lane);
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int u = i >> 2, mt = i & 3;
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt)
-      st.acc[mt][qt] = M::mfma32(vf[i % kVAhead], pfr[qt][u], st.acc[mt][qt]);
-    if (i + kVAhead < 16)
-      vf[i % kVAhead] = load_vt_frag(vl, (i + kVAhead) >> 2, (i + kVAhead) & 3, lane);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x100, 2 * kVAhead, 1);
-#pragma unroll
-  for (int i = 0; i < 16 - kVAhead; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, NQ, 1);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, NQ * kVAhead, 1);
-}
-
-// One workgroup of 32*kPrefillWaves threads: tile = index into the pass's prefill tiles,
-// hq = query head.  lds0..lds3: LDS stages of kStageBytes each (distinct arrays).
+// One workgroup of 64*kPrefillWaves threads: tile = index into the pass's prefill tiles,
+// hq = query head, lds = kPrefillLdsBytes of LDS.
 template <int DT, typename T>
 __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
                                              const T* __restrict__ q, const T* __restrict__ kc,
                                              const T* __restrict__ vc, T* __restrict__ out, int tile,
-                                             int hq, lds_char* lds0, lds_char* lds1, lds_char* lds2,
-                                             lds_char* lds3) {
+                                             int hq, lds_char* lds) {
   using M = Mma<DT>;
+  // values that are the same in every lane are told so (the compiler cannot always tell)
+  auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane(x); };
+  auto uni64 = [&](uint64_t x) { return ((uint64_t)uni((uint32_t)(x >> 32)) << 32) | uni((uint32_t)x); };
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  const int wave = uni(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hg = lane >> 5;
   const int hk = hq / p.group;
   const int s = f.pre_tile_seq[tile];  // written by the planning kernel
@@ -279,109 +197,170 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
   const int n_new = sd.n_new, c = sd.n_cached;
   const int i0 = (tile - f.pre_tile_start[s]) * kPrefillTileM;  // first row of the tile
   const int i1 = min(i0 + kPrefillTileM, n_new);                // one past its last row
-  const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
 
   // key range of the whole tile (all waves walk the same steps: they share the LDS tiles)
   int lo_t, hi_t, tmp;
   visible_range(c + i0, p.window, lo_t, tmp);
   visible_range(c + i1 - 1, p.window, tmp, hi_t);
   const int key_begin = lo_t & ~(kKeysPerStep - 1);
+  const int n_steps = (hi_t - key_begin) / kKeysPerStep + 1;  // >= 1
   const int kv_last = c + n_new - 1;  // last cache position this sequence has written
+  const int whole_hi = (kv_last - key_begin - (kKeysPerStep - 1)) >= 0
+                           ? (kv_last - key_begin - (kKeysPerStep - 1)) / kKeysPerStep
+                           : -1;  // last step with all 64 rows written
 
-  // this wave's rows
-  const int w_i0 = i0 + wave * 32 * NQ;
-  const int w_i1 = min(w_i0 + 32 * NQ, i1);  // may be <= w_i0: wave has no live row
-  const bool wave_live = w_i0 < i1;
-  int w_lo_min = 0, w_lo_max = 0, w_hi_min = 0, w_hi_max = -1;
-  if (wave_live) {
+  // this wave's rows, and the steps that hold a key visible to one of them
+  const int w_i0 = i0 + wave * 32;
+  const int w_i1 = min(w_i0 + 32, i1);  // may be <= w_i0: wave has no live row
+  int j_first = 0, j_last = -1;          // active steps
+  int nomask_lo = 0, nomask_hi = -1;     // steps none of whose scores is hidden from any row
+  if (w_i0 < i1) {
+    int w_lo_min, w_lo_max, w_hi_min, w_hi_max;
     visible_range(c + w_i0, p.window, w_lo_min, w_hi_min);
     visible_range(c + w_i1 - 1, p.window, w_lo_max, w_hi_max);
+    j_first = (w_lo_min - key_begin) / kKeysPerStep;
+    j_last = (w_hi_max - key_begin) / kKeysPerStep;
+    if (w_i1 - w_i0 == 32) {
+      nomask_lo = (w_lo_max - key_begin + kKeysPerStep - 1) / kKeysPerStep;
+      nomask_hi = (w_hi_min - key_begin - (kKeysPerStep - 1)) >= 0
+                      ? (w_hi_min - key_begin - (kKeysPerStep - 1)) / kKeysPerStep
+                      : -1;
+    }
   }
-
-  // Q^T fragments (B operand): lane = (row l32 of q-tile, k-group hg), k-step t -> d chunk 2t+hg
-  frag8 qf[NQ][8];
-  int row_pos[NQ];  // absolute position of the lane's row per q-tile (rows past the tile: -1)
-#pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    const int i = w_i0 + qt * 32 + l32;
-    const bool live = i < i1;
-    row_pos[qt] = live ? c + i : -1;
-    const int ic = live ? i : (i1 - 1);
-    const T* qrow = q + ((int64_t)(sd.q_offset + ic) * p.n_q_heads + hq) * kHeadDim;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) qf[qt][t] = load_frag8(qrow + (2 * t + hg) * 8);
-  }
-
-  PrefillState st;
-#pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-    for (int qt = 0; qt < NQ; ++qt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st.acc[mt][qt][r] = 0.f;
-#pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    st.m_run[qt] = -1e30f;
-    st.l_run[qt] = 0.f;
-  }
-  const float sl2 = p.scale * 1.4426950408889634f;
-
-  // Copies run kStages-1 steps ahead.  The loop is unrolled by kStages so that every
-  // sub-iteration names its stages statically.  A wave waits for its own part of step j with
-  // vmcnt(newer copy instructions), the barrier extends that to the whole workgroup and also
-  // says that everyone is done reading the stage that step j+3 will overwrite.
-  lds_char* const stages[kStages] = {lds0, lds1, lds2, lds3};
-#pragma unroll
-  for (int a = 0; a < kStages - 1; ++a)
-    if (key_begin + a * kKeysPerStep <= hi_t)
-      stage_step(stages[a], kc, vc, bt, key_begin + a * kKeysPerStep, B, p.n_kv_heads, hk, wave, lane, kv_last);
-
-  for (int key0 = key_begin; key0 <= hi_t; key0 += kStages * kKeysPerStep) {
-#pragma unroll
-    for (int sub = 0; sub < kStages; ++sub) {
-      const int k0 = key0 + sub * kKeysPerStep;
-      if (k0 > hi_t) break;
-      // copy instructions of this wave issued after those of step k0
-      const int newer = min(kStages - 2, (hi_t - k0) / kKeysPerStep);
-      // (0x0070 = expcnt unused, lgkmcnt(0): this wave's LDS reads of the previous step are back)
-      if (newer >= 2)
-        __builtin_amdgcn_s_waitcnt(0x0070 | (2 * kCopyInstrPerStep));
-      else if (newer == 1)
-        __builtin_amdgcn_s_waitcnt(0x0070 | kCopyInstrPerStep);
-      else
-        __builtin_amdgcn_s_waitcnt(0x0070);
-      // bare barrier: a full __syncthreads() would also wait for the copies still in flight
-      __builtin_amdgcn_s_barrier();
-      if (k0 + (kStages - 1) * kKeysPerStep <= hi_t)
-        stage_step(stages[(sub + kStages - 1) % kStages], kc, vc, bt, k0 + (kStages - 1) * kKeysPerStep, B,
-                   p.n_kv_heads, hk, wave, lane, kv_last);
-      // hidden from every row of this wave?
-      if (!wave_live || k0 > w_hi_max || k0 + kKeysPerStep - 1 < w_lo_min) continue;
-      const bool need_mask =
-          k0 + kKeysPerStep - 1 > w_hi_min || k0 < w_lo_max || w_i1 - w_i0 < 32 * NQ;
-      prefill_compute_step<DT>(st, stages[sub], qf, row_pos, k0, p.window, sl2, need_mask, l32, hg, lane);
+  // Steady iterations b: steps b-1 and b active, step b unmasked, K(b+1) and V(b) whole, step
+  // b+2 exists; an even number of them starting at an even b.
+  int fast_lo = 0, fast_hi = -1;
+  {
+    const int lo = (max(max(j_first + 1, nomask_lo), 0) + 1) & ~1;
+    const int hi = min(min(nomask_hi, j_last), min(n_steps - 3, whole_hi - 1));
+    if (hi - lo + 1 >= 2) {
+      fast_lo = lo;
+      fast_hi = lo + ((hi - lo + 1) & ~1) - 1;
     }
   }
 
-  // ---- normalise and store: acc[mt][qt][r] is column d = 32mt + 8(r/4) + 4hg + r%4 of the lane's row
+  // Q^T fragments (B operand): lane = (row l32, k-group hg), k-step t -> d chunk 2t+hg
+  u32x32 qf;
+  int row_pos;  // absolute position of the lane's row (rows past the tile: -1)
+  {
+    const int i = w_i0 + l32;
+    const bool live = i < i1;
+    row_pos = live ? c + i : -1;
+    const int ic = live ? i : (i1 - 1);
+    const T* qrow = q + ((int64_t)(sd.q_offset + ic) * p.n_q_heads + hq) * kHeadDim;
 #pragma unroll
-  for (int qt = 0; qt < NQ; ++qt) {
-    float l = st.l_run[qt];
-    l += __shfl_xor(l, 32);
-    if (row_pos[qt] < 0) continue;
-    const float inv = 1.f / l;
-    const int i = row_pos[qt] - c;
-    T* orow = out + ((int64_t)(sd.q_offset + i) * p.n_q_heads + hq) * kHeadDim;
+    for (int t = 0; t < 8; ++t) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(qrow + (2 * t + hg) * 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qf[4 * t + e] = v[e];
+    }
+  }
+  int rlo, rhi;
+  visible_range(row_pos, p.window, rlo, rhi);  // rows past the tile: rhi = -1, nothing visible
+  i32x4 thr = {rhi - 4 * hg, rlo - 4 * hg, 0, 0};
+
+  u32x4 va;
+  u32x8 ka;
+  {
+    const int lds0 = (int)(uintptr_t)lds;  // LDS byte address of K slot 0
+    const int g = lane >> 4, sl = lane & 15;
+    const int x = 4 * (g >> 1) + (sl >> 2);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) ka[t] = lds0 + l32 * 256 + (((2 * t + hg) ^ (l32 & 15)) << 4);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        uint2 w;
-        w.x = M::pack2(st.acc[mt][qt][4 * rq] * inv, st.acc[mt][qt][4 * rq + 1] * inv);
-        w.y = M::pack2(st.acc[mt][qt][4 * rq + 2] * inv, st.acc[mt][qt][4 * rq + 3] * inv);
-        *reinterpret_cast<uint2*>(orow + 32 * mt + 8 * rq + 4 * hg) = w;
-      }
+      va[mt] = lds0 + kVRingBase + x * 256 + ((2 * (mt ^ (x & 3)) + (g & 1)) << 5) + ((sl & 3) << 3);
   }
+
+  // ---- copies.  Step j of the tile covers keys key_begin + 64 j .. + 63, which lie in cache block
+  // (step0 + j) / spb of the sequence (spb = 64-key steps per block, a power of two).
+  TileCopy kcopy, vcopy;
+  kcopy.init<false>(wave, lane);
+  vcopy.init<true>(wave, lane);
+  const uint32_t lds_k0 = (uint32_t)(uintptr_t)lds;
+  constexpr uint32_t kRowBytes = kHeadDim * sizeof(T);
+  const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
+  const uint32_t step0 = (uint32_t)key_begin / kKeysPerStep;
+  const uint32_t spb = (uint32_t)B / kKeysPerStep;
+  const uint32_t spb_shift = __builtin_ctz(spb);
+  const uint64_t blk_bytes = (uint64_t)p.n_kv_heads * B * kRowBytes;  // one cache block, all heads (< 4 GiB)
+  const char* const k_head = reinterpret_cast<const char*>(kc) + (uint64_t)hk * B * kRowBytes;
+  const char* const v_head = reinterpret_cast<const char*>(vc) + (uint64_t)hk * B * kRowBytes;
+  // K(0) goes out before the first hand-over; the sequence continues from there with
+  //   off_prev   byte offset (block and position inside it, head excluded) of step b's tiles
+  //   phys_next  physical block of step b+1, fetched one hand-over earlier
+  uint64_t off_prev = (uint64_t)(uint32_t)load_uniform_i32(bt + (step0 >> spb_shift)) * blk_bytes +
+                      (step0 & (spb - 1)) * (kKeysPerStep * kRowBytes);
+  uint32_t phys_next = n_steps > 1 ? (uint32_t)load_uniform_i32(bt + ((step0 + 1) >> spb_shift)) : 0u;
+  if (whole_hi < 0) kcopy.issue<true>(k_head + off_prev, lds_k0, kv_last - key_begin);
+  else kcopy.issue<false>(k_head + off_prev, lds_k0, 0);
+
+  // ---- the walk
+  f32x32_t acc01, acc23, sc;
+  u32x16 p0, p1;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    acc01[r] = 0.f;
+    acc23[r] = 0.f;
+    sc[r] = 0.f;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    p0[r] = 0u;
+    p1[r] = 0u;
+  }
+  f32x4_t mlcs = {-1e30f, 0.f, 0.f, p.scale * 1.4426950408889634f};  // m, l, rescale factor, scale*log2e
+  u32x4 koff, voff;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    koff[i] = kcopy.lane_off[i];
+    voff[i] = vcopy.lane_off[i];
+  }
+  const u32x4 s60 = {uni(n_steps), uni(j_first), uni(j_last), uni(nomask_lo)};
+  const u32x4 s64 = {uni(nomask_hi), uni(fast_lo), uni(fast_hi), uni(whole_hi)};
+  const u32x4 s68 = {uni(kv_last - key_begin), uni(key_begin), uni(p.window), uni(step0)};
+  const u32x2 s72 = {uni(spb - 1), uni(spb_shift)};
+  const u32x2 s80 = {uni((uint32_t)blk_bytes), uni(lds_k0 + kcopy.lds_off[0])};
+  const uint64_t bt_s = uni64(reinterpret_cast<uint64_t>(bt));
+  const uint64_t k_head_s = uni64(reinterpret_cast<uint64_t>(k_head));
+  const uint64_t v_head_s = uni64(reinterpret_cast<uint64_t>(v_head));
+  uint64_t off_prev_s = uni64(off_prev);
+  uint32_t phys_next_s = uni(phys_next), b_s = uni(0u);
+  const float ninf = -INFINITY;
+#define FSF_TILE_OPERANDS                                                                      \
+  : "+{v[94:125]}"(acc01), "+{v[126:157]}"(acc23), "+{v[158:189]}"(sc), "+{v[190:205]}"(p0),   \
+    "+{v[206:221]}"(p1), "+{v[40:43]}"(mlcs), "+{v[32:35]}"(thr), "+{s[90:91]}"(off_prev_s),   \
+    "+{s94}"(phys_next_s), "+{s97}"(b_s)                                                       \
+  : "{v[50:53]}"(va), "{v[54:61]}"(ka), "{v[62:93]}"(qf), "{v[44:47]}"(koff),                  \
+    "{v[36:39]}"(voff), "{v48}"(ninf), "{s[60:63]}"(s60), "{s[64:67]}"(s64),                   \
+    "{s[68:71]}"(s68), "{s[72:73]}"(s72), "{s[74:75]}"(bt_s), "{s[76:77]}"(k_head_s),          \
+    "{s[78:79]}"(v_head_s), "{s[80:81]}"(s80)                                                  \
+  : "memory", "vcc", "scc", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s92",     \
+    "s93", "s95", "s96", "v28", "v29", FSF_FRAG_REGS, FSF_SOFTMAX_TMP_REGS
+  if constexpr (DT == FSF_BF16)
+    asm volatile(FSF_TILE_SEQUENCE("v_mfma_f32_32x32x16_bf16", "v_cvt_pk_bf16_f32") FSF_TILE_OPERANDS);
+  else
+    asm volatile(FSF_TILE_SEQUENCE("v_mfma_f32_32x32x16_f16", "v_cvt_pk_f16_f32") FSF_TILE_OPERANDS);
+#undef FSF_TILE_OPERANDS
+
+  // ---- normalise and store: accumulator mt, register r is column d = 32mt + 8(r/4) + 4hg + r%4
+  // of the lane's row
+  float l = mlcs[1];
+  l += __shfl_xor(l, 32);
+  if (row_pos < 0) return;
+  const float inv = 1.f / l;
+  T* orow = out + ((int64_t)(sd.q_offset + row_pos - c) * p.n_q_heads + hq) * kHeadDim;
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int e = 16 * (mt & 1) + 4 * rq;
+      const f32x32_t& a = mt < 2 ? acc01 : acc23;
+      uint2 w;
+      w.x = M::pack2(a[e] * inv, a[e + 1] * inv);
+      w.y = M::pack2(a[e + 2] * inv, a[e + 3] * inv);
+      *reinterpret_cast<uint2*>(orow + 32 * mt + 8 * rq + 4 * hg) = w;
+    }
 }
 
 }  // namespace fsf

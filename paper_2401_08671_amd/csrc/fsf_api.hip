@@ -53,9 +53,16 @@ bool descs_ok(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs, int3
   return off == n_tokens;
 }
 
+// The matrix-core path takes 2-byte dtypes, head_dim 128, blocks of 64 * 2^k tokens (a 64-key
+// step never straddles a block and finds its block with a shift), up to 16 query heads per
+// KV head, and a cache block (all heads) below 4 GiB (its byte offsets are formed in 32-bit
+// scalar multiplies).
 bool fast_path_ok(const fsf_attn_cfg* c) {
+  const int32_t steps_per_block = c->block_size / 64;
   return !(c->flags & FSF_FLAG_FORCE_GENERIC) && (c->dtype == FSF_BF16 || c->dtype == FSF_F16) &&
          c->head_dim == fsf::kHeadDim && c->block_size % 64 == 0 &&
+         (steps_per_block & (steps_per_block - 1)) == 0 &&
+         (uint64_t)c->n_kv_heads * c->block_size * fsf::kHeadDim * 2 < (1ull << 32) &&
          c->n_q_heads / c->n_kv_heads <= 16 && c->scale > 0.f;
 }
 

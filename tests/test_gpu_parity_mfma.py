@@ -81,6 +81,35 @@ def test_prefill_long_chunk_over_long_prefix():
     check_step(Step(spec, poison="nan"), "prefill 700 rows over 1500 cached")
 
 
+@pytest.mark.parametrize("block", [128, 256])
+def test_prefill_larger_blocks(block):
+    """Several 64-key steps per cache block: the step -> block walk and the offset inside a block."""
+    seqs = [(300, 900), (70, 0), (1, 300), (130, 129), (2, 511)]
+    spec = wl.BatchSpec("preB", 4, 2, 128, block, "bf16", seqs, seed=21)
+    check_step(Step(spec, poison="nan"), f"prefill block={block}")
+
+
+def test_prefill_block_192_takes_the_generic_kernel():
+    """Blocks that are not 64 * 2^k tokens are served by the generic kernel, with the same results."""
+    spec = wl.BatchSpec("pre192", 4, 2, 128, 192, "bf16", [(200, 300), (1, 500)], seed=22)
+    check_step(Step(spec, poison="nan"), "prefill block=192")
+
+
+def test_prefill_sharp_softmax_raises_the_reference_often():
+    """A large logit scale makes row maxima jump by far more than 2^8 from step to step, so the
+    running reference is raised (and the accumulators rescaled) inside the unmasked stretch too."""
+    spec = wl.BatchSpec("presharp", 2, 1, 128, 64, "bf16", [(300, 2000), (140, 0)], seed=23, scale=0.7)
+    check_step(Step(spec, poison="nan"), "prefill scale=0.7")
+
+
+@pytest.mark.parametrize("window", [300, 1000])
+def test_prefill_window_inside_long_prefix(window):
+    """The visible range starts deep inside the cached prefix: leading steps are skipped, both
+    ends of the range are masked, the stretch between them is not."""
+    spec = wl.BatchSpec("prewin", 4, 1, 128, 64, "f16", [(260, 2000), (129, 700)], window=window, seed=24)
+    check_step(Step(spec, poison="nan"), f"prefill window={window} over a long prefix")
+
+
 @pytest.mark.parametrize("flags", [0, fsf.FSF_FLAG_FUSED_LAUNCH])
 def test_mixed_batch_order_independent(flags):
     """Chunks and generations interleaved in any order (the kernels may not assume chunks come first);
