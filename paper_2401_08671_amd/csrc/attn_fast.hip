@@ -25,6 +25,14 @@ __device__ __forceinline__ void prefill_block_to_work(const Pass& p, const FastP
   tile = f.n_pre_tiles - 1 - t;
 }
 
+#ifdef FSF_CLOCK_PROBE
+// Developer aid (build with -DFSF_CLOCK_PROBE): every 16th prompt-chunk workgroup records how
+// many shader-clock ticks and how many ticks of the constant 100 MHz counter it ran for, which
+// gives the clock the chip actually held inside the kernel.
+constexpr int kClockProbeSlots = 256;
+__device__ unsigned long long g_clock_probe[2 * kClockProbeSlots];
+#endif
+
 template <int DT, typename T>
 __global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastPlan f,
                                                                  const T* __restrict__ q,
@@ -34,7 +42,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastP
   __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
   int tile, hq;
   prefill_block_to_work(p, f, blockIdx.x, tile, hq);
+#ifdef FSF_CLOCK_PROBE
+  const uint64_t c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+#endif
   prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds);
+#ifdef FSF_CLOCK_PROBE
+  const uint64_t c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+  if (threadIdx.x == 0 && blockIdx.x % 16 == 0 && blockIdx.x / 16 < kClockProbeSlots) {
+    g_clock_probe[2 * (blockIdx.x / 16)] = c1 - c0;
+    g_clock_probe[2 * (blockIdx.x / 16) + 1] = r1 - r0;
+  }
+#endif
 }
 
 // One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
@@ -127,3 +145,11 @@ hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, co
 #undef FSF_LAUNCH
 
 }  // namespace fsf
+
+#ifdef FSF_CLOCK_PROBE
+// host buffer of 512 uint64: (shader ticks, 100 MHz ticks) per probed workgroup of the last launch
+extern "C" int fsf_dbg_clock_read(unsigned long long* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fsf::g_clock_probe),
+                                  sizeof(unsigned long long) * 2 * fsf::kClockProbeSlots);
+}
+#endif

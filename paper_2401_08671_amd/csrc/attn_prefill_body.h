@@ -156,7 +156,7 @@ struct TileCopy {
 //   step's index in the sequence (key/64)   s72 steps per cache block - 1   s73 log2 of steps
 //   per block   s[74:75] block table of the sequence   s[76:77] K base of this head   s[78:79]
 //   V base   s80 bytes per cache block   s81 LDS address of the wave's first copy row
-//   s82..s89, s92, s93, s95, s96 temporaries   s[90:91] offset of step b's tiles   s94 physical
+//   s82..s89, s92, s93, s95, s96, s98, s99 temporaries   s[90:91] offset of step b's tiles   s94 physical
 //   block of step b+1   s97 b
 // Every block of MFMAs ends with the idle cycles the matrix core needs before vector code may
 // read what the last MFMA wrote.
@@ -336,7 +336,7 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
     "{s[68:71]}"(s68), "{s[72:73]}"(s72), "{s[74:75]}"(bt_s), "{s[76:77]}"(k_head_s),          \
     "{s[78:79]}"(v_head_s), "{s[80:81]}"(s80)                                                  \
   : "memory", "vcc", "scc", "s82", "s83", "s84", "s85", "s86", "s87", "s88", "s89", "s92",     \
-    "s93", "s95", "s96", "v28", "v29", FSF_FRAG_REGS, FSF_SOFTMAX_TMP_REGS
+    "s93", "s95", "s96", "s98", "s99", "v28", "v29", FSF_FRAG_REGS, FSF_SOFTMAX_TMP_REGS
   if constexpr (DT == FSF_BF16)
     asm volatile(FSF_TILE_SEQUENCE("v_mfma_f32_32x32x16_bf16", "v_cvt_pk_bf16_f32") FSF_TILE_OPERANDS);
   else

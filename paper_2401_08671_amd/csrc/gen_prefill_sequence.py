@@ -39,7 +39,7 @@ S_BT, S_KHEAD, S_VHEAD = 74, 76, 78      # 64-bit pairs
 S_BLK_BYTES, S_LDS_ROW0 = 's80', 's81'
 S_RAISED = 's[88:89]'       # lanes whose reference was raised by the softmax of this step
 S_PHYS_NEXT, S_PAIRS, S_B = 's94', 's95', 's97'
-# s82..s87, s92, s93, s96: temporaries;  s[90:91]: byte offset of step b's tiles
+# s82..s87, s92, s93, s96, s98, s99: temporaries;  s[90:91]: byte offset of step b's tiles
 
 TILE_BYTES = 16384          # one K or V tile in LDS
 V_RING = 2 * TILE_BYTES     # K slots at 0 and 16384, V slots at 32768 and 49152
@@ -71,7 +71,10 @@ def pf(buf, u):
 
 # ---------------------------------------------------------------------------------------
 # S^T = K Q^T of one step: 8 k-steps x 2 key halves, K fragments read three k-steps ahead
-def qk(kslot):
+def qk(kslot, after=None):
+    """`after`: {k-step t: instructions to place behind its two MFMAs} (no vector ALU work on
+    the scores or fragments; scalar and copy instructions are fine)"""
+    after = after or {}
     kb = kslot * TILE_BYTES
     ahead = NFRAG // 2
     frag = lambda t, kt: T0 + ((t % ahead) * 2 + kt) * 4
@@ -84,6 +87,7 @@ def qk(kslot):
             L.append(f'MFMA {sc(kt)}, v[{frag(t, kt)}:{frag(t, kt) + 3}], {qf(t)}, {c}')
         if t + ahead < 8:
             L += [read(t + ahead, kt) for kt in range(2)]
+        L += after.get(t, [])
     return L + MFMA_DRAIN
 
 
@@ -200,12 +204,14 @@ def mask_scores():
 
 # ---------------------------------------------------------------------------------------
 # hand-over: copies of the next tiles, address arithmetic on the scalar unit
+def copy1(offs, lds_imm, i, base='s[86:87]'):
+    # M0 = LDS address of lane 0's 16 bytes; one idle state between writing M0 and the copy
+    return [f's_add_u32 m0, {S_LDS_ROW0}, {lds_imm + i * 1024}', 's_nop 0',
+            f'global_load_lds_dwordx4 v{offs[i]}, {base}']
+
+
 def copy4(offs, lds_imm):
-    L = []
-    for i in range(4):
-        L += [f's_add_u32 m0, {S_LDS_ROW0}, {lds_imm + i * 1024}', 's_nop 0',
-              f'global_load_lds_dwordx4 v{offs[i]}, s[86:87]']
-    return L
+    return [l for i in range(4) for l in copy1(offs, lds_imm, i)]
 
 
 def copy4_clamped(offs, lds_imm):
@@ -239,8 +245,8 @@ def k_base():
     return [f's_add_u32 s86, s{S_KHEAD}, s84', f's_addc_u32 s87, s{S_KHEAD + 1}, s85']
 
 
-def v_base():
-    return [f's_add_u32 s86, s{S_VHEAD}, s90', f's_addc_u32 s87, s{S_VHEAD + 1}, s91']
+def v_base(lo='s86', hi='s87'):
+    return [f's_add_u32 {lo}, s{S_VHEAD}, s90', f's_addc_u32 {hi}, s{S_VHEAD + 1}, s91']
 
 
 def hand_over_begin():
@@ -248,12 +254,20 @@ def hand_over_begin():
     return ['s_waitcnt vmcnt(0) lgkmcnt(0)', 's_barrier', f's_add_u32 s82, {S_STEP0}, {S_B}']
 
 
-def hand_over_steady(sub):
-    kslot, vslot = (sub + 1) & 1, sub & 1
-    L = hand_over_begin() + offset_of_next_step()
-    L += k_base() + copy4(KOFF, kslot * TILE_BYTES)
-    L += v_base() + copy4(VOFF, V_RING + vslot * TILE_BYTES)
+def hand_over_steady():
+    """addresses only (K base in s[86:87], V base in s[98:99]); the copies themselves are spread
+    through the first product, so that the four waves of a workgroup do not queue 32 KB of
+    copies at the same moment behind the barrier"""
+    L = hand_over_begin() + offset_of_next_step() + k_base() + v_base('s98', 's99')
     return L + ['s_mov_b64 s[90:91], s[84:85]'] + prefetch_block_id()
+
+
+def steady_copies(sub):
+    """K(b+1) behind k-steps 0..3 of QK(b), V(b) behind k-steps 4..7"""
+    kslot, vslot = (sub + 1) & 1, sub & 1
+    after = {i: copy1(KOFF, kslot * TILE_BYTES, i) for i in range(4)}
+    after.update({4 + i: copy1(VOFF, V_RING + vslot * TILE_BYTES, i, 's[98:99]') for i in range(4)})
+    return after
 
 
 def hand_over_general(sub):
@@ -300,7 +314,7 @@ def general_iteration(sub):
 
 
 def steady_iteration(sub):
-    L = hand_over_steady(sub) + qk(sub)
+    L = hand_over_steady() + qk(sub, steady_copies(sub))
     L += pv(sub, (sub + 1) & 1, between=softmax(1 - sub)) + rescale()
     return L + [f's_add_u32 {S_B}, {S_B}, 1']
 
