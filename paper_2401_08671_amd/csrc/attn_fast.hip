@@ -34,7 +34,7 @@ __device__ unsigned long long g_clock_probe[2 * kClockProbeSlots];
 #endif
 
 template <int DT, typename T>
-__global__ __launch_bounds__(kThreads, 2) void attn_prefill_kernel(Pass p, FastPlan f,
+__global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastPlan f,
                                                                  const T* __restrict__ q,
                                                                  const T* __restrict__ kc,
                                                                  const T* __restrict__ vc,
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
 }
 
 template <int DT, typename T>
-__global__ __launch_bounds__(kThreads, 2) void attn_fused_kernel(Pass p, FastPlan f,
+__global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPlan f,
                                                                const T* __restrict__ q,
                                                                const T* __restrict__ kc,
                                                                const T* __restrict__ vc,

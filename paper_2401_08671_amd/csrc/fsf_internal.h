@@ -53,7 +53,7 @@ __device__ __forceinline__ int32_t load_uniform_i32(const int32_t* ptr) {
 //   prompt chunks   (n_new  > 1): "tiles" = (sequence, kPrefillTileM consecutive rows)
 // ---------------------------------------------------------------------------------------
 constexpr int kHeadDim = 128;
-constexpr int kPrefillTileM = 128;   // query rows per prefill workgroup (4 waves x 32 rows)
+constexpr int kPrefillTileM = 256;   // query rows per prefill workgroup (4 waves x 64 rows)
 constexpr int kMaxDecodeItemsExtra = 8192;  // items beyond one per sequence (bounds the workspace)
 
 // Visible key range of the row at position pos.

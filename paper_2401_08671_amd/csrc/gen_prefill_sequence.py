@@ -9,27 +9,40 @@ attn_prefill_body.h, which documents the algorithm, the LDS layout and the regis
 The sequence is emitted as the string of one inline-asm statement.  Two tokens stay macro
 parameters so that one sequence serves both element types: MFMA (the 32x32x16 matrix
 instruction) and CVT (the packing float -> 2-byte conversion).
+
+A wave owns 64 rows as two 32-row blocks (rb = 0, 1) and runs alone on its SIMD with all 512
+registers: 256 vector registers (v) for everything the vector ALU touches and 256 accumulation
+registers (a) for what only the matrix core touches.
 """
 import os
 import sys
 
-# ---- register map (vector)
-V_TMP_COPY = (28, 29)       # temporaries of a clamped copy
-V_RHI, V_RLO = 32, 33       # last / first visible key of the lane's row, minus 4*hg
+# ---- vector registers
+V_TMP_COPY = (28, 29)           # temporaries of a clamped copy
+V_RHI = [30, 32]                # last visible key of the lane's row in row block rb, minus 4*hg
+V_RLO = [31, 33]                # first visible key ..., minus 4*hg
 V_RHI_REL, V_RLO_REL = 34, 35   # the same relative to the first key of the step
-VOFF = [36, 37, 38, 39]     # lane offsets of the wave's four V copy instructions
-V_M, V_L, V_C, V_SL2 = 'v40', 'v41', 'v42', 'v43'   # running max, running sum, rescale factor, scale*log2(e)
-KOFF = [44, 45, 46, 47]     # ... of its four K copy instructions
-V_NINF = 'v48'
-VA = 50                     # v50..v53: LDS address of the lane's V^T fragment, per 32-wide d tile
-KA = 54                     # v54..v61: LDS address of the lane's K fragment, per k-step
-QF = 62                     # v62..v93: Q^T fragments
-ACC = 94                    # v94..v157: O^T, four 32x32 accumulators
-SC = 158                    # v158..v189: S^T, two 32x32 accumulators
-PF = [190, 206]             # the two P^T buffers, 16 registers each
-TMP = 222                   # v222..v231: softmax temporaries
-T0, NFRAG = 232, 6          # v232..v255: six 4-register K / V^T fragments in flight
-# ---- register map (scalar)
+VOFF = [36, 37, 38, 39]         # lane offsets of the wave's four V copy instructions
+KOFF = [40, 41, 42, 43]         # ... of its four K copy instructions
+V_M = ['v44', 'v47']            # running reference (log2 domain) per row block
+V_L = ['v45', 'v48']            # running sum
+V_C = ['v46', 'v49']            # factor of the last raise of the reference
+V_SL2, V_NINF = 'v50', 'v51'    # scale*log2(e), -inf
+VA = 52                         # v52..v55: LDS address of the lane's V^T fragment, per 32-wide d tile
+KA = 56                         # v56..v63: LDS address of the lane's K fragment, per k-step
+SB = [64, 128]                  # two S^T buffers of 64 registers: 32*rb + 16*kt + r
+PB = 192                        # P^T, 32 registers: 16*rb + r
+V_OUT = [224, 226]              # 64-bit address of the lane's output row per row block (+ 8*hg bytes)
+V_Q = [228, 230]                # 64-bit address of the lane's query row (+ 16*hg bytes); prologue only
+TMP = 232                       # v232..v255: temporaries
+# ---- accumulation registers
+AO = 0                          # a0..a127: O^T, 64*rb + 16*mt + r
+AQ = 128                        # a128..a191: Q^T fragments, 32*rb + 4*t + r
+AF, NSLOT = 192, 16             # a192..a255: sixteen 4-register K / V^T fragments in flight
+# ---- scalar registers
+S_VBASE = 's[52:53]'            # temporary: address of the V tile being copied
+S_RAISED = ['s[88:89]', 's[54:55]']   # lanes whose reference the last softmax raised, per row block
+S_LIVE = ['s[56:57]', 's[58:59]']     # lanes whose row exists, per row block
 S_NSTEPS, S_JFIRST, S_JLAST = 's60', 's61', 's62'
 S_NOMASK_LO, S_NOMASK_HI = 's63', 's64'
 S_FAST_LO, S_FAST_HI, S_WHOLE_HI = 's65', 's66', 's67'
@@ -37,13 +50,14 @@ S_LAST_ROW, S_KEY_BEGIN, S_WINDOW, S_STEP0 = 's68', 's69', 's70', 's71'
 S_SPB_MASK, S_SPB_SHIFT = 's72', 's73'
 S_BT, S_KHEAD, S_VHEAD = 74, 76, 78      # 64-bit pairs
 S_BLK_BYTES, S_LDS_ROW0 = 's80', 's81'
-S_RAISED = 's[88:89]'       # lanes whose reference was raised by the softmax of this step
-S_PHYS_NEXT, S_PAIRS, S_B = 's94', 's95', 's97'
-# s82..s87, s92, s93, s96, s98, s99: temporaries;  s[90:91]: byte offset of step b's tiles
+S_OFF0, S_OFF1 = 's[90:91]', 's[98:99]'  # byte offset of the tiles of step b, of step b+1
+S_PHYS, S_PAIRS, S_B = 's94', 's95', 's97'   # physical block of step b+2; steady pairs left; b
+# s82..s87, s92, s93, s96: temporaries (s[84:85] offset of step b+2, s[86:87] address of a K tile)
 
 TILE_BYTES = 16384          # one K or V tile in LDS
 V_RING = 2 * TILE_BYTES     # K slots at 0 and 16384, V slots at 32768 and 49152
-MFMA_DRAIN = ['s_nop 7', 's_nop 3']   # idle cycles before vector code may read the last MFMA's result
+MFMA_DRAIN = ['s_nop 7', 's_nop 3']   # idle cycles before other code may read the last MFMA's result
+LOOKAHEAD = 7               # fragments whose LDS reads are in flight ahead of the MFMAs
 
 _uid = [0]
 
@@ -53,168 +67,197 @@ def label(name):
     return f'.Lfsf_{name}{_uid[0]}_%='
 
 
-def acc(mt):
-    return f'v[{ACC + 16 * mt}:{ACC + 16 * mt + 15}]'
+def S(buf, rb, j):
+    return f'v{SB[buf] + 32 * rb + j}'
 
 
-def sc(kt):
-    return f'v[{SC + 16 * kt}:{SC + 16 * kt + 15}]'
+def s_acc(buf, rb, kt):
+    b = SB[buf] + 32 * rb + 16 * kt
+    return f'v[{b}:{b + 15}]'
 
 
-def qf(t):
-    return f'v[{QF + 4 * t}:{QF + 4 * t + 3}]'
+def o_acc(rb, mt):
+    b = AO + 64 * rb + 16 * mt
+    return f'a[{b}:{b + 15}]'
 
 
-def pf(buf, u):
-    return f'v[{PF[buf] + 4 * u}:{PF[buf] + 4 * u + 3}]'
+def q_frag(rb, t):
+    b = AQ + 32 * rb + 4 * t
+    return f'a[{b}:{b + 3}]'
+
+
+def p_frag(rb, u):
+    b = PB + 16 * rb + 4 * u
+    return f'v[{b}:{b + 3}]'
 
 
 # ---------------------------------------------------------------------------------------
-# S^T = K Q^T of one step: 8 k-steps x 2 key halves, K fragments read three k-steps ahead
-def qk(kslot, after=None):
-    """`after`: {k-step t: instructions to place behind its two MFMAs} (no vector ALU work on
-    the scores or fragments; scalar and copy instructions are fine)"""
-    after = after or {}
-    kb = kslot * TILE_BYTES
-    ahead = NFRAG // 2
-    frag = lambda t, kt: T0 + ((t % ahead) * 2 + kt) * 4
-    read = lambda t, kt: f'ds_read_b128 v[{frag(t, kt)}:{frag(t, kt) + 3}], v{KA + t} offset:{kb + kt * 8192}'
-    L = [read(t, kt) for t in range(ahead) for kt in range(2)]
+def softmax(buf):
+    """Online softmax of S^T buffer `buf` (already masked where needed), both row blocks.
+    A lane holds 32 scores of one row per row block; the other half-wave holds the row's other
+    32.  The scores are replaced in place by the probabilities (fp32); returns (that sequence,
+    the conversions that pack them into P^T: register r = pack(p[2r], p[2r+1]))."""
+    streams = []   # per row block: groups of instructions that stay together
+    for rb in range(2):
+        t = [TMP + 12 * rb + i for i in range(4)]
+        sa, sb = TMP + 12 * rb + 4, TMP + 12 * rb + 5
+        m, l, c = V_M[rb], V_L[rb], V_C[rb]
+        s = lambda j: S(buf, rb, j)
+        G = [[f'v_max3_f32 v{t[k]}, {s(3 * k)}, {s(3 * k + 1)}, {s(3 * k + 2)}' for k in range(4)]]
+        chain = []
+        j, k = 12, 0
+        while j + 1 < 32:
+            chain.append(f'v_max3_f32 v{t[k]}, v{t[k]}, {s(j)}, {s(j + 1)}')
+            j += 2
+            k = (k + 1) % 4
+        G += [chain[0:4], chain[4:8], chain[8:10]]
+        G += [[f'v_max3_f32 v{t[0]}, v{t[0]}, v{t[1]}, v{t[2]}'],
+              [f'v_max_f32 v{t[0]}, v{t[0]}, v{t[3]}'],
+              # the other half-wave holds the other 32 keys of the same rows
+              [f'v_mov_b32 v{t[1]}, v{t[0]}', 's_nop 1', f'v_permlane32_swap_b32 v{t[1]}, v{t[0]}'],
+              [f'v_max_f32 v{t[0]}, v{t[0]}, v{t[1]}'],
+              # raise the running reference only where the maximum outgrew it by more than 2^8
+              [f'v_mul_f32 v{t[0]}, {V_SL2}, v{t[0]}'],
+              [f'v_max_f32 v{t[1]}, v{t[0]}, {m}'],
+              [f'v_sub_f32 v{t[2]}, v{t[1]}, {m}'],
+              [f'v_cmp_lt_f32 vcc, 0x41000000, v{t[2]}', f'v_cndmask_b32 v{t[1]}, {m}, v{t[1]}, vcc',
+               f's_mov_b64 {S_RAISED[rb]}, vcc'],
+              [f'v_sub_f32 v{t[2]}, {m}, v{t[1]}'],
+              [f'v_exp_f32 {c}, v{t[2]}', f'v_mov_b32 {m}, v{t[1]}', f'v_mov_b32 v{sa}, 0', f'v_mov_b32 v{sb}, 0'],
+              [f'v_mul_f32 {l}, {l}, {c}']]
+        for g in range(8):
+            js = [4 * g + i for i in range(4)]
+            G += [[f'v_fma_f32 {s(j)}, {s(j)}, {V_SL2}, -{m}' for j in js],
+                  [f'v_exp_f32 {s(j)}, {s(j)}' for j in js],
+                  [f'v_add_f32 v{sa}, v{sa}, {s(js[0])}', f'v_add_f32 v{sb}, v{sb}, {s(js[1])}',
+                   f'v_add_f32 v{sa}, v{sa}, {s(js[2])}', f'v_add_f32 v{sb}, v{sb}, {s(js[3])}']]
+        G += [[f'v_add_f32 v{sa}, v{sa}, v{sb}'], [f'v_add_f32 {l}, {l}, v{sa}']]
+        streams.append(G)
+    # the two row blocks are independent: alternate their groups, which keeps an instruction
+    # away from the one that needs its result
+    probs = []
+    for ga, gb in zip(*streams):
+        probs += ga + gb
+    pack = [f'CVT v{PB + 16 * rb + r}, {S(buf, rb, 2 * r)}, {S(buf, rb, 2 * r + 1)}'
+            for rb in range(2) for r in range(16)]
+    return probs, pack
+
+
+def pv_program(vslot):
+    """O^T += V^T P^T: fragment (u, mt) = keys 16u..16u+15 x d tile mt, shared by both row blocks"""
+    prog = []
+    for u in range(4):
+        for mt in range(4):
+            reads = [f'ds_read_b64_tr_b16 a[{{r0}}:{{r1}}], v{VA + mt} offset:{vslot * TILE_BYTES + 16 * u * 256}',
+                     f'ds_read_b64_tr_b16 a[{{r2}}:{{r3}}], v{VA + mt} offset:{vslot * TILE_BYTES + (16 * u + 8) * 256}']
+            mfmas = [f'MFMA {o_acc(rb, mt)}, a[{{r0}}:{{r3}}], {p_frag(rb, u)}, {o_acc(rb, mt)}' for rb in range(2)]
+            prog.append((reads, mfmas))
+    return prog
+
+
+def qk_program(kslot, buf):
+    """S^T[buf] = K Q^T: fragment (t, kt) = key half kt x d chunk pair t, shared by both row blocks"""
+    prog = []
     for t in range(8):
-        L.append(f's_waitcnt lgkmcnt({2 * min(ahead - 1, 7 - t)})')
         for kt in range(2):
-            c = '0' if t == 0 else sc(kt)
-            L.append(f'MFMA {sc(kt)}, v[{frag(t, kt)}:{frag(t, kt) + 3}], {qf(t)}, {c}')
-        if t + ahead < 8:
-            L += [read(t + ahead, kt) for kt in range(2)]
-        L += after.get(t, [])
-    return L + MFMA_DRAIN
+            reads = [f'ds_read_b128 a[{{r0}}:{{r3}}], v{KA + t} offset:{kslot * TILE_BYTES + kt * 8192}']
+            mfmas = [f'MFMA {s_acc(buf, rb, kt)}, a[{{r0}}:{{r3}}], {q_frag(rb, t)}, ' +
+                     ('0' if t == 0 else s_acc(buf, rb, kt)) for rb in range(2)]
+            prog.append((reads, mfmas))
+    return prog
 
 
-# O^T += V^T P^T of one step: MFMA i covers k-step u = i / 4 (16 keys), d tile mt = i % 4
-def pv_reads(i, vslot):
-    vb = vslot * TILE_BYTES   # va[] already points into the V ring
-    u, mt = i >> 2, i & 3
-    r = T0 + (i % NFRAG) * 4
-    return [f'ds_read_b64_tr_b16 v[{r}:{r + 1}], v{VA + mt} offset:{vb + 16 * u * 256}',
-            f'ds_read_b64_tr_b16 v[{r + 2}:{r + 3}], v{VA + mt} offset:{vb + (16 * u + 8) * 256}']
-
-
-def pv_mfma(i, buf):
-    u, mt = i >> 2, i & 3
-    r = T0 + (i % NFRAG) * 4
-    return [f's_waitcnt lgkmcnt({2 * min(NFRAG - 1, 15 - i)})',
-            f'MFMA {acc(mt)}, v[{r}:{r + 3}], {pf(buf, u)}, {acc(mt)}']
-
-
-def pv(buf, vslot, between=None):
-    """P^T from buffer buf, V from slot vslot; `between` = vector instructions to spread
-    between the MFMAs (they must not touch the accumulators, buffer buf or the fragments)."""
-    V = list(between or [])
-    per = (len(V) + 16) // 17
+def mfma_block(prog, valu=(), valu_late=(), n_early=0, after=None):
+    """The MFMAs of `prog` with their LDS reads LOOKAHEAD fragments ahead and exact waits.
+    valu: vector instructions spread evenly between the MFMAs; valu_late: more of them that
+    may only start once the first n_early fragments' MFMAs have been issued (they overwrite
+    registers those MFMAs read); after: {k: instructions placed behind the k-th MFMA}."""
+    after = after or {}
+    V = list(valu) + list(valu_late)
+    first_late = len(valu)
+    n_mfma = 2 * len(prog)
+    per = (len(V) + n_mfma) // (n_mfma + 1)
     pos = [0]
 
     def take(n):
         out = V[pos[0]:pos[0] + n]
         pos[0] += n
         return out
+    issued = []   # fragment of every LDS read issued so far, in order
     L = []
-    for i in range(NFRAG):
-        L += pv_reads(i, vslot)
-    L += take(per)
-    for i in range(16):
-        L += pv_mfma(i, buf)
-        if i + NFRAG < 16:
-            L += pv_reads(i + NFRAG, vslot)
-        L += take(per if i < 15 else len(V))
+
+    def issue(f):
+        r = AF + 4 * (f % NSLOT)
+        for rd in prog[f][0]:
+            L.append(rd.format(r0=r, r1=r + 1, r2=r + 2, r3=r + 3))
+            issued.append(f)
+    for f in range(min(LOOKAHEAD, len(prog))):
+        issue(f)
+    L += take(min(per, first_late))
+    k = 0
+    for f in range(len(prog)):
+        last = max(i for i, x in enumerate(issued) if x == f)
+        L.append(f's_waitcnt lgkmcnt({min(15, len(issued) - 1 - last)})')
+        r = AF + 4 * (f % NSLOT)
+        for i, mf in enumerate(prog[f][1]):
+            L.append(mf.format(r0=r, r3=r + 3))
+            if i == 0 and f + LOOKAHEAD < len(prog):
+                issue(f + LOOKAHEAD)
+            k += 1
+            n = per if f >= n_early else min(per, max(0, first_late - pos[0]))
+            L += take(n)
+            L += after.get(k, [])
+    L += take(len(V))
     return L + MFMA_DRAIN
 
 
-def softmax(new):
-    """Online softmax of the step's scores (already masked where needed) -> P^T buffer `new`.
-    A lane holds 32 scores of one row; the other half-wave holds the row's other 32."""
-    e = [TMP + i for i in range(8)]
-    t = e[4:]
-    sa, sb = TMP + 8, TMP + 9
-    S = lambda j: f'v{SC + j}'
-    V = [f'v_max3_f32 v{t[c]}, {S(3 * c)}, {S(3 * c + 1)}, {S(3 * c + 2)}' for c in range(4)]
-    j, c = 12, 0
-    while j + 1 < 32:
-        V.append(f'v_max3_f32 v{t[c]}, v{t[c]}, {S(j)}, {S(j + 1)}')
-        j += 2
-        c = (c + 1) % 4
-    V += [f'v_max3_f32 v{t[0]}, v{t[0]}, v{t[1]}, v{t[2]}',
-          f'v_max_f32 v{t[0]}, v{t[0]}, v{t[3]}',
-          f'v_mov_b32 v{t[1]}, v{t[0]}',
-          's_nop 1',
-          f'v_permlane32_swap_b32 v{t[1]}, v{t[0]}',
-          f'v_max_f32 v{t[0]}, v{t[0]}, v{t[1]}',
-          # raise the running reference only where the maximum outgrew it by more than 2^8
-          f'v_mul_f32 v{t[0]}, {V_SL2}, v{t[0]}',
-          f'v_max_f32 v{t[1]}, v{t[0]}, {V_M}',
-          f'v_sub_f32 v{t[2]}, v{t[1]}, {V_M}',
-          f'v_cmp_lt_f32 vcc, 0x41000000, v{t[2]}',
-          f'v_cndmask_b32 v{t[1]}, {V_M}, v{t[1]}, vcc',
-          f's_mov_b64 {S_RAISED}, vcc',
-          f'v_sub_f32 v{t[2]}, {V_M}, v{t[1]}',
-          f'v_exp_f32 {V_C}, v{t[2]}',
-          f'v_mov_b32 {V_M}, v{t[1]}',
-          f'v_mov_b32 v{sa}, 0',
-          f'v_mov_b32 v{sb}, 0',
-          f'v_mul_f32 {V_L}, {V_L}, {V_C}']
-    # probabilities, their sum, and the packed operand: P^T register r = pack(p[2r], p[2r+1])
-    for g in range(8):
-        ee = e[:4] if g % 2 == 0 else e[4:]
-        js = [4 * g + i for i in range(4)]
-        V += [f'v_fma_f32 v{ee[i]}, {S(js[i])}, {V_SL2}, -{V_M}' for i in range(4)]
-        V += [f'v_exp_f32 v{ee[i]}, v{ee[i]}' for i in range(4)]
-        V += [f'v_add_f32 v{sa}, v{sa}, v{ee[0]}',
-              f'v_add_f32 v{sb}, v{sb}, v{ee[1]}',
-              f'CVT v{PF[new] + 2 * g}, v{ee[0]}, v{ee[1]}',
-              f'v_add_f32 v{sa}, v{sa}, v{ee[2]}',
-              f'v_add_f32 v{sb}, v{sb}, v{ee[3]}',
-              f'CVT v{PF[new] + 2 * g + 1}, v{ee[2]}, v{ee[3]}']
-    V += [f'v_add_f32 v{sa}, v{sa}, v{sb}', f'v_add_f32 {V_L}, {V_L}, v{sa}']
-    return V
-
-
-def rescale():
-    """O^T *= factor where the softmax raised the reference (skipped when no lane did)."""
+def rescale(rb):
+    """O^T of row block rb *= factor where the softmax raised the reference (skipped when no lane did)"""
     keep = label('keep')
-    return ([f's_cmp_eq_u64 {S_RAISED}, 0', f's_cbranch_scc1 {keep}'] +
-            [f'v_mul_f32 v{ACC + r}, v{ACC + r}, {V_C}' for r in range(64)] + [f'{keep}:'])
+    L = [f's_cmp_eq_u64 {S_RAISED[rb]}, 0', f's_cbranch_scc1 {keep}']
+    for r0 in range(0, 64, 8):
+        regs = [(AO + 64 * rb + r0 + i, TMP + i) for i in range(8)]
+        L += [f'v_accvgpr_read_b32 v{t}, a{a}' for a, t in regs]
+        L += [f'v_mul_f32 v{t}, v{t}, {V_C[rb]}' for a, t in regs]
+        L += [f'v_accvgpr_write_b32 a{a}, v{t}' for a, t in regs]
+    return L + [f'{keep}:']
 
 
 def key_of_score(j):
-    """key (inside the step, without the lane's 4*hg) of score register j"""
+    """key (inside the step, without the lane's 4*hg) of score register j of a row block"""
     return 32 * (j >> 4) + 8 * ((j & 15) >> 2) + (j & 3)
 
 
-def mask_scores():
-    """scores of keys outside [rlo, rhi] of the lane's row become -inf"""
-    no_win = label('nowin')
-    L = [f's_lshl_b32 s96, {S_B}, 6', f's_add_u32 s96, s96, {S_KEY_BEGIN}', f'v_subrev_u32 v{V_RHI_REL}, s96, v{V_RHI}']
-    for j in range(32):
-        L += [f'v_cmp_gt_i32 vcc, {key_of_score(j)}, v{V_RHI_REL}', f'v_cndmask_b32 v{SC + j}, v{SC + j}, {V_NINF}, vcc']
-    L += [f's_cmp_eq_u32 {S_WINDOW}, 0', f's_cbranch_scc1 {no_win}', f'v_subrev_u32 v{V_RLO_REL}, s96, v{V_RLO}']
-    for j in range(32):
-        L += [f'v_cmp_lt_i32 vcc, {key_of_score(j)}, v{V_RLO_REL}', f'v_cndmask_b32 v{SC + j}, v{SC + j}, {V_NINF}, vcc']
-    return L + [f'{no_win}:']
+def mask_scores(buf):
+    """scores of keys outside [rlo, rhi] of the lane's rows become -inf"""
+    L = [f's_lshl_b32 s96, {S_B}, 6', f's_add_u32 s96, s96, {S_KEY_BEGIN}']
+    for rb in range(2):
+        no_win = label('nowin')
+        L += [f'v_subrev_u32 v{V_RHI_REL}, s96, v{V_RHI[rb]}']
+        for j in range(32):
+            L += [f'v_cmp_gt_i32 vcc, {key_of_score(j)}, v{V_RHI_REL}',
+                  f'v_cndmask_b32 {S(buf, rb, j)}, {S(buf, rb, j)}, {V_NINF}, vcc']
+        L += [f's_cmp_eq_u32 {S_WINDOW}, 0', f's_cbranch_scc1 {no_win}', f'v_subrev_u32 v{V_RLO_REL}, s96, v{V_RLO[rb]}']
+        for j in range(32):
+            L += [f'v_cmp_lt_i32 vcc, {key_of_score(j)}, v{V_RLO_REL}',
+                  f'v_cndmask_b32 {S(buf, rb, j)}, {S(buf, rb, j)}, {V_NINF}, vcc']
+        L += [f'{no_win}:']
+    return L
 
 
 # ---------------------------------------------------------------------------------------
-# hand-over: copies of the next tiles, address arithmetic on the scalar unit
-def copy1(offs, lds_imm, i, base='s[86:87]'):
+# copies of K and V tiles (global -> LDS, 16 bytes per lane) and their addresses
+def copy1(offs, lds_imm, i, base):
     # M0 = LDS address of lane 0's 16 bytes; one idle state between writing M0 and the copy
     return [f's_add_u32 m0, {S_LDS_ROW0}, {lds_imm + i * 1024}', 's_nop 0',
             f'global_load_lds_dwordx4 v{offs[i]}, {base}']
 
 
-def copy4(offs, lds_imm):
-    return [l for i in range(4) for l in copy1(offs, lds_imm, i)]
+def copy4(offs, lds_imm, base):
+    return [l for i in range(4) for l in copy1(offs, lds_imm, i, base)]
 
 
-def copy4_clamped(offs, lds_imm):
+def copy4_clamped(offs, lds_imm, base):
     """rows past s83 (last written row of the step) are fetched from row s83 instead"""
     a, b = V_TMP_COPY
     L = []
@@ -222,31 +265,45 @@ def copy4_clamped(offs, lds_imm):
         L += [f'v_lshrrev_b32 v{a}, 8, v{offs[i]}', f'v_min_u32 v{a}, s83, v{a}', f'v_lshlrev_b32 v{a}, 8, v{a}',
               f'v_and_b32 v{b}, 0xff, v{offs[i]}', f'v_or_b32 v{a}, v{a}, v{b}',
               f's_add_u32 m0, {S_LDS_ROW0}, {lds_imm + i * 1024}', 's_nop 0',
-              f'global_load_lds_dwordx4 v{a}, s[86:87]']
+              f'global_load_lds_dwordx4 v{a}, {base}']
     return L
 
 
-def offset_of_next_step():
-    """s82 = step b's index in the sequence -> s[84:85] = byte offset of step b+1's tiles
-    (physical block * bytes per block + position inside the block; head excluded)"""
-    return ['s_add_u32 s83, s82, 1', f's_and_b32 s83, s83, {S_SPB_MASK}', 's_lshl_b32 s83, s83, 14',
-            f's_mul_hi_u32 s85, {S_PHYS_NEXT}, {S_BLK_BYTES}', f's_mul_i32 s84, {S_PHYS_NEXT}, {S_BLK_BYTES}',
+def copy_tile(offs, lds_imm, base, step_reg):
+    """whole copy, or clamped if step_reg is past the last step with all 64 rows written"""
+    clamp, done = label('clamp'), label('copied')
+    L = [f's_cmp_gt_i32 {step_reg}, {S_WHOLE_HI}', f's_cbranch_scc1 {clamp}']
+    L += copy4(offs, lds_imm, base) + [f's_branch {done}', f'{clamp}:']
+    L += [f's_lshl_b32 s83, {step_reg}, 6', f's_sub_i32 s83, {S_LAST_ROW}, s83']
+    return L + copy4_clamped(offs, lds_imm, base) + [f'{done}:']
+
+
+def offset_of_step_b_plus_2():
+    """s82 = step b's index in the sequence, S_PHYS = physical block of step b+2 -> s[84:85] =
+    byte offset of its tiles (block * bytes per block + position inside the block; head excluded)"""
+    return ['s_add_u32 s83, s82, 2', f's_and_b32 s83, s83, {S_SPB_MASK}', 's_lshl_b32 s83, s83, 14',
+            f's_mul_hi_u32 s85, {S_PHYS}, {S_BLK_BYTES}', f's_mul_i32 s84, {S_PHYS}, {S_BLK_BYTES}',
             's_add_u32 s84, s84, s83', 's_addc_u32 s85, s85, 0']
 
 
 def prefetch_block_id():
-    """physical block of step b+2 (s82 = step b's index in the sequence)"""
-    return ['s_add_u32 s83, s82, 2', f's_lshr_b32 s83, s83, {S_SPB_SHIFT}', 's_lshl_b32 s83, s83, 2',
+    """physical block of step min(b+3, n_steps-1), read through the scalar cache"""
+    return [f's_add_u32 s83, {S_B}, 3', f's_sub_u32 s96, {S_NSTEPS}, 1', 's_min_u32 s83, s83, s96',
+            f's_add_u32 s83, s83, {S_STEP0}', f's_lshr_b32 s83, s83, {S_SPB_SHIFT}', 's_lshl_b32 s83, s83, 2',
             f's_add_u32 s92, s{S_BT}, s83', f's_addc_u32 s93, s{S_BT + 1}, 0',
-            f's_load_dword {S_PHYS_NEXT}, s[92:93], 0x0']
+            f's_load_dword {S_PHYS}, s[92:93], 0x0']
 
 
 def k_base():
     return [f's_add_u32 s86, s{S_KHEAD}, s84', f's_addc_u32 s87, s{S_KHEAD + 1}, s85']
 
 
-def v_base(lo='s86', hi='s87'):
-    return [f's_add_u32 {lo}, s{S_VHEAD}, s90', f's_addc_u32 {hi}, s{S_VHEAD + 1}, s91']
+def v_base():
+    return [f's_add_u32 s52, s{S_VHEAD}, s90', f's_addc_u32 s53, s{S_VHEAD + 1}, s91']
+
+
+def rotate_offsets():
+    return [f's_mov_b64 {S_OFF0}, {S_OFF1}', f's_mov_b64 {S_OFF1}, s[84:85]']
 
 
 def hand_over_begin():
@@ -255,42 +312,29 @@ def hand_over_begin():
 
 
 def hand_over_steady():
-    """addresses only (K base in s[86:87], V base in s[98:99]); the copies themselves are spread
-    through the first product, so that the four waves of a workgroup do not queue 32 KB of
+    """addresses only (K tile at s[86:87], V tile at s[52:53]); the copies themselves are spread
+    through the MFMAs that follow, so that the four waves of a workgroup do not queue 32 KB of
     copies at the same moment behind the barrier"""
-    L = hand_over_begin() + offset_of_next_step() + k_base() + v_base('s98', 's99')
-    return L + ['s_mov_b64 s[90:91], s[84:85]'] + prefetch_block_id()
+    return (hand_over_begin() + offset_of_step_b_plus_2() + k_base() + v_base() + rotate_offsets() +
+            prefetch_block_id())
 
 
 def steady_copies(sub):
-    """K(b+1) behind k-steps 0..3 of QK(b), V(b) behind k-steps 4..7"""
-    kslot, vslot = (sub + 1) & 1, sub & 1
-    after = {i: copy1(KOFF, kslot * TILE_BYTES, i) for i in range(4)}
-    after.update({4 + i: copy1(VOFF, V_RING + vslot * TILE_BYTES, i, 's[98:99]') for i in range(4)})
+    """K(b+2) behind MFMAs 2, 4, 6, 8 and V(b) behind MFMAs 10, 12, 14, 16"""
+    after = {2 + 2 * i: copy1(KOFF, sub * TILE_BYTES, i, 's[86:87]') for i in range(4)}
+    after.update({10 + 2 * i: copy1(VOFF, V_RING + sub * TILE_BYTES, i, S_VBASE) for i in range(4)})
     return after
 
 
 def hand_over_general(sub):
-    kslot, vslot = (sub + 1) & 1, sub & 1
-    no_k, k_clamp, k_done = label('nok'), label('kclamp'), label('kdone')
-    no_v, v_clamp, v_done = label('nov'), label('vclamp'), label('vdone')
-    no_p = label('nop')
+    """iteration b, b & 1 = sub: K(b+2) -> K slot sub, V(b) -> V slot sub (both last read in iteration b-1)"""
+    no_k, no_v = label('nok'), label('nov')
     L = hand_over_begin()
-    # K(b+1), if there is such a step; clamped if the step holds unwritten rows
-    L += [f's_add_u32 s96, {S_B}, 1', f's_cmp_ge_i32 s96, {S_NSTEPS}', f's_cbranch_scc1 {no_k}']
-    L += offset_of_next_step() + k_base() + [f's_cmp_gt_i32 s96, {S_WHOLE_HI}', f's_cbranch_scc1 {k_clamp}']
-    L += copy4(KOFF, kslot * TILE_BYTES) + [f's_branch {k_done}', f'{k_clamp}:']
-    L += ['s_lshl_b32 s83, s96, 6', f's_sub_i32 s83, {S_LAST_ROW}, s83']
-    L += copy4_clamped(KOFF, kslot * TILE_BYTES) + [f'{k_done}:', f'{no_k}:']
-    # V(b)
+    L += [f's_add_u32 s96, {S_B}, 2', f's_cmp_ge_i32 s96, {S_NSTEPS}', f's_cbranch_scc1 {no_k}']
+    L += offset_of_step_b_plus_2() + k_base() + copy_tile(KOFF, sub * TILE_BYTES, 's[86:87]', 's96') + [f'{no_k}:']
     L += [f's_cmp_ge_i32 {S_B}, {S_NSTEPS}', f's_cbranch_scc1 {no_v}']
-    L += v_base() + [f's_cmp_gt_i32 {S_B}, {S_WHOLE_HI}', f's_cbranch_scc1 {v_clamp}']
-    L += copy4(VOFF, V_RING + vslot * TILE_BYTES) + [f's_branch {v_done}', f'{v_clamp}:']
-    L += [f's_lshl_b32 s83, {S_B}, 6', f's_sub_i32 s83, {S_LAST_ROW}, s83']
-    L += copy4_clamped(VOFF, V_RING + vslot * TILE_BYTES) + [f'{v_done}:', f'{no_v}:']
-    L += ['s_mov_b64 s[90:91], s[84:85]']
-    L += [f's_add_u32 s96, {S_B}, 2', f's_cmp_ge_i32 s96, {S_NSTEPS}', f's_cbranch_scc1 {no_p}']
-    return L + prefetch_block_id() + [f'{no_p}:']
+    L += v_base() + copy_tile(VOFF, V_RING + sub * TILE_BYTES, S_VBASE, S_B) + [f'{no_v}:']
+    return L + rotate_offsets() + prefetch_block_id()
 
 
 # ---------------------------------------------------------------------------------------
@@ -301,27 +345,77 @@ def unless_active(reg, skip):
 
 
 def general_iteration(sub):
-    no_qk, no_pv, no_s, do_mask, no_mask = (label(n) for n in ('noqk', 'nopv', 'nos', 'mask', 'nomask'))
+    """iteration b (b & 1 = sub): PV(b-1), softmax(b) -> P, QK(b+1), each only if its step is active"""
+    no_pv, no_s, no_qk, do_mask, no_mask = (label(n) for n in ('nopv', 'nos', 'noqk', 'mask', 'nomask'))
     L = hand_over_general(sub)
-    L += unless_active(S_B, no_qk) + qk(sub) + [f'{no_qk}:']
-    L += [f's_sub_u32 s96, {S_B}, 1'] + unless_active('s96', no_pv) + pv(sub, (sub + 1) & 1) + [f'{no_pv}:']
+    L += [f's_sub_u32 s96, {S_B}, 1'] + unless_active('s96', no_pv) + mfma_block(pv_program(1 - sub)) + [f'{no_pv}:']
     L += unless_active(S_B, no_s)
     L += [f's_cmp_lt_i32 {S_B}, {S_NOMASK_LO}', f's_cbranch_scc1 {do_mask}',
           f's_cmp_gt_i32 {S_B}, {S_NOMASK_HI}', f's_cbranch_scc1 {do_mask}', f's_branch {no_mask}']
-    L += [f'{do_mask}:'] + mask_scores() + [f'{no_mask}:']
-    L += softmax(1 - sub) + rescale() + [f'{no_s}:']
+    L += [f'{do_mask}:'] + mask_scores(sub) + [f'{no_mask}:']
+    probs, pack = softmax(sub)
+    L += probs + pack + rescale(0) + rescale(1) + [f'{no_s}:']
+    L += [f's_add_u32 s96, {S_B}, 1'] + unless_active('s96', no_qk) + mfma_block(qk_program(1 - sub, 1 - sub)) + [f'{no_qk}:']
     return L + [f's_add_u32 {S_B}, {S_B}, 1']
 
 
 def steady_iteration(sub):
-    L = hand_over_steady() + qk(sub, steady_copies(sub))
-    L += pv(sub, (sub + 1) & 1, between=softmax(1 - sub)) + rescale()
-    return L + [f's_add_u32 {S_B}, {S_B}, 1']
+    """all three parts active, step b unmasked, every copy whole: the 64 MFMAs of PV(b-1) and
+    QK(b+1) in one stream with the vector work of softmax(b) between them"""
+    probs, pack = softmax(sub)
+    prog = pv_program(1 - sub) + qk_program(1 - sub, 1 - sub)
+    L = hand_over_steady() + mfma_block(prog, probs, pack, n_early=16, after=steady_copies(sub))
+    return L + rescale(0) + rescale(1) + [f's_add_u32 {S_B}, {S_B}, 1']
+
+
+def prologue():
+    """Q^T into accumulation registers, O^T = 0, K(0) and K(1) on their way, QK(0)"""
+    no_k1, no_qk = label('nok1'), label('noqk0')
+    L = []
+    for rb in range(2):
+        for t in range(8):
+            r = SB[0] + 32 * rb + 4 * t
+            L.append(f'global_load_dwordx4 v[{r}:{r + 3}], v[{V_Q[rb]}:{V_Q[rb] + 1}], off offset:{32 * t}')
+    L += [f'v_accvgpr_write_b32 a{AO + r}, 0' for r in range(128)]
+    L += [f'v_mov_b32 {V_M[rb]}, 0xf149f2ca' for rb in range(2)]      # -1e30
+    L += [f'v_mov_b32 {V_L[rb]}, 0' for rb in range(2)] + [f'v_mov_b32 {V_C[rb]}, 0' for rb in range(2)]
+    L += [f'v_mov_b32 {V_NINF}, 0xff800000', 's_waitcnt vmcnt(0)']
+    L += [f'v_accvgpr_write_b32 a{AQ + i}, v{SB[0] + i}' for i in range(64)]
+    # K(0) -> K slot 0, K(1) -> K slot 1
+    L += ['s_mov_b32 s96, 0', f's_add_u32 s86, s{S_KHEAD}, s90', f's_addc_u32 s87, s{S_KHEAD + 1}, s91']
+    L += copy_tile(KOFF, 0, 's[86:87]', 's96')
+    L += ['s_mov_b32 s96, 1', f's_cmp_ge_i32 s96, {S_NSTEPS}', f's_cbranch_scc1 {no_k1}']
+    L += [f's_add_u32 s86, s{S_KHEAD}, s98', f's_addc_u32 s87, s{S_KHEAD + 1}, s99']
+    L += copy_tile(KOFF, TILE_BYTES, 's[86:87]', 's96') + [f'{no_k1}:']
+    L += ['s_waitcnt vmcnt(0) lgkmcnt(0)', 's_barrier', 's_mov_b32 s96, 0']
+    L += unless_active('s96', no_qk) + mfma_block(qk_program(0, 0)) + [f'{no_qk}:']
+    return L
+
+
+def epilogue():
+    """O^T / l, rounded, to the lane's output rows: accumulator mt, register r of a row block is
+    column 32 mt + 8 (r / 4) + 4 hg + r % 4"""
+    L = []
+    for rb in range(2):
+        t, inv = TMP + 8, TMP + 9
+        L += [f'v_mov_b32 v{t}, {V_L[rb]}', 's_nop 1', f'v_permlane32_swap_b32 v{t}, {V_L[rb]}',
+              f'v_add_f32 v{t}, v{t}, {V_L[rb]}', f'v_rcp_f32 v{inv}, v{t}', f's_mov_b64 exec, {S_LIVE[rb]}']
+        for mt in range(4):
+            for rq in range(4):
+                a0 = AO + 64 * rb + 16 * mt + 4 * rq
+                d = [TMP + 4 * (rq & 1) + i for i in range(4)]
+                L += [f'v_accvgpr_read_b32 v{d[i]}, a{a0 + i}' for i in range(4)]
+                L += [f'v_mul_f32 v{d[i]}, v{d[i]}, v{inv}' for i in range(4)]
+                L += [f'CVT v{d[0]}, v{d[0]}, v{d[1]}', f'CVT v{d[1]}, v{d[2]}, v{d[3]}',
+                      f'global_store_dwordx2 v[{V_OUT[rb]}:{V_OUT[rb] + 1}], v[{d[0]}:{d[1]}], off offset:{64 * mt + 16 * rq}']
+        L += ['s_mov_b64 exec, -1']
+    return L
 
 
 def tile():
     even, even_body, odd, steady, done = (f'.Lfsf_{n}_%=' for n in ('g0', 'g0body', 'g1', 'fast', 'done'))
-    L = [f'{even}:', f's_cmp_gt_i32 {S_B}, {S_NSTEPS}', f's_cbranch_scc1 {done}']
+    L = prologue()
+    L += [f'{even}:', f's_cmp_gt_i32 {S_B}, {S_NSTEPS}', f's_cbranch_scc1 {done}']
     # an even b with fast_lo <= b and b + 1 <= fast_hi: run steady pairs up to fast_hi
     L += [f's_cmp_lt_i32 {S_B}, {S_FAST_LO}', f's_cbranch_scc1 {even_body}',
           f's_add_u32 s96, {S_B}, 1', f's_cmp_gt_i32 s96, {S_FAST_HI}', f's_cbranch_scc1 {even_body}',
@@ -332,7 +426,8 @@ def tile():
           f's_branch {even}']
     L += [f'{even_body}:'] + general_iteration(0)
     L += [f'{odd}:', f's_cmp_gt_i32 {S_B}, {S_NSTEPS}', f's_cbranch_scc1 {done}'] + general_iteration(1)
-    return L + [f's_branch {even}', f'{done}:']
+    L += [f's_branch {even}', f'{done}:']
+    return L + epilogue()
 
 
 HEADER = """\
@@ -343,9 +438,20 @@ HEADER = """\
 """
 
 
+def clobbers():
+    """registers the sequence writes that are not operands of the asm statement"""
+    v = list(V_TMP_COPY) + [V_RHI_REL, V_RLO_REL] + list(range(44, 50)) + [51]
+    v += list(range(SB[0], PB + 32)) + list(range(TMP, 256))
+    s = [52, 53, 54, 55] + list(range(82, 90)) + [92, 93, 95, 96]
+    names = [f'"s{r}"' for r in s] + [f'"v{r}"' for r in v] + [f'"a{r}"' for r in range(256)]
+    rows = [', '.join(names[i:i + 12]) for i in range(0, len(names), 12)]
+    return '#define FSF_TILE_CLOBBERS \\\n  ' + ', \\\n  '.join(rows) + '\n'
+
+
 def render():
+    _uid[0] = 0
     lines = tile()
-    out = [HEADER + '#define FSF_TILE_SEQUENCE(MFMA, CVT) \\']
+    out = [HEADER + clobbers() + '\n#define FSF_TILE_SEQUENCE(MFMA, CVT) \\']
     for k, l in enumerate(lines):
         cont = ' \\' if k + 1 < len(lines) else ''
         if l.endswith(':'):

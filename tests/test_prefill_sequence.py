@@ -43,21 +43,22 @@ def regs_in(text, kind):
 
 
 def declared_registers():
+    """registers pinned as operands of the asm statement plus the generated clobber list"""
     body = open(os.path.join(CSRC, "attn_prefill_body.h")).read()
     start = body.index("#define FSF_TILE_OPERANDS")
     ops = body[start:body.index("#undef FSF_TILE_OPERANDS")]
     ops = ops[:ops.index("if constexpr")]
-    for macro in ("FSF_FRAG_REGS", "FSF_SOFTMAX_TMP_REGS"):
-        m = re.search(rf"#define {macro}(.*?)\n(?!\s+\")(?=\S|\n)", body, flags=re.S)
-        ops += m.group(1)
-    pinned = re.findall(r'\{([vs][^}]*)\}', ops) + re.findall(r'"([vs]\d+)"', ops)
+    pinned = re.findall(r'\{([vsa][^}]*)\}', ops)
+    gen = open(os.path.join(CSRC, "attn_prefill_sequence.h")).read()
+    clob = gen[gen.index("#define FSF_TILE_CLOBBERS"):gen.index("#define FSF_TILE_SEQUENCE")]
+    pinned += re.findall(r'"([vsa]\d+)"', clob)
     text = " ".join(pinned)
-    return regs_in(text, "v"), regs_in(text, "s")
+    return regs_in(text, "v"), regs_in(text, "s"), regs_in(text, "a")
 
 
 def test_sequence_only_touches_declared_registers():
-    v_ok, s_ok = declared_registers()
-    assert len(v_ok) > 200 and len(s_ok) > 30
+    v_ok, s_ok, a_ok = declared_registers()
+    assert len(v_ok) > 200 and len(s_ok) > 30 and len(a_ok) == 256
     for l in sequence_lines():
         if l.endswith(":"):
             continue
@@ -65,7 +66,8 @@ def test_sequence_only_touches_declared_registers():
         code = re.sub(r"\.Lfsf_\w+", "", code)
         bad_v = regs_in(code, "v") - v_ok
         bad_s = regs_in(code, "s") - s_ok
-        assert not bad_v and not bad_s, f"{l}: v{sorted(bad_v)} s{sorted(bad_s)} not declared"
+        bad_a = regs_in(code, "a") - a_ok
+        assert not bad_v and not bad_s and not bad_a, f"{l}: v{sorted(bad_v)} s{sorted(bad_s)} a{sorted(bad_a)} not declared"
 
 
 def test_every_iteration_has_exactly_one_barrier_on_every_path():
@@ -73,8 +75,10 @@ def test_every_iteration_has_exactly_one_barrier_on_every_path():
     increments there is exactly one s_barrier and it is not inside any skippable region
     (no forward branch jumps over it)."""
     lines = sequence_lines()
+    first = next(i for i, l in enumerate(lines) if l.startswith(".Lfsf_g0_"))
+    assert sum(l.startswith("s_barrier") for l in lines[:first]) == 1   # the one before QK(0)
     chunks, cur = [], []
-    for l in lines:
+    for l in lines[first:]:
         cur.append(l)
         if l.startswith("s_add_u32 s97, s97, 1"):
             chunks.append(cur)
@@ -96,6 +100,9 @@ def test_lds_offsets_stay_inside_the_four_slots():
         m = re.search(r"offset:(\d+)", l)
         if m:
             off = int(m.group(1))
-            assert off < 65536
             if l.startswith("ds_read_b64_tr_b16"):   # V addresses already include the V ring base
                 assert off < 32768
+            elif l.startswith("ds_read"):
+                assert off < 32768                  # K slots
+            else:
+                assert off < 4096                   # global loads and stores of a row
