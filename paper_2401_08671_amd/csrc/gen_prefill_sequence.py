@@ -58,6 +58,7 @@ TILE_BYTES = 16384          # one K or V tile in LDS
 V_RING = 2 * TILE_BYTES     # K slots at 0 and 16384, V slots at 32768 and 49152
 MFMA_DRAIN = ['s_nop 7', 's_nop 3']   # idle cycles before other code may read the last MFMA's result
 LOOKAHEAD = 7               # fragments whose LDS reads are in flight ahead of the MFMAs
+WAIT_EVERY = 2              # one s_waitcnt per this many fragments
 
 _uid = [0]
 
@@ -125,12 +126,19 @@ def softmax(buf):
               [f'v_sub_f32 v{t[2]}, {m}, v{t[1]}'],
               [f'v_exp_f32 {c}, v{t[2]}', f'v_mov_b32 {m}, v{t[1]}', f'v_mov_b32 v{sa}, 0', f'v_mov_b32 v{sb}, 0'],
               [f'v_mul_f32 {l}, {l}, {c}']]
-        for g in range(8):
-            js = [4 * g + i for i in range(4)]
-            G += [[f'v_fma_f32 {s(j)}, {s(j)}, {V_SL2}, -{m}' for j in js],
-                  [f'v_exp_f32 {s(j)}, {s(j)}' for j in js],
-                  [f'v_add_f32 v{sa}, v{sa}, {s(js[0])}', f'v_add_f32 v{sb}, v{sb}, {s(js[1])}',
-                   f'v_add_f32 v{sa}, v{sa}, {s(js[2])}', f'v_add_f32 v{sb}, v{sb}, {s(js[3])}']]
+        # exponent, exponential and sum of element j run one behind the other, so that the
+        # slow exponentials are spread evenly through the stream (a run of them keeps the MFMA
+        # that is due next from being issued in time)
+        for i in range(32 + 2):
+            grp = []
+            if i < 32:
+                grp.append(f'v_fma_f32 {s(i)}, {s(i)}, {V_SL2}, -{m}')
+            if 0 <= i - 1 < 32:
+                grp.append(f'v_exp_f32 {s(i - 1)}, {s(i - 1)}')
+            if 0 <= i - 2 < 32:
+                acc_ = sa if (i - 2) % 2 == 0 else sb
+                grp.append(f'v_add_f32 v{acc_}, v{acc_}, {s(i - 2)}')
+            G.append(grp)
         G += [[f'v_add_f32 v{sa}, v{sa}, v{sb}'], [f'v_add_f32 {l}, {l}, v{sa}']]
         streams.append(G)
     # the two row blocks are independent: alternate their groups, which keeps an instruction
@@ -196,8 +204,9 @@ def mfma_block(prog, valu=(), valu_late=(), n_early=0, after=None):
     L += take(min(per, first_late))
     k = 0
     for f in range(len(prog)):
-        last = max(i for i, x in enumerate(issued) if x == f)
-        L.append(f's_waitcnt lgkmcnt({min(15, len(issued) - 1 - last)})')
+        if f % WAIT_EVERY == 0:   # one wait covers this fragment and the next WAIT_EVERY - 1
+            last = max(i for i, x in enumerate(issued) if x <= min(f + WAIT_EVERY - 1, len(prog) - 1))
+            L.append(f's_waitcnt lgkmcnt({min(15, len(issued) - 1 - last)})')
         r = AF + 4 * (f % NSLOT)
         for i, mf in enumerate(prog[f][1]):
             L.append(mf.format(r0=r, r3=r + 3))
