@@ -17,20 +17,34 @@ constexpr int kThreads = 64 * kPrefillWaves;
 constexpr int kUnitsPerGroup = kThreads / 64;  // generation-row units (waves) per workgroup
 
 // Prefill workgroups are numbered so that the tiles with the most keys to visit (the last
-// rows of a chunk) start first.
+// rows of a chunk) start first.  The tiles started last (tile index < pre_split_tiles) come as
+// pre_parts workgroups each, one per part of the key range.
 __device__ __forceinline__ void prefill_block_to_work(const Pass& p, const FastPlan& f, int block,
-                                                      int& tile, int& hq) {
-  const int t = block / p.n_q_heads;
-  hq = block - t * p.n_q_heads;
-  tile = f.n_pre_tiles - 1 - t;
+                                                      int& tile, int& hq, int& part) {
+  const int whole = (f.n_pre_tiles - f.pre_split_tiles) * p.n_q_heads;  // workgroups of unsplit tiles
+  if (block < whole) {
+    const int t = block / p.n_q_heads;
+    hq = block - t * p.n_q_heads;
+    tile = f.n_pre_tiles - 1 - t;
+    part = 0;
+  } else {
+    const int idx = block - whole;
+    const int per_tile = f.pre_parts * p.n_q_heads;
+    const int t = idx / per_tile;
+    const int r = idx - t * per_tile;
+    part = r / p.n_q_heads;
+    hq = r - part * p.n_q_heads;
+    tile = f.pre_split_tiles - 1 - t;
+  }
 }
 
 #ifdef FSF_CLOCK_PROBE
-// Developer aid (build with -DFSF_CLOCK_PROBE): every 16th prompt-chunk workgroup records how
-// many shader-clock ticks and how many ticks of the constant 100 MHz counter it ran for, which
-// gives the clock the chip actually held inside the kernel.
-constexpr int kClockProbeSlots = 256;
-__device__ unsigned long long g_clock_probe[2 * kClockProbeSlots];
+// Developer aid (build with -DFSF_CLOCK_PROBE): the first 2048 prompt-chunk workgroups record
+// how many shader-clock ticks they ran for and when, on the constant 100 MHz counter, they
+// started and ended: the clock the chip actually held inside the kernel, and the timeline of
+// the launch (rounds, tail).
+constexpr int kClockProbeSlots = 2048;
+__device__ unsigned long long g_clock_probe[3 * kClockProbeSlots];
 #endif
 
 template <int DT, typename T>
@@ -40,17 +54,18 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastP
                                                                  const T* __restrict__ vc,
                                                                  T* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
-  int tile, hq;
-  prefill_block_to_work(p, f, blockIdx.x, tile, hq);
+  int tile, hq, part;
+  prefill_block_to_work(p, f, blockIdx.x, tile, hq, part);
 #ifdef FSF_CLOCK_PROBE
   const uint64_t c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
 #endif
-  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds);
+  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, part, (lds_char*)lds);
 #ifdef FSF_CLOCK_PROBE
   const uint64_t c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
-  if (threadIdx.x == 0 && blockIdx.x % 16 == 0 && blockIdx.x / 16 < kClockProbeSlots) {
-    g_clock_probe[2 * (blockIdx.x / 16)] = c1 - c0;
-    g_clock_probe[2 * (blockIdx.x / 16) + 1] = r1 - r0;
+  if (threadIdx.x == 0 && blockIdx.x < kClockProbeSlots) {
+    g_clock_probe[3 * blockIdx.x] = c1 - c0;
+    g_clock_probe[3 * blockIdx.x + 1] = r0;
+    g_clock_probe[3 * blockIdx.x + 2] = r1;
   }
 #endif
 }
@@ -85,9 +100,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
   const bool is_prefill = pre_upto > pre_before;
   const int idx = is_prefill ? pre_before : b - pre_before;
   if (is_prefill) {  // uniform per workgroup
-    int tile, hq;
-    prefill_block_to_work(p, f, idx, tile, hq);
-    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, (lds_char*)lds);
+    int tile, hq, part;
+    prefill_block_to_work(p, f, idx, tile, hq, part);  // the fused grid is launched without split tiles
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, part, (lds_char*)lds);
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;
@@ -114,7 +129,8 @@ hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, 
                                const void* v_cache, void* out, hipStream_t stream) {
   if (f.n_pre_tiles == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_PREFILL, stream);
-  const unsigned grid = (unsigned)f.n_pre_tiles * p.n_q_heads;
+  const unsigned grid =
+      (unsigned)(f.n_pre_tiles - f.pre_split_tiles + f.pre_split_tiles * f.pre_parts) * p.n_q_heads;
   FSF_LAUNCH(attn_prefill_kernel, grid)
   return hipGetLastError();
 }
@@ -147,9 +163,10 @@ hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, co
 }  // namespace fsf
 
 #ifdef FSF_CLOCK_PROBE
-// host buffer of 512 uint64: (shader ticks, 100 MHz ticks) per probed workgroup of the last launch
+// host buffer of 3 * 2048 uint64: (shader ticks, start, end on the 100 MHz counter) per workgroup of
+// the last launch
 extern "C" int fsf_dbg_clock_read(unsigned long long* host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fsf::g_clock_probe),
-                                  sizeof(unsigned long long) * 2 * fsf::kClockProbeSlots);
+                                  sizeof(unsigned long long) * 3 * fsf::kClockProbeSlots);
 }
 #endif

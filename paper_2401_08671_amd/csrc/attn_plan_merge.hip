@@ -97,6 +97,35 @@ __global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __rest
   orow[lane * 2 + 1] = from_float<T>(a1 * inv);
 }
 
+// Split prompt-chunk tiles: one wave per (row of a split tile, query head) combines the
+// pre_parts partial results of that row in the same way; lanes own two output columns each.
+template <typename T>
+__global__ __launch_bounds__(64) void prefill_merge_kernel(Pass p, FastPlan f, T* __restrict__ out) {
+  const int hq = blockIdx.x % p.n_q_heads;
+  const int trow = blockIdx.x / p.n_q_heads;  // tile * kPrefillTileM + row inside the tile
+  const int tile = trow / kPrefillTileM;
+  const int s = f.pre_tile_seq[tile];
+  const int i = (tile - f.pre_tile_start[s]) * kPrefillTileM + trow % kPrefillTileM;  // row of the chunk
+  if (i >= p.descs[s].n_new) return;
+  const int lane = threadIdx.x;
+  const float* part = f.pre_part + ((int64_t)trow * p.n_q_heads + hq) * f.pre_parts * kPrefillPartRowFloats;
+  float m = -INFINITY;
+  for (int k = 0; k < f.pre_parts; ++k) m = fmaxf(m, part[k * kPrefillPartRowFloats + kHeadDim]);
+  float l = 0.f, a0 = 0.f, a1 = 0.f;
+  for (int k = 0; k < f.pre_parts; ++k) {
+    const float* pk = part + k * kPrefillPartRowFloats;
+    const float w = fast_exp2(pk[kHeadDim] - m);
+    l += pk[kHeadDim + 1] * w;
+    const float2 a = *reinterpret_cast<const float2*>(pk + lane * 2);
+    a0 += a.x * w;
+    a1 += a.y * w;
+  }
+  const float inv = 1.f / l;
+  T* orow = out + ((int64_t)(p.descs[s].q_offset + i) * p.n_q_heads + hq) * kHeadDim;
+  orow[lane * 2] = from_float<T>(a0 * inv);
+  orow[lane * 2 + 1] = from_float<T>(a1 * inv);
+}
+
 }  // namespace
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream) {
@@ -113,6 +142,17 @@ hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStr
     merge_kernel<bf16_t><<<grid, 64, 0, stream>>>(p, f, (bf16_t*)out);
   else
     merge_kernel<f16_t><<<grid, 64, 0, stream>>>(p, f, (f16_t*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream) {
+  if (f.pre_split_tiles == 0 || f.pre_parts < 2) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_MERGE, stream);
+  const unsigned grid = (unsigned)f.pre_split_tiles * kPrefillTileM * p.n_q_heads;
+  if (p.dtype == FSF_BF16)
+    prefill_merge_kernel<bf16_t><<<grid, 64, 0, stream>>>(p, f, (bf16_t*)out);
+  else
+    prefill_merge_kernel<f16_t><<<grid, 64, 0, stream>>>(p, f, (f16_t*)out);
   return hipGetLastError();
 }
 

@@ -125,7 +125,7 @@ __device__ __forceinline__ uint32_t copy_lane_offset(int wave, int lane, int i) 
 //   v232..v255 temporaries
 //   a0..a127 O^T (64 rb + 16 mt + r)   a128..a191 Q^T fragments (32 rb + 4 t + r)
 //   a192..a255 sixteen K / V^T fragments in flight
-//   s[52:53] address of a V tile   s[88:89] s[54:55] lanes whose reference was raised, rb 0, 1
+//   s51 1 if the result is stored as a partial one   s[52:53] address of a V tile   s[88:89] s[54:55] lanes whose reference was raised, rb 0, 1
 //   s[56:57] s[58:59] lanes whose row exists   s60 n_steps   s61 s62 first, last active step
 //   of the wave   s63 s64 first, last step that needs no mask   s65 s66 fast_lo, fast_hi   s67
 //   last step with all 64 rows written   s68 last written key - first key of the tile   s69
@@ -146,12 +146,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 
 // One workgroup of 64*kPrefillWaves threads: tile = index into the pass's prefill tiles,
-// hq = query head, lds = kPrefillLdsBytes of LDS.
+// hq = query head, part = which part of the tile's key range (0 unless the tile is split),
+// lds = kPrefillLdsBytes of LDS.
 template <int DT, typename T>
 __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
                                              const T* __restrict__ q, const T* __restrict__ kc,
                                              const T* __restrict__ vc, T* __restrict__ out, int tile,
-                                             int hq, lds_char* lds) {
+                                             int hq, int part, lds_char* lds) {
   // values that are the same in every lane are told so (the compiler cannot always tell)
   auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane(x); };
   auto uni64 = [&](uint64_t x) { return ((uint64_t)uni((uint32_t)(x >> 32)) << 32) | uni((uint32_t)x); };
@@ -170,8 +171,16 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
   int lo_t, hi_t, tmp;
   visible_range(c + i0, p.window, lo_t, tmp);
   visible_range(c + i1 - 1, p.window, tmp, hi_t);
-  const int key_begin = lo_t & ~(kKeysPerStep - 1);
-  const int n_steps = (hi_t - key_begin) / kKeysPerStep + 1;  // >= 1
+  int key_begin = lo_t & ~(kKeysPerStep - 1);
+  int n_steps = (hi_t - key_begin) / kKeysPerStep + 1;  // >= 1
+  // a split tile: this workgroup walks part `part` of the steps and stores a partial result
+  const bool is_split = tile < f.pre_split_tiles;
+  if (is_split) {
+    const int s_lo = (int)((int64_t)part * n_steps / f.pre_parts);
+    const int s_hi = (int)((int64_t)(part + 1) * n_steps / f.pre_parts);
+    key_begin += s_lo * kKeysPerStep;
+    n_steps = s_hi - s_lo;  // >= 1: the host keeps parts at kPrefillMinPartSteps steps or more
+  }
   const int kv_last = c + n_new - 1;  // last cache position this sequence has written
   const int whole_hi = (kv_last - key_begin - (kKeysPerStep - 1)) >= 0
                            ? (kv_last - key_begin - (kKeysPerStep - 1)) / kKeysPerStep
@@ -186,10 +195,15 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
     int w_lo_min, w_lo_max, w_hi_min, w_hi_max;
     visible_range(c + w_i0, p.window, w_lo_min, w_hi_min);
     visible_range(c + w_i1 - 1, p.window, w_lo_max, w_hi_max);
-    j_first = (w_lo_min - key_begin) / kKeysPerStep;
-    j_last = (w_hi_max - key_begin) / kKeysPerStep;
+    // clipped to the steps this workgroup walks (all of the tile's unless it is split)
+    j_first = w_lo_min > key_begin ? (w_lo_min - key_begin) / kKeysPerStep : 0;
+    j_last = w_hi_max >= key_begin ? min((w_hi_max - key_begin) / kKeysPerStep, n_steps - 1) : -1;
+    if (j_last < j_first) {
+      j_first = 0;
+      j_last = -1;
+    }
     if (w_i1 - w_i0 == kRowsPerWave) {
-      nomask_lo = (w_lo_max - key_begin + kKeysPerStep - 1) / kKeysPerStep;
+      nomask_lo = w_lo_max > key_begin ? (w_lo_max - key_begin + kKeysPerStep - 1) / kKeysPerStep : 0;
       nomask_hi = (w_hi_min - key_begin - (kKeysPerStep - 1)) >= 0
                       ? (w_hi_min - key_begin - (kKeysPerStep - 1)) / kKeysPerStep
                       : -1;
@@ -224,7 +238,10 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
     // Q^T fragment t of the lane is d chunk 2t + hg (8 elements); its output columns are
     // 32 mt + 8 rq + 4 hg + 0..3
     const uint64_t qa = reinterpret_cast<uint64_t>(q + row + 8 * hg);
-    const uint64_t oa = reinterpret_cast<uint64_t>(out + row + 4 * hg);
+    // a split tile's rows go to the partial-result buffer: [tile row, head, part][136 floats]
+    const int64_t prow = (((int64_t)tile * kPrefillTileM + (ic - i0)) * p.n_q_heads + hq) * f.pre_parts + part;
+    const uint64_t oa = is_split ? reinterpret_cast<uint64_t>(f.pre_part + prow * kPrefillPartRowFloats + 4 * hg)
+                                 : reinterpret_cast<uint64_t>(out + row + 4 * hg);
     q_ptr[2 * rb] = (uint32_t)qa;
     q_ptr[2 * rb + 1] = (uint32_t)(qa >> 32);
     o_ptr[2 * rb] = (uint32_t)oa;
@@ -281,10 +298,12 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
   const uint64_t k_head_s = uni64(reinterpret_cast<uint64_t>(k_head));
   const uint64_t v_head_s = uni64(reinterpret_cast<uint64_t>(v_head));
   const float sl2 = p.scale * 1.4426950408889634f;  // scale * log2(e)
+  const uint32_t partial = uni(is_split ? 1u : 0u);
 #define FSF_TILE_OPERANDS                                                                          \
   : "+{s[90:91]}"(off0_s), "+{s[98:99]}"(off1_s), "+{s94}"(phys2_s), "+{s97}"(b_s)                 \
   : "{v[30:33]}"(thr), "{v[36:39]}"(voff), "{v[40:43]}"(koff), "{v50}"(sl2), "{v[52:55]}"(va),     \
-    "{v[56:63]}"(ka), "{v[224:227]}"(o_ptr), "{v[228:231]}"(q_ptr), "{s[56:57]}"(live[0]),         \
+    "{v[56:63]}"(ka), "{v[224:227]}"(o_ptr), "{v[228:231]}"(q_ptr), "{s51}"(partial),              \
+    "{s[56:57]}"(live[0]),                                                                         \
     "{s[58:59]}"(live[1]), "{s[60:63]}"(s60), "{s[64:67]}"(s64), "{s[68:71]}"(s68),                \
     "{s[72:73]}"(s72), "{s[74:75]}"(bt_s), "{s[76:77]}"(k_head_s), "{s[78:79]}"(v_head_s),         \
     "{s[80:81]}"(s80)                                                                              \

@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
+
 #include "fsf_internal.h"
 
 namespace {
@@ -70,7 +72,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace sections of the matrix-core path, in order.
 struct WsLayout {
-  size_t dec_item_start, pre_tile_start, dec_item_seq, pre_tile_seq, split_seqs, part_ml, part_acc, total;
+  size_t dec_item_start, pre_tile_start, dec_item_seq, pre_tile_seq, split_seqs, part_ml, part_acc, pre_part, total;
 };
 
 WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
@@ -92,6 +94,10 @@ WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
   off += align256(items_cap * c->n_q_heads * 2 * sizeof(float));
   w.part_acc = off;
   off += align256(items_cap * c->n_q_heads * fsf::kHeadDim * sizeof(float));
+  // partial results of split prompt-chunk tiles: at most kMaxPrefillSplitUnits (tile, head, part) workgroups
+  const size_t split_units = std::min<size_t>(fsf::kMaxPrefillSplitUnits, tiles_cap * c->n_q_heads * 16);
+  w.pre_part = off;
+  off += align256(split_units * fsf::kPrefillTileM * fsf::kPrefillPartRowFloats * sizeof(float));
   w.total = off;
   return w;
 }
@@ -101,6 +107,57 @@ int env_int(const char* name, int dflt) {
   if (!v || !*v) return dflt;
   const int x = atoi(v);
   return x > 0 ? x : dflt;
+}
+
+int compute_units() {
+  static int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
+      cu = 256;
+    return cu;
+  }();
+  return n;
+}
+
+// Prompt-chunk workgroups (tile x head) are started heaviest first, one per compute unit at a
+// time.  When the last round of them is less than half full (or there is less than one round),
+// the tiles of that round are cut into parts along their keys so that the round fills the
+// chip: f.pre_split_tiles tiles (the last to be started: tile indices 0 ..), f.pre_parts parts each.
+void choose_prefill_split(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs, fsf::FastPlan& f) {
+  f.pre_split_tiles = 0;
+  f.pre_parts = 1;
+  const int H = c->n_q_heads;
+  const int cus = env_int("FSF_PREFILL_SPLIT_UNITS", compute_units());  // tests force splits with a large value
+  if ((c->flags & FSF_FLAG_FUSED_LAUNCH) || f.n_pre_tiles == 0 || getenv("FSF_PREFILL_NO_SPLIT")) return;
+  const int64_t groups = (int64_t)f.n_pre_tiles * H;
+  const int64_t tail = groups % cus;  // workgroups of the last, partial round
+  if (tail == 0 || 2 * tail > cus) return;
+  // whole tiles only, and all of the partial round: an unsplit workgroup left in it would
+  // last as long as the round did before
+  int split_tiles = (int)((tail + H - 1) / H);
+  if (split_tiles > f.n_pre_tiles) split_tiles = f.n_pre_tiles;
+  int parts = std::max(2, (int)((cus + (int64_t)split_tiles * H / 2) / ((int64_t)split_tiles * H)));
+  if ((int64_t)split_tiles * H * parts > fsf::kMaxPrefillSplitUnits)
+    parts = (int)(fsf::kMaxPrefillSplitUnits / ((int64_t)split_tiles * H));
+  // no part shorter than kPrefillMinPartSteps steps: look at the shortest of the tiles to split
+  int tile = 0, min_steps = 1 << 30;
+  for (int32_t s = 0; s < n_seqs && tile < split_tiles; ++s) {
+    if (h[s].n_new == 1) continue;
+    const int n_tiles = (h[s].n_new + fsf::kPrefillTileM - 1) / fsf::kPrefillTileM;
+    for (int t = 0; t < n_tiles && tile < split_tiles; ++t, ++tile) {
+      const int i0 = t * fsf::kPrefillTileM;
+      const int i1 = std::min(i0 + fsf::kPrefillTileM, h[s].n_new);
+      int lo, hi, tmp;
+      fsf::visible_range(h[s].n_cached + i0, c->window, lo, tmp);
+      fsf::visible_range(h[s].n_cached + i1 - 1, c->window, tmp, hi);
+      min_steps = std::min(min_steps, (hi - (lo & ~63)) / 64 + 1);
+    }
+  }
+  parts = std::min(std::min(parts, 16), min_steps / fsf::kPrefillMinPartSteps);
+  if (parts < 2) return;
+  f.pre_split_tiles = split_tiles;
+  f.pre_parts = parts;
 }
 
 }  // namespace
@@ -207,6 +264,8 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.n_dec_items = (int32_t)n_dec;
   f.n_pre_tiles = (int32_t)n_pre;
   f.n_split_seqs = n_split;
+  f.pre_part = (float*)(ws + w.pre_part);
+  choose_prefill_split(cfg, descs_host, n_seqs, f);
 
   hipError_t e = fsf::launch_plan(p, f, stream);
   if (cfg->flags & FSF_FLAG_FUSED_LAUNCH) {
@@ -215,6 +274,7 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
     if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
     if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
   }
+  if (e == hipSuccess) e = fsf::launch_prefill_merge(p, f, out, stream);
   if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }

@@ -55,6 +55,12 @@ __device__ __forceinline__ int32_t load_uniform_i32(const int32_t* ptr) {
 constexpr int kHeadDim = 128;
 constexpr int kPrefillTileM = 256;   // query rows per prefill workgroup (4 waves x 64 rows)
 constexpr int kMaxDecodeItemsExtra = 8192;  // items beyond one per sequence (bounds the workspace)
+// Prompt-chunk tiles that would leave most compute units idle (a partial last round of
+// workgroups, or fewer workgroups than units) have their key range cut into parts, one
+// workgroup each, which store unnormalised partial results that a merge kernel combines.
+constexpr int kMaxPrefillSplitUnits = 512;  // (tile, head, part) workgroups with partial results (bounds the workspace)
+constexpr int kPrefillPartRowFloats = 136;  // a partial row: O 128 floats, m, l, padding to a multiple of 16 bytes
+constexpr int kPrefillMinPartSteps = 8;     // no part is shorter than this many 64-key steps
 
 // Visible key range of the row at position pos.
 __host__ __device__ inline void visible_range(int pos, int window, int& lo, int& hi) {
@@ -95,15 +101,19 @@ struct FastPlan {
   int32_t* split_seqs;      // [n_split_seqs] sequences whose generation row was cut into > 1 item
   float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
   float* part_acc;          // [items, n_q_heads, 128] unnormalised outputs per split
+  float* pre_part;          // [pre_split_tiles * 256 rows, n_q_heads, pre_parts, 136] partial results of split tiles
   int32_t split_blocks;     // target cache blocks per decode item
   int32_t min_item_blocks;  // no split leaves an item with fewer blocks than this
   int32_t n_dec_items, n_pre_tiles, n_split_seqs;  // host-side totals (grid sizes)
+  int32_t pre_split_tiles;  // tiles 0 .. pre_split_tiles-1 (the last to be started) are cut into
+  int32_t pre_parts;        // this many parts each (1: nothing is split)
 };
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);
 hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                               const void* v_cache, void* out, hipStream_t stream);
 hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream);
+hipError_t launch_prefill_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream);
 hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                                const void* v_cache, void* out, hipStream_t stream);
 // prompt-chunk tiles and generation-row items in ONE launch, so the two kinds of work overlap

@@ -40,6 +40,7 @@ AO = 0                          # a0..a127: O^T, 64*rb + 16*mt + r
 AQ = 128                        # a128..a191: Q^T fragments, 32*rb + 4*t + r
 AF, NSLOT = 192, 16             # a192..a255: sixteen 4-register K / V^T fragments in flight
 # ---- scalar registers
+S_PARTIAL = 's51'               # 0: store normalised outputs; 1: store the unnormalised partial result
 S_VBASE = 's[52:53]'            # temporary: address of the V tile being copied
 S_RAISED = ['s[88:89]', 's[54:55]']   # lanes whose reference the last softmax raised, per row block
 S_LIVE = ['s[56:57]', 's[58:59]']     # lanes whose row exists, per row block
@@ -401,24 +402,44 @@ def prologue():
     return L
 
 
+PARTIAL_ROW_FLOATS = 136     # a partial result row: O^T 128 floats, then m, l (then padding to 16 bytes x 34)
+
+
 def epilogue():
-    """O^T / l, rounded, to the lane's output rows: accumulator mt, register r of a row block is
-    column 32 mt + 8 (r / 4) + 4 hg + r % 4"""
-    L = []
-    for rb in range(2):
-        t, inv = TMP + 8, TMP + 9
-        L += [f'v_mov_b32 v{t}, {V_L[rb]}', 's_nop 1', f'v_permlane32_swap_b32 v{t}, {V_L[rb]}',
-              f'v_add_f32 v{t}, v{t}, {V_L[rb]}', f'v_rcp_f32 v{inv}, v{t}', f's_mov_b64 exec, {S_LIVE[rb]}']
-        for mt in range(4):
-            for rq in range(4):
-                a0 = AO + 64 * rb + 16 * mt + 4 * rq
-                d = [TMP + 4 * (rq & 1) + i for i in range(4)]
-                L += [f'v_accvgpr_read_b32 v{d[i]}, a{a0 + i}' for i in range(4)]
-                L += [f'v_mul_f32 v{d[i]}, v{d[i]}, v{inv}' for i in range(4)]
-                L += [f'CVT v{d[0]}, v{d[0]}, v{d[1]}', f'CVT v{d[1]}, v{d[2]}, v{d[3]}',
-                      f'global_store_dwordx2 v[{V_OUT[rb]}:{V_OUT[rb] + 1}], v[{d[0]}:{d[1]}], off offset:{64 * mt + 16 * rq}']
-        L += ['s_mov_b64 exec, -1']
-    return L
+    """Normal mode: O^T / l, rounded, to the lane's output rows.  Partial mode (the tile's key
+    range was split across workgroups): O^T as it is, the reference m and the sum l, in fp32, to
+    the lane's rows of the partial-result buffer.  Accumulator mt, register r of a row block is
+    column 32 mt + 8 (r / 4) + 4 hg + r % 4; the row addresses already include the lane's 4 hg
+    columns."""
+    partial, end = label('partial'), label('end')
+    L = [f's_cmp_eq_u32 {S_PARTIAL}, 0', f's_cbranch_scc0 {partial}']
+    for mode in ('normal', 'partial'):
+        if mode == 'partial':
+            L += [f's_branch {end}', f'{partial}:']
+        for rb in range(2):
+            t, inv = TMP + 8, TMP + 9
+            # the other half-wave holds the sum over the other 32 keys of every step
+            L += [f'v_mov_b32 v{t}, {V_L[rb]}', 's_nop 1', f'v_permlane32_swap_b32 v{t}, {V_L[rb]}',
+                  f'v_add_f32 v{t}, v{t}, {V_L[rb]}']
+            if mode == 'normal':
+                L += [f'v_rcp_f32 v{inv}, v{t}', f's_mov_b64 exec, {S_LIVE[rb]}']
+            else:
+                L += [f'v_mov_b32 v{TMP + 10}, {V_M[rb]}', f'v_mov_b32 v{TMP + 11}, v{t}', f's_mov_b64 exec, {S_LIVE[rb]}',
+                      f'global_store_dwordx2 v[{V_OUT[rb]}:{V_OUT[rb] + 1}], v[{TMP + 10}:{TMP + 11}], off offset:512']
+            for mt in range(4):
+                for rq in range(4):
+                    a0 = AO + 64 * rb + 16 * mt + 4 * rq
+                    d = [TMP + 4 * (rq & 1) + i for i in range(4)]
+                    L += [f'v_accvgpr_read_b32 v{d[i]}, a{a0 + i}' for i in range(4)]
+                    if mode == 'normal':
+                        L += [f'v_mul_f32 v{d[i]}, v{d[i]}, v{inv}' for i in range(4)]
+                        L += [f'CVT v{d[0]}, v{d[0]}, v{d[1]}', f'CVT v{d[1]}, v{d[2]}, v{d[3]}',
+                              f'global_store_dwordx2 v[{V_OUT[rb]}:{V_OUT[rb] + 1}], v[{d[0]}:{d[1]}], off offset:{64 * mt + 16 * rq}']
+                    else:
+                        L += ['s_nop 0',
+                              f'global_store_dwordx4 v[{V_OUT[rb]}:{V_OUT[rb] + 1}], v[{d[0]}:{d[3]}], off offset:{128 * mt + 32 * rq}']
+            L += ['s_mov_b64 exec, -1']
+    return L + [f'{end}:']
 
 
 def tile():

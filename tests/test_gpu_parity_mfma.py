@@ -110,6 +110,28 @@ def test_prefill_window_inside_long_prefix(window):
     check_step(Step(spec, poison="nan"), f"prefill window={window} over a long prefix")
 
 
+@pytest.fixture
+def prefill_split_env():
+    """Pretend the chip has this many compute units, so that small batches get split tiles."""
+    old = os.environ.get("FSF_PREFILL_SPLIT_UNITS")
+    yield lambda units: os.environ.update(FSF_PREFILL_SPLIT_UNITS=str(units))
+    if old is None:
+        os.environ.pop("FSF_PREFILL_SPLIT_UNITS", None)
+    else:
+        os.environ["FSF_PREFILL_SPLIT_UNITS"] = old
+
+
+@pytest.mark.parametrize("units,window,dtype", [(64, 0, "bf16"), (64, 700, "f16"), (40, 0, "bf16"), (1000, 0, "bf16")])
+def test_prefill_tiles_split_along_keys(prefill_split_env, units, window, dtype):
+    """Tiles of a partial last round are cut into parts along their keys (one workgroup each,
+    unnormalised partial results, merge): forced here by a small unit count.  Parts that end
+    before a row's first visible key, or start after its last, contribute nothing to that row."""
+    prefill_split_env(units)
+    seqs = [(700, 1500), (1, 900), (300, 2100), (1, 64)]
+    spec = wl.BatchSpec("presplit", 2, 1, 128, 64, dtype, seqs, window=window, seed=31)
+    check_step(Step(spec, poison="nan"), f"prefill split units={units} window={window} {dtype}")
+
+
 @pytest.mark.parametrize("flags", [0, fsf.FSF_FLAG_FUSED_LAUNCH])
 def test_mixed_batch_order_independent(flags):
     """Chunks and generations interleaved in any order (the kernels may not assume chunks come first);
