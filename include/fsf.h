@@ -162,6 +162,26 @@ int fsf_sched_create(fsf_sched** out, int32_t token_budget, int32_t max_seqs, in
                      int64_t num_blocks, const int32_t* free_list_order);
 void fsf_sched_destroy(fsf_sched* s);
 
+/*
+ * Composition policy, to be chosen before the first request (default Dynamic SplitFuse).
+ * The other two are the batch decisions the paper contrasts it with (Sec. 2.2, Sec. 3,
+ * Sec. 4.4), for the scheduling simulator; neither splits a prompt:
+ *   FSF_POLICY_PROMPT_FIRST        while prompts wait, a pass holds whole prompts only (first
+ *                                  come first served, as many as fit token_budget, the first
+ *                                  even if longer) and generations wait; else all generations
+ *   FSF_POLICY_WHOLE_PROMPT_JOINS  every pass runs the generations (at most token_budget and
+ *                                  max_seqs of them) and waiting prompts join whole while
+ *                                  sequences and blocks allow; no token budget for prompts
+ * Generations keep their descriptors ahead of the prompts in every policy.
+ * Returns FSF_ERR_INVALID_ARG for an unknown policy or once requests exist.
+ */
+typedef enum {
+  FSF_POLICY_SPLITFUSE = 0,
+  FSF_POLICY_PROMPT_FIRST = 1,
+  FSF_POLICY_WHOLE_PROMPT_JOINS = 2
+} fsf_policy;
+int fsf_sched_set_policy(fsf_sched* s, int32_t policy);
+
 /* Queue a request: prompt_len >= 1 tokens to read, max_new_tokens >= 1 tokens to emit.
  * The sequence emits its first token in the pass that consumes its last prompt token,
  * then runs as a generation until max_new_tokens are emitted; the last emitted token

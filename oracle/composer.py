@@ -31,6 +31,20 @@ R6  out of blocks: a generation that cannot get its block is skipped this pass (
 R7  descriptor order: generations (rotation order), then prompt chunks (arrival order);
     ``q_offset`` is the running sum of ``n_new``.
 R8  if requests exist but nothing can be scheduled the composer reports "no blocks".
+
+Two further policies serve the scheduling simulator as points of comparison.  They are the
+batch decisions the paper sets Dynamic SplitFuse against (Sec. 2.2 continuous batching with
+a bound on sequences; Sec. 3 and Sec. 4.4: prompt processing that preempts generation),
+reduced to the decision itself; neither ever splits a prompt:
+
+P1  ``prompt_first``: if any prompt waits, the pass holds whole prompts only, in arrival
+    order, as long as their token sum stays within ``token_budget`` (the first prompt is
+    taken even if it alone exceeds it) and sequences and blocks allow; generations wait.
+    A prompt that cannot get its blocks waits and nothing behind it starts.  If no prompt
+    could be placed, or none waits, the pass runs the generations as in R1, R2, R6.
+P2  ``whole_prompt_joins``: every pass runs the generations (R1, R2, R6) and then lets
+    waiting prompts join whole, in arrival order, while sequences and blocks allow; there
+    is no token budget for prompts.
 """
 from __future__ import annotations
 
@@ -56,10 +70,15 @@ def _ceil_div(a: int, b: int) -> int:
     return -(-a // b)
 
 
+POLICIES = ("splitfuse", "prompt_first", "whole_prompt_joins")
+
+
 class SplitFuseComposer:
     def __init__(self, token_budget: int, max_seqs: int, block_size: int, num_blocks: int,
-                 free_list_order=None):
+                 free_list_order=None, policy: str = "splitfuse"):
         assert token_budget >= 1 and max_seqs >= 1 and block_size >= 1 and num_blocks >= 1
+        assert policy in POLICIES
+        self.policy = policy
         self.token_budget = token_budget
         self.max_seqs = max_seqs
         self.block_size = block_size
@@ -95,21 +114,51 @@ class SplitFuseComposer:
         budget_left = self.token_budget
         seqs_left = self.max_seqs
 
-        # generations first (R1, R2, R6)
-        for seq in self.decodes:
-            if budget_left == 0 or seqs_left == 0:
-                break
-            need = _ceil_div(seq.n_cached + 1, B) - _ceil_div(seq.n_cached, B)
-            if need > len(self.free):
-                continue
-            for _ in range(need):
-                seq.blocks.append(self.free.popleft())
-            batch.append((seq, 1, 1, True))
-            budget_left -= 1
-            seqs_left -= 1
+        def place_generations():
+            nonlocal budget_left, seqs_left
+            for seq in self.decodes:            # R1, R2, R6
+                if budget_left == 0 or seqs_left == 0:
+                    break
+                need = _ceil_div(seq.n_cached + 1, B) - _ceil_div(seq.n_cached, B)
+                if need > len(self.free):
+                    continue
+                for _ in range(need):
+                    seq.blocks.append(self.free.popleft())
+                batch.append((seq, 1, 1, True))
+                budget_left -= 1
+                seqs_left -= 1
 
-        # then prompt tokens fill what is left of the budget (R3, R6)
-        for seq in self.prompts:
+        def place_whole_prompts(token_cap):
+            """whole prompts in arrival order; token_cap None = no cap (P2), else P1's cap"""
+            nonlocal seqs_left
+            placed_tokens = 0
+            for seq in self.prompts:
+                if seqs_left == 0:
+                    break
+                assert seq.n_cached == 0
+                if token_cap is not None and placed_tokens > 0 and placed_tokens + seq.prompt_len > token_cap:
+                    break
+                need = _ceil_div(seq.prompt_len, B)
+                if need > len(self.free):
+                    break
+                for _ in range(need):
+                    seq.blocks.append(self.free.popleft())
+                batch.append((seq, seq.prompt_len, 1, False))
+                placed_tokens += seq.prompt_len
+                seqs_left -= 1
+            return placed_tokens
+
+        if self.policy == "prompt_first":
+            if place_whole_prompts(self.token_budget) == 0:
+                place_generations()
+        elif self.policy == "whole_prompt_joins":
+            place_generations()
+            place_whole_prompts(None)
+        else:
+            place_generations()
+
+        # Dynamic SplitFuse: prompt tokens fill what is left of the budget (R3, R6)
+        for seq in (self.prompts if self.policy == "splitfuse" else ()):
             if budget_left == 0 or seqs_left == 0:
                 break
             want = min(seq.prompt_len - seq.n_cached, budget_left)
@@ -133,7 +182,7 @@ class SplitFuseComposer:
 
         descs, tables, emits = [], [], []
         q_off = 0
-        for seq, n_new, em, _ in batch:
+        for seq, n_new, em, _ in batch:        # generations were placed before prompts (R7)
             descs.append((n_new, seq.n_cached, q_off, seq.seq_id))
             tables.append(list(seq.blocks))
             emits.append(em)

@@ -6,6 +6,17 @@
 // budget when enough tokens wait (rule 2).  Generations go first so prompts never stall
 // them.  Cache storage is handed out in fixed-size blocks (Sec. 2.1).
 //
+// Two more composition policies exist for comparison runs of the scheduling simulator: they
+// are the behaviours the paper contrasts Dynamic SplitFuse with (Sec. 2.2, Sec. 3, Sec. 4.4),
+// reduced to their batch decision:
+//   prompt-first       whenever prompts wait, the pass processes whole prompts only (first
+//                      come first served, as many as fit the token budget, the first one
+//                      even if it is longer) and running generations wait; otherwise all
+//                      generations run
+//   whole-prompt-joins continuous batching with a bound on sequences only: every pass runs
+//                      the generations and lets waiting prompts join whole, unsplit
+// Neither splits a prompt; both use the same block allocator and rotation.
+//
 // Pure host code: no HIP calls.  Sequences live in a slab indexed by small integers;
 // the two queues hold slab indices.  compose() works in two phases, plan then apply, so
 // an error leaves the scheduler untouched.
@@ -52,6 +63,7 @@ struct fsf_sched {
   std::vector<int32_t> decodes;  // slab indices, rotation order
   std::vector<Planned> pending;
   bool has_pending = false;
+  int32_t policy = FSF_POLICY_SPLITFUSE;
 };
 
 extern "C" int fsf_sched_create(fsf_sched** out, int32_t token_budget, int32_t max_seqs,
@@ -81,6 +93,13 @@ extern "C" int fsf_sched_create(fsf_sched** out, int32_t token_budget, int32_t m
 }
 
 extern "C" void fsf_sched_destroy(fsf_sched* s) { delete s; }
+
+extern "C" int fsf_sched_set_policy(fsf_sched* s, int32_t policy) {
+  if (!s || policy < FSF_POLICY_SPLITFUSE || policy > FSF_POLICY_WHOLE_PROMPT_JOINS) return FSF_ERR_INVALID_ARG;
+  if (s->has_pending || !s->prompts.empty() || !s->decodes.empty()) return FSF_ERR_INVALID_ARG;
+  s->policy = policy;
+  return FSF_OK;
+}
 
 extern "C" int fsf_sched_add_request(fsf_sched* s, int32_t seq_id, int32_t prompt_len,
                                      int32_t max_new_tokens) {
@@ -119,7 +138,44 @@ extern "C" int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t*
   int32_t seqs_left = s->max_seqs;
   std::vector<Planned> plan;
 
+  // ---- the comparison policies never split a prompt
+  bool prompt_pass = false;
+  if (s->policy != FSF_POLICY_SPLITFUSE) {
+    const bool prompt_first = s->policy == FSF_POLICY_PROMPT_FIRST;
+    if (!prompt_first) {  // whole-prompt-joins: generations run in every pass
+      for (int32_t slot : s->decodes) {
+        if (budget_left == 0 || seqs_left == 0) break;
+        const Seq& q = s->slab[slot];
+        int64_t need = ceil_div(q.n_cached + 1, B) - ceil_div(q.n_cached, B);
+        if (need > free_left) continue;
+        if (static_cast<int64_t>(q.blocks.size()) + need > max_blocks) return FSF_ERR_INVALID_ARG;
+        plan.push_back({slot, 1, static_cast<int32_t>(need), true, true});
+        free_left -= need;
+        --budget_left;
+        --seqs_left;
+      }
+    }
+    int64_t prompt_tokens = 0;
+    for (int32_t slot : s->prompts) {
+      if (seqs_left == 0) break;
+      const Seq& q = s->slab[slot];
+      const int64_t want = q.prompt_len;  // n_cached is 0: prompts are never split
+      // prompt-first fills a token budget with whole prompts (the first always goes);
+      // whole-prompt-joins knows no token budget
+      if (prompt_first && prompt_tokens > 0 && prompt_tokens + want > s->token_budget) break;
+      const int64_t need = ceil_div(want, B);
+      if (need > free_left) break;  // waits for blocks; no later prompt overtakes it
+      if (need > max_blocks) return FSF_ERR_INVALID_ARG;
+      plan.push_back({slot, static_cast<int32_t>(want), static_cast<int32_t>(need), true, false});
+      free_left -= need;
+      prompt_tokens += want;
+      --seqs_left;
+    }
+    prompt_pass = prompt_first && prompt_tokens > 0;
+  }
   // ---- plan: generations first, one token each, rotation order
+  // (prompt-first: only in a pass without prompts; whole-prompt-joins: done above)
+  if (s->policy == FSF_POLICY_SPLITFUSE || (s->policy == FSF_POLICY_PROMPT_FIRST && !prompt_pass))
   for (int32_t slot : s->decodes) {
     if (budget_left == 0 || seqs_left == 0) break;
     const Seq& q = s->slab[slot];
@@ -132,6 +188,7 @@ extern "C" int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t*
     --seqs_left;
   }
   // ---- plan: prompt tokens fill the rest of the budget, first come first served
+  if (s->policy == FSF_POLICY_SPLITFUSE)
   for (int32_t slot : s->prompts) {
     if (budget_left == 0 || seqs_left == 0) break;
     const Seq& q = s->slab[slot];

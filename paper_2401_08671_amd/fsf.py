@@ -148,6 +148,9 @@ def alloc_workspace(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int, d
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+FSF_POLICY_SPLITFUSE, FSF_POLICY_PROMPT_FIRST, FSF_POLICY_WHOLE_PROMPT_JOINS = 0, 1, 2
+
+
 class Scheduler:
     """fsf_sched_* / fsf_compose_batch (host only)."""
 
@@ -164,6 +167,9 @@ class Scheduler:
         self._descs = np.zeros((max_seqs, 4), dtype=np.int32)
         self._tables = np.zeros((max_seqs, max_blocks), dtype=np.int32)
         self._emits = np.zeros(max_seqs, dtype=np.int32)
+
+    def set_policy(self, policy: int) -> None:
+        _check(lib().fsf_sched_set_policy(self._h, policy), "fsf_sched_set_policy")
 
     def add_request(self, seq_id: int, prompt_len: int, max_new_tokens: int) -> None:
         _check(lib().fsf_sched_add_request(self._h, seq_id, prompt_len, max_new_tokens), "fsf_sched_add_request")

@@ -111,6 +111,20 @@ def stream_requests(n_steps: int = 200, rate: float = 1.0, seed: int = 1005):
     return out
 
 
+def chat_requests(n_requests: int = 512, prompt_mean: float = 2600.0, gen_mean: float = 60.0,
+                  rel_sd: float = 0.3, seed: int = 2024):
+    """Requests of the paper's serving benchmarks (Sec. 4.1, figure captions): prompt and
+    generation lengths normal with the given means and a standard deviation of 30 % of the
+    mean, rounded, at least 1 token (prompts at least 16).  Returns ``[(prompt_len, gen_len)]``."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n_requests):
+        p = int(max(16, round(rng.normal(prompt_mean, rel_sd * prompt_mean))))
+        g = int(max(1, round(rng.normal(gen_mean, rel_sd * gen_mean))))
+        out.append((p, g))
+    return out
+
+
 # --------------------------------------------------------------------------------------
 # descriptors, block tables, tensors
 # --------------------------------------------------------------------------------------

@@ -7,11 +7,17 @@ from paper_2401_08671_amd import fsf
 from paper_2401_08671_amd import workloads as wl
 
 
-def run_both(budget, max_seqs, B, num_blocks, arrivals, n_steps, free_order=None, max_blocks=None):
+POLICY_ID = {"splitfuse": fsf.FSF_POLICY_SPLITFUSE, "prompt_first": fsf.FSF_POLICY_PROMPT_FIRST,
+             "whole_prompt_joins": fsf.FSF_POLICY_WHOLE_PROMPT_JOINS}
+
+
+def run_both(budget, max_seqs, B, num_blocks, arrivals, n_steps, free_order=None, max_blocks=None,
+             policy="splitfuse"):
     if max_blocks is None:
         max_blocks = num_blocks
-    ref = SplitFuseComposer(budget, max_seqs, B, num_blocks, free_order)
+    ref = SplitFuseComposer(budget, max_seqs, B, num_blocks, free_order, policy=policy)
     nat = fsf.Scheduler(budget, max_seqs, B, num_blocks, max_blocks, free_order)
+    nat.set_policy(POLICY_ID[policy])
     steps = 0
     for step in range(n_steps):
         for sid, plen, gen in arrivals.get(step, []):
@@ -38,8 +44,9 @@ def run_both(budget, max_seqs, B, num_blocks, arrivals, n_steps, free_order=None
     return steps
 
 
+@pytest.mark.parametrize("policy", ["splitfuse", "prompt_first", "whole_prompt_joins"])
 @pytest.mark.parametrize("seed", range(8))
-def test_equal_schedules_random_streams(seed):
+def test_equal_schedules_random_streams(seed, policy):
     rng = np.random.default_rng(100 + seed)
     budget = int(rng.integers(4, 300))
     B = int(rng.choice([1, 2, 16, 64]))
@@ -54,7 +61,17 @@ def test_equal_schedules_random_streams(seed):
     # seeds alternate between a roomy pool and a tight one (exercises shrinking/skipping)
     num_blocks = max(tot, 1) if seed % 2 == 0 else max(tot // 6, 8)
     order = rng.permutation(num_blocks)
-    run_both(budget, max_seqs, B, num_blocks, arrivals, 20000, order)
+    run_both(budget, max_seqs, B, num_blocks, arrivals, 20000, order, policy=policy)
+
+
+def test_policy_is_fixed_once_requests_exist():
+    s = fsf.Scheduler(8, 4, 4, 16, max_blocks=8)
+    with pytest.raises(fsf.FsfError):
+        s.set_policy(3)
+    s.set_policy(fsf.FSF_POLICY_PROMPT_FIRST)
+    s.add_request(0, 5, 2)
+    with pytest.raises(fsf.FsfError):
+        s.set_policy(fsf.FSF_POLICY_SPLITFUSE)
 
 
 def test_long_prompt_stream_shape_200_steps():

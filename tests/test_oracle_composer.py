@@ -194,3 +194,72 @@ def test_generations_hold_the_budget_before_new_prompts():
     assert seen[1] == [(0, 1), (1, 1), (2, 1)] and seen[3] == [(0, 3), (1, 3), (2, 3)]
     assert seen[4] == [(3, 0), (4, 0)]                    # generations 0-2 retired after 4 tokens each
     assert seen[7] == [(3, 3), (4, 3)] and comp.n_live() == 0
+
+
+# ---------------------------------------------------------------------------------------
+# the two comparison policies of the scheduling simulator
+def _run(policy, budget, max_seqs, B, num_blocks, arrivals, n_steps=400):
+    c = SplitFuseComposer(budget, max_seqs, B, num_blocks, policy=policy)
+    passes = []
+    for step in range(n_steps):
+        for r in arrivals.get(step, []):
+            c.add_request(*r)
+        if c.n_live() == 0 and step > max(arrivals):
+            break
+        descs, tables, emits = c.compose()
+        passes.append((descs, emits))
+        c.step_done()
+    assert c.n_live() == 0 and c.n_free_blocks() == num_blocks
+    return passes
+
+
+def test_prompt_first_hand_worked_schedule():
+    """budget 8: prompts of 5 and 6 tokens arrive together, each wants 2 tokens.  Pass 0 takes
+    the first prompt only (5 + 6 > 8), pass 1 the second while sequence 0 waits, then both
+    generate together once."""
+    passes = _run("prompt_first", 8, 4, 4, 16, {0: [(0, 5, 2), (1, 6, 2)]})
+    assert [[(n, c, sid) for n, c, _, sid in d] for d, _ in passes] == [
+        [(5, 0, 0)], [(6, 0, 1)], [(1, 5, 0), (1, 6, 1)]]
+    assert [e for _, e in passes] == [[1], [1], [1, 1]]
+
+
+def test_whole_prompt_joins_hand_worked_schedule():
+    """both prompts join the first pass whole (no token budget for prompts), a later prompt of
+    20 tokens joins the running generations in pass 1"""
+    passes = _run("whole_prompt_joins", 8, 4, 4, 32, {0: [(0, 5, 3), (1, 6, 3)], 1: [(2, 20, 1)]})
+    assert [[(n, c, sid) for n, c, _, sid in d] for d, _ in passes] == [
+        [(5, 0, 0), (6, 0, 1)], [(1, 5, 0), (1, 6, 1), (20, 0, 2)], [(1, 6, 0), (1, 7, 1)]]
+
+
+@pytest.mark.parametrize("policy", ["prompt_first", "whole_prompt_joins"])
+@pytest.mark.parametrize("seed", range(4))
+def test_comparison_policies_invariants(policy, seed):
+    rng = np.random.default_rng(500 + seed)
+    budget, B = int(rng.integers(8, 200)), int(rng.choice([1, 4, 16]))
+    arrivals, sid, blocks = {}, 0, 0
+    for step in range(60):
+        for _ in range(rng.poisson(0.4)):
+            plen, gen = int(rng.integers(1, 3 * budget)), int(rng.integers(1, 30))
+            arrivals.setdefault(step, []).append((sid, plen, gen))
+            blocks += -(-(plen + gen) // B)
+            sid += 1
+    if not arrivals:
+        arrivals = {0: [(0, 3, 2)]}
+        blocks = 8
+    prompt_len = {r[0]: r[1] for rs in arrivals.values() for r in rs}
+    passes = _run(policy, budget, 64, B, blocks, arrivals, n_steps=5000)
+    seen_prompt = set()
+    for descs, emits in passes:
+        gens = [d for d in descs if d[1] > 0]
+        prompts = [d for d in descs if d[1] == 0]
+        assert all(n == 1 for n, *_ in gens)
+        for n, c, _, s in prompts:                       # never split, processed exactly once
+            assert n == prompt_len[s] and s not in seen_prompt
+            seen_prompt.add(s)
+        assert all(emits)                                # every entry produces a token
+        assert descs[:len(gens)] == gens                 # generations ahead of prompts
+        if policy == "prompt_first":
+            assert not (gens and prompts)                # a pass is one or the other
+            if len(prompts) > 1:
+                assert sum(n for n, *_ in prompts) <= budget
+    assert seen_prompt == set(prompt_len)

@@ -1,0 +1,95 @@
+"""Scheduling simulator: the library's (native composer) against the oracle's, and pins of the
+oracle's metrics on hand-worked cases."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import policy_sim as ref
+from paper_2401_08671_amd import policy_sim as sim
+from paper_2401_08671_amd import workloads as wl
+
+
+def toy_step_time(descs):
+    """a deterministic stand-in: 1 ms + 1 us per token + 1 ns per cached token"""
+    return 1e-3 + 1e-6 * sum(d[0] for d in descs) + 1e-9 * sum(d[1] for d in descs)
+
+
+def test_hand_worked_single_client_constant_step():
+    """One client, step time 0.5 s, budget 4, SplitFuse: request (prompt 6, 3 tokens) takes two
+    prompt passes (first token at 1.0 s) and two more passes; the next request (prompt 2, 1 token)
+    is sent at 2.0 s and answered at 2.5 s."""
+    reqs = [(6, 3), (2, 1)]
+    log, total, n_passes = ref.simulate("splitfuse", reqs, 1, lambda d: 0.5, 4, 4, 2, 64)
+    assert [r["sent"] for r in log] == [0.0, 2.0]
+    assert log[0]["tokens"] == [1.0, 1.5, 2.0] and log[1]["tokens"] == [2.5]
+    assert total == 2.5 and n_passes == 5
+    m = ref.metrics(reqs, log, total)
+    assert m["throughput_rps"] == 2 / 2.5
+    assert m["mean_request_latency_s"] == (2.0 + 0.5) / 2
+    # prompt targets: 6/512 s and 2/512 s are both missed by far
+    assert m["prompt_sla_met"] == 0.0 and m["effective_throughput_rps_at_2_tok_s"] == 0.0
+    assert m["token_latency_p50_s"] == 0.5 and m["token_latency_p95_s"] == 0.5
+
+
+def test_metrics_ema_and_percentiles_by_hand():
+    """gaps 0.1, 0.1, 1.0, 0.1: EMA (alpha 0.2) = 0.1, 0.1, 0.28, 0.244 -> worst 0.28: meets 2 tok/s
+    (0.5 s) but not 4 tok/s (0.25 s); percentiles of [0.1, 0.1, 0.1, 1.0]: P50 0.1, P90 0.73, P95 0.865"""
+    reqs = [(512, 5)]
+    log = [{"sent": 0.0, "tokens": [0.5, 0.6, 0.7, 1.7, 1.8]}]
+    m = ref.metrics(reqs, log, 2.0)
+    assert m["prompt_sla_met"] == 1.0                       # 0.5 s <= 512/512 s
+    assert m["effective_throughput_rps_at_2_tok_s"] == 0.5
+    assert m["effective_throughput_rps_at_4_tok_s"] == 0.0
+    assert m["token_latency_p50_s"] == pytest.approx(0.1)
+    assert m["token_latency_p90_s"] == pytest.approx(0.1 + 0.9 * 0.7)
+    assert m["token_latency_p95_s"] == pytest.approx(0.1 + 0.9 * 0.85)
+
+
+def test_prompt_first_stalls_running_generations_splitfuse_does_not():
+    """The mechanism behind the paper's tail-latency result (Sec. 4.4): with a step time that grows
+    with the tokens in the pass, a long prompt arriving while another request generates produces one
+    long gap under prompt-first and none under SplitFuse."""
+    reqs = [(64, 40), (4000, 2)]
+    step = lambda d: 0.01 + 1e-4 * sum(x[0] for x in d)
+    worst = {}
+    for policy in ("splitfuse", "prompt_first"):
+        log, total, _ = ref.simulate(policy, reqs, 2, step, 256, 8, 16, 1024)
+        worst[policy] = max(np.diff(log[0]["tokens"]))
+    assert worst["prompt_first"] > 0.4                      # the 4000-token pass: 0.41 s
+    assert worst["splitfuse"] < 0.04                        # never more than a 256-token pass
+
+
+@pytest.mark.parametrize("policy", ["splitfuse", "prompt_first", "whole_prompt_joins"])
+@pytest.mark.parametrize("n_clients", [1, 5])
+def test_native_simulation_equals_oracle(policy, n_clients):
+    reqs = wl.chat_requests(24, prompt_mean=300, gen_mean=12, seed=7)
+    B = 16
+    blocks = sum(-(-(p + g) // B) for p, g in reqs)
+    log, total, n_passes = ref.simulate(policy, reqs, n_clients, toy_step_time, 128, n_clients + 1, B, blocks)
+    sent, tokens, total2, n_passes2 = sim.simulate(policy, reqs, n_clients, toy_step_time, 128, n_clients + 1, B, blocks)
+    assert total2 == total and n_passes2 == n_passes
+    assert sent.tolist() == [r["sent"] for r in log]
+    for a, r in zip(tokens, log):
+        assert a.tolist() == r["tokens"]
+    m_ref, m = ref.metrics(reqs, log, total), sim.metrics(reqs, sent, tokens, total)
+    assert set(m_ref) == set(m)
+    for k in m_ref:
+        assert m[k] == pytest.approx(m_ref[k], rel=1e-12, abs=1e-15), k
+
+
+def test_forward_model_regimes():
+    """few tokens: the pass costs a read of the weights; many: their flops (Sec. 3.1)"""
+    fm = sim.ForwardModel()
+    assert fm.linear_s(1) == fm.linear_s(64) == 26e9 / 6.5e12
+    assert fm.linear_s(4096) == pytest.approx(4096 * 26e9 / 1.05e15)
+    one_decode = fm([(1, 1000, 0, 0)])
+    assert one_decode > fm.linear_s(1) and one_decode < fm.linear_s(1) * 1.1
+
+
+@pytest.mark.gpu
+def test_measured_attention_runs_a_small_closed_loop():
+    reqs = wl.chat_requests(6, prompt_mean=700, gen_mean=6, seed=3)
+    out = sim.run("splitfuse", reqs, 3, token_budget=512, measured=True)
+    assert out["requests"] == 6 and out["attention_gpu_s_one_layer_total"] > 0
+    assert math.isfinite(out["token_latency_p95_s"])
