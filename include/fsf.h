@@ -106,7 +106,10 @@ int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new,
 /*
  * Bytes of device workspace fsf_ragged_attention needs for a pass of at most n_seqs
  * sequences, n_tokens tokens and max_blocks table columns.  Never zero (a small plan
- * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.
+ * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.  On the
+ * matrix-core path it holds the work tables, the partial results of generation rows whose
+ * keys were split (at most n_seqs + 8192 units) and of prompt-chunk tiles whose keys were
+ * split (at most 512 units of 256 rows, 71 MB).
  */
 size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_seqs,
                                             int32_t n_tokens, int32_t max_blocks);
@@ -132,8 +135,10 @@ size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_s
  * Tuning knobs (environment, read per call; defaults suit MI355X): FSF_DECODE_TARGET_WAVES
  * (about how many generation-row wave units a pass is cut into, default 16384) and
  * FSF_DECODE_MIN_ITEM_BLOCKS (no KV split leaves fewer cache blocks than this per unit,
- * default 16).
- * Fast paths: bf16/f16 with head_dim 128 and block_size a multiple of 32; every other
+ * default 16); FSF_PREFILL_NO_SPLIT (set: prompt-chunk tiles are never split along their keys)
+ * and FSF_PREFILL_SPLIT_UNITS (the number of compute units the split rule assumes, default
+ * the device's).
+ * Fast paths: bf16/f16 with head_dim 128 and block_size 64 * 2^k; every other
  * supported shape (any dtype, head_dim <= 256 and a multiple of 4/sizeof-ratio, any
  * block_size) runs a generic fp32 kernel.
  */
