@@ -1,0 +1,95 @@
+"""The rest of a decoder layer at the ragged-batch shape: how long the weight GEMMs of a forward
+pass take as a function of the number of forward tokens, measured on the GPU.
+
+This library contains the attention step of a pass only.  The paper's two observations about a
+whole pass (Sec. 3.1) are about the other part: with few tokens the pass is bound by reading the
+weights, with many by their flops, and the transition fixes a sensible token budget.  To put the
+attention step in that context, and to give the scheduling simulator a measured duration for
+the linear part instead of a model, this module times the layer's GEMMs (QKV, output projection,
+gated MLP) with random bf16 weights of a Llama-2-13B-shaped layer through the vendor GEMM library
+(torch.matmul: hipBLASLt) for a grid of token counts.  Nothing here is part of the attention path.
+
+    python -m paper_2401_08671_amd.layer_model        # prints one JSON object
+"""
+from __future__ import annotations
+
+import bisect
+import json
+import sys
+
+import torch
+
+SHAPE_13B = dict(hidden=5120, n_heads=40, head_dim=128, mlp=13824, n_layers=40)
+TOKEN_GRID = (1, 16, 32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 8192, 16384)
+
+
+def layer_gemm_flops(shape=SHAPE_13B) -> int:
+    """flops of the layer's GEMMs per token"""
+    h, qkv, mlp = shape["hidden"], 3 * shape["n_heads"] * shape["head_dim"], shape["mlp"]
+    return 2 * (h * qkv + h * h + h * 2 * mlp + mlp * h)
+
+
+def layer_weight_bytes(shape=SHAPE_13B) -> int:
+    return layer_gemm_flops(shape)  # 2 bytes per weight, 2 flops per weight and token
+
+
+def measure_linear(shape=SHAPE_13B, grid=TOKEN_GRID, reps: int = 5, device="cuda"):
+    """[(tokens, seconds for the GEMMs of ONE layer)], fastest of reps; weights of three layers
+    are cycled so that a pass never finds its weights in cache"""
+    h, qkv, mlp = shape["hidden"], 3 * shape["n_heads"] * shape["head_dim"], shape["mlp"]
+    g = torch.Generator(device=device).manual_seed(5)
+    mk = lambda *s: (torch.randn(*s, generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    layers = [dict(wqkv=mk(h, qkv), wo=mk(h, h), wgu=mk(h, 2 * mlp), wd=mk(mlp, h)) for _ in range(3)]
+    out = []
+    for T in grid:
+        x = mk(T, h)
+        best = float("inf")
+        for r in range(reps + 2):
+            w = layers[r % 3]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            a = x @ w["wqkv"]
+            b = a[:, :h] @ w["wo"]
+            c = b @ w["wgu"]
+            d = (torch.nn.functional.silu(c[:, :mlp]) * c[:, mlp:]) @ w["wd"]
+            e1.record()
+            torch.cuda.synchronize()
+            if r >= 2:
+                best = min(best, e0.elapsed_time(e1) * 1e-3)
+        del a, b, c, d
+        out.append((T, best))
+    return out
+
+
+class MeasuredLinear:
+    """seconds of the linear part of a pass of n tokens: table of measure_linear, interpolated"""
+
+    def __init__(self, table, n_layers: int):
+        self.tokens = [t for t, _ in table]
+        self.secs = [s for _, s in table]
+        self.n_layers = n_layers
+
+    def __call__(self, n_tokens: int) -> float:
+        i = bisect.bisect_left(self.tokens, n_tokens)
+        if i == 0:
+            per_layer = self.secs[0]
+        elif i == len(self.tokens):  # beyond the grid: flops-bound, scale the last point
+            per_layer = self.secs[-1] * n_tokens / self.tokens[-1]
+        else:
+            t0, t1, s0, s1 = self.tokens[i - 1], self.tokens[i], self.secs[i - 1], self.secs[i]
+            per_layer = s0 + (s1 - s0) * (n_tokens - t0) / (t1 - t0)
+        return self.n_layers * per_layer
+
+
+def main():
+    assert torch.cuda.is_available(), "needs a GPU"
+    table = measure_linear()
+    fl, by = layer_gemm_flops(), layer_weight_bytes()
+    rows = [dict(tokens=T, layer_ms=s * 1e3, tflops=T * fl / s / 1e12, weight_gbs=by / s / 1e9,
+                 tokens_per_s_whole_model=T / (s * SHAPE_13B["n_layers"])) for T, s in table]
+    json.dump(dict(shape=SHAPE_13B, gemm_flops_per_token_per_layer=fl, weight_bytes_per_layer=by, rows=rows), sys.stdout)
+    print()
+
+
+if __name__ == "__main__":
+    main()

@@ -21,9 +21,10 @@ runs: the attention part of every layer is either *measured* (``MeasuredAttentio
 pass's KV append and ragged attention are executed on the GPU through the library on
 buffers of the pass's real shape and block tables, and timed with events) or taken from the
 rates the kernels reach; the rest of the layer (weight GEMMs), which this library does not
-contain, is a two-regime model: reading the weights once, or the flops of the forward
-tokens, whichever takes longer (Sec. 3.1: few tokens are bound by weight reads, many by
-compute).
+contain, is either measured as well (``layer_model``: the layer's GEMMs through the vendor
+library at the pass's token count) or a two-regime model: reading the weights once, or the
+flops of the forward tokens, whichever takes longer (Sec. 3.1: few tokens are bound by weight
+reads, many by compute).
 
     python -m paper_2401_08671_amd.policy_sim [--clients 16] [--requests 128] [--analytic]
 """
@@ -140,8 +141,11 @@ class ForwardModel:
     matrix_rate: float = 1.05e15
     fixed_s: float = 100e-6          # launches and host work per pass
     attention: object = None
+    linear: object = None            # None: the two-regime model; else a callable n_tokens -> seconds
 
     def linear_s(self, n_tokens: int) -> float:
+        if self.linear is not None:
+            return self.linear(n_tokens)
         return max(self.weight_bytes / self.hbm_rate, n_tokens * self.linear_flops_per_token / self.matrix_rate)
 
     def attention_layer_s(self, descs) -> float:
@@ -212,6 +216,9 @@ class MeasuredAttention:
         return best
 
 
+_LINEAR_TABLE = None
+
+
 def run(policy: str, requests, n_clients: int, token_budget: int, measured: bool, block_size: int = 64):
     need = sum(-(-(p + g) // block_size) for p, g in sorted(requests, key=lambda r: -(r[0] + r[1]))[:n_clients])
     num_blocks = need + 64
@@ -219,6 +226,11 @@ def run(policy: str, requests, n_clients: int, token_budget: int, measured: bool
     model = ForwardModel()
     on_pass = None
     if measured:
+        from . import layer_model
+        global _LINEAR_TABLE
+        if _LINEAR_TABLE is None:   # the layer's GEMMs, timed once per process
+            _LINEAR_TABLE = layer_model.measure_linear()
+        model.linear = layer_model.MeasuredLinear(_LINEAR_TABLE, model.n_layers)
         # whole-prompt policies can put every client's prompt into one pass
         max_tokens = max(token_budget, sum(sorted((p for p, _ in requests), reverse=True)[:n_clients]) + n_clients)
         att = MeasuredAttention(model, block_size, num_blocks, max_blocks, max_seqs=n_clients + 1,
@@ -230,7 +242,8 @@ def run(policy: str, requests, n_clients: int, token_budget: int, measured: bool
                                              num_blocks=num_blocks, max_blocks=max_blocks, on_pass=on_pass)
     out = metrics(requests, sent, tokens, total)
     out.update(policy=policy, clients=n_clients, passes=n_passes,
-               attention="measured on the GPU" if measured else "from the kernels' rates")
+               attention="measured on the GPU" if measured else "from the kernels' rates",
+               linear_part="GEMMs measured on the GPU" if measured else "two-regime model")
     if measured:
         out["attention_gpu_s_one_layer_total"] = model.attention.total_gpu_s
     return out
