@@ -12,6 +12,9 @@ length matters in addition to the token count:
                sequence with the same number of cached tokens
   budget       forward tokens 64 .. 8192 for (a) one prompt chunk at n_cached 0,
                (b) generation rows at n_cached 1024, (c) the half/half SplitFuse mix
+  block_size   the cache block size (Sec. 2.1: non-contiguous fixed-size blocks) against the
+               HBM rate of 512 generation rows over 2048 cached tokens and the matrix rate of
+               one 4096-row chunk over 4096 cached tokens, physical blocks randomly permuted
 
     python -m paper_2401_08671_amd.sweeps            # prints one JSON object
 """
@@ -23,7 +26,7 @@ import sys
 import torch
 
 from . import workloads as wl
-from .harness import DeviceStep
+from .harness import DeviceStep, algorithmic_work
 
 
 def time_spec(spec: wl.BatchSpec, steps: int = 10, warmup: int = 2) -> float:
@@ -42,13 +45,13 @@ def time_spec(spec: wl.BatchSpec, steps: int = 10, warmup: int = 2) -> float:
     return e0.elapsed_time(e1) / steps
 
 
-def spec_of(seqs, name):
-    return wl.BatchSpec(name, 40, 40, 128, 64, "bf16", seqs, seed=4242)
+def spec_of(seqs, name, block=64):
+    return wl.BatchSpec(name, 40, 40, 128, block, "bf16", seqs, seed=4242)
 
 
 def main():
     assert torch.cuda.is_available(), "sweeps need a GPU"
-    out = {"shape": "Hq=40 Hkv=40 d=128 block=64 bf16, one layer", "composition": [], "budget": []}
+    out = {"shape": "Hq=40 Hkv=40 d=128 block=64 bf16, one layer", "composition": [], "budget": [], "block_size": []}
     T, ctx = 2048, 1024
     n_seq = 1
     while n_seq <= T:
@@ -65,6 +68,14 @@ def main():
             ms = time_spec(spec_of(seqs, f"budget-{kind}-{budget}"))
             row[kind] = {"ms": ms, "tokens_per_s": budget / (ms * 1e-3)}
         out["budget"].append(row)
+    for block in (64, 128, 256):
+        dec = spec_of([(1, 2048)] * 512, f"block-{block}-decodes", block)
+        pre = spec_of([(4096, 4096)], f"block-{block}-chunk", block)
+        ms_d, ms_p = time_spec(dec), time_spec(pre)
+        wd, wp = algorithmic_work(dec), algorithmic_work(pre)
+        out["block_size"].append({"block_size": block, "decodes_ms": ms_d,
+                                  "decodes_GBs": wd["total_bytes"] / (ms_d * 1e-3) / 1e9,
+                                  "chunk_ms": ms_p, "chunk_TFLOPs": wp["prefill_flops"] / (ms_p * 1e-3) / 1e12})
     json.dump(out, sys.stdout)
     print()
 
