@@ -152,6 +152,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5, 6])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measurement of the device's ceilings")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the attention step shards by KV head with no "
@@ -232,6 +233,16 @@ def main():
                          "TFLOPs": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 if pre_ms else 0.0,
                          "frac_mfma": work["prefill_flops"] / (pre_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if pre_ms else 0.0},
     }
+    if not args.no_ceilings:
+        # what the device sustains with nothing else in the way (scattered 16 KB tiles streamed with
+        # non-temporal loads; a register-resident bf16 MFMA loop on normally distributed operands)
+        from paper_2401_08671_amd import ceilings
+        c = ceilings.measure(hbm_bytes=4 << 30)
+        ceil = (c["hbm_read_scattered_16KB_tiles_nontemporal_loads"]["GBs"] if hbm_bound
+                else c["mfma_bf16_normal_operands"]["TFLOPs"])
+        line["roofline"]["measured_ceiling"] = ceil
+        line["roofline"]["frac_of_measured_ceiling"] = achieved / ceil
+        line["measured_ceilings"] = c
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(ds, k0, v0)
         line["cpu_baseline"] = base

@@ -232,6 +232,25 @@ typedef enum {
 int fsf_profile_enable(int on);
 int fsf_profile_read(double* ms_out, int64_t* launches_out);
 
+/*
+ * Measurement aids: what the device sustains with nothing else in the way, to set beside the
+ * published peaks the roofline fractions use.  Both run synchronously (they time themselves with
+ * HIP events on hip_stream and wait) and write only to `scratch` (device, >= 4096 bytes).
+ *   fsf_ceiling_mfma_bf16  a register-resident loop of 32x32x16 bf16 MFMAs, two waves per SIMD;
+ *                          `operands` (device, >= 16 MiB, read once) supplies the fragment values:
+ *                          the rate depends on them, because the clock the chip holds does.
+ *                          iters: MFMAs per wave / 8.  Outputs (host): TFLOP/s and the shader clock
+ *                          in MHz seen inside the kernel.
+ *   fsf_ceiling_hbm_read   every wave streams 32 scattered 16 KB tiles of `buf` (device, `bytes`
+ *                          long, >= 512 KiB; the largest power-of-two tile count that fits is
+ *                          used), with non-temporal loads if nontemporal != 0.  Output: GB/s.
+ * Return FSF_ERR_INVALID_ARG on null or too small buffers, FSF_ERR_HIP on a runtime error.
+ */
+int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters, void* scratch,
+                          double* tflops_out, double* mhz_out, void* hip_stream);
+int fsf_ceiling_hbm_read(const void* buf, int64_t bytes, int32_t nontemporal, void* scratch,
+                         double* gbs_out, void* hip_stream);
+
 /* Introspection (host): free blocks, live sequences (waiting prompts + generations). */
 int64_t fsf_sched_free_blocks(const fsf_sched* s);
 int32_t fsf_sched_live_seqs(const fsf_sched* s);
