@@ -123,8 +123,9 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
                                             const T* __restrict__ kc, const T* __restrict__ vc,
                                             T* __restrict__ out, int unit, int lane) {
   const int n = lane & 15, kg = lane >> 4;
-  const int item = unit / p.n_kv_heads;
-  const int hk = unit - item * p.n_kv_heads;
+  const int slot = unit / p.n_kv_heads;  // launch order: items with the most cache blocks first
+  const int hk = unit - slot * p.n_kv_heads;
+  const int item = f.dec_order[slot];
   const int s = f.dec_item_seq[item];  // written by the planning kernel
   const int split = item - f.dec_item_start[s];
   const fsf_seq_desc sd = p.descs[s];

@@ -72,7 +72,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace sections of the matrix-core path, in order.
 struct WsLayout {
-  size_t dec_item_start, pre_tile_start, dec_item_seq, pre_tile_seq, split_seqs, part_ml, part_acc, pre_part, total;
+  size_t dec_item_start, pre_tile_start, dec_item_seq, dec_order, pre_tile_seq, split_seqs, part_ml, part_acc, pre_part, total;
 };
 
 WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
@@ -85,6 +85,8 @@ WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
   w.pre_tile_start = off;
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
   w.dec_item_seq = off;
+  off += align256(items_cap * sizeof(int32_t));
+  w.dec_order = off;
   off += align256(items_cap * sizeof(int32_t));
   w.pre_tile_seq = off;
   off += align256(tiles_cap * sizeof(int32_t));
@@ -244,6 +246,7 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.dec_item_start = (int32_t*)(ws + w.dec_item_start);
   f.pre_tile_start = (int32_t*)(ws + w.pre_tile_start);
   f.dec_item_seq = (int32_t*)(ws + w.dec_item_seq);
+  f.dec_order = (int32_t*)(ws + w.dec_order);
   f.pre_tile_seq = (int32_t*)(ws + w.pre_tile_seq);
   f.split_seqs = (int32_t*)(ws + w.split_seqs);
   f.part_ml = (float*)(ws + w.part_ml);

@@ -97,6 +97,7 @@ struct FastPlan {
   int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of decode items per sequence
   int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
   int32_t* dec_item_seq;    // [items]  sequence index of every decode item
+  int32_t* dec_order;       // [items]  launch slot -> decode item, items with the most cache blocks first
   int32_t* pre_tile_seq;    // [tiles]  sequence index of every prefill tile
   int32_t* split_seqs;      // [n_split_seqs] sequences whose generation row was cut into > 1 item
   float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
