@@ -251,6 +251,19 @@ int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t i
 int fsf_ceiling_hbm_read(const void* buf, int64_t bytes, int32_t nontemporal, void* scratch,
                          double* gbs_out, void* hip_stream);
 
+/*
+ * Introspection (host only, no device call): how fsf_ragged_attention would cut the prompt
+ * chunks of a pass into workgroups on a device with compute_units_assumed compute units.  A
+ * chunk is tiled 256 rows at a time (tiles are numbered in descriptor order); a tile may be
+ * cut into parts along its keys (a tile that would outlast the rest of the pass, or the tiles
+ * of a last round of workgroups that is at most half full).  Writes up to cap entries of
+ * (tile, part, n_parts, slab) in start order (slab: number of the (tile, part) in the
+ * partial-result buffer, -1 for an unsplit tile); one workgroup per entry and query head.
+ * Returns the number of entries, or -1 on invalid arguments.
+ */
+int32_t fsf_plan_prefill_groups(const fsf_attn_cfg* cfg, const fsf_seq_desc* descs_host, int32_t n_seqs,
+                                int32_t compute_units_assumed, int32_t* groups_out, int32_t cap);
+
 /* Introspection (host): free blocks, live sequences (waiting prompts + generations). */
 int64_t fsf_sched_free_blocks(const fsf_sched* s);
 int32_t fsf_sched_live_seqs(const fsf_sched* s);

@@ -16,26 +16,12 @@ namespace {
 constexpr int kThreads = 64 * kPrefillWaves;
 constexpr int kUnitsPerGroup = kThreads / 64;  // generation-row units (waves) per workgroup
 
-// Prefill workgroups are numbered so that the tiles with the most keys to visit (the last
-// rows of a chunk) start first.  The tiles started last (tile index < pre_split_tiles) come as
-// pre_parts workgroups each, one per part of the key range.
-__device__ __forceinline__ void prefill_block_to_work(const Pass& p, const FastPlan& f, int block,
-                                                      int& tile, int& hq, int& part) {
-  const int whole = (f.n_pre_tiles - f.pre_split_tiles) * p.n_q_heads;  // workgroups of unsplit tiles
-  if (block < whole) {
-    const int t = block / p.n_q_heads;
-    hq = block - t * p.n_q_heads;
-    tile = f.n_pre_tiles - 1 - t;
-    part = 0;
-  } else {
-    const int idx = block - whole;
-    const int per_tile = f.pre_parts * p.n_q_heads;
-    const int t = idx / per_tile;
-    const int r = idx - t * per_tile;
-    part = r / p.n_q_heads;
-    hq = r - part * p.n_q_heads;
-    tile = f.pre_split_tiles - 1 - t;
-  }
+// Prefill workgroups: (tile, part) groups in their start order, query heads innermost.
+__device__ __forceinline__ PrefillWork prefill_block_to_work(const Pass& p, const FastPlan& f, int block,
+                                                             int& hq) {
+  const int g = block / p.n_q_heads;
+  hq = block - g * p.n_q_heads;
+  return prefill_group_to_work(g, f.n_pre_tiles, f.split);
 }
 
 #ifdef FSF_CLOCK_PROBE
@@ -54,12 +40,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastP
                                                                  const T* __restrict__ vc,
                                                                  T* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
-  int tile, hq, part;
-  prefill_block_to_work(p, f, blockIdx.x, tile, hq, part);
+  int hq;
+  const PrefillWork w = prefill_block_to_work(p, f, blockIdx.x, hq);
 #ifdef FSF_CLOCK_PROBE
   const uint64_t c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
 #endif
-  prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, part, (lds_char*)lds);
+  prefill_tile<DT, T>(p, f, q, kc, vc, out, w, hq, (lds_char*)lds);
 #ifdef FSF_CLOCK_PROBE
   const uint64_t c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
   if (threadIdx.x == 0 && blockIdx.x < kClockProbeSlots) {
@@ -100,9 +86,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
   const bool is_prefill = pre_upto > pre_before;
   const int idx = is_prefill ? pre_before : b - pre_before;
   if (is_prefill) {  // uniform per workgroup
-    int tile, hq, part;
-    prefill_block_to_work(p, f, idx, tile, hq, part);  // the fused grid is launched without split tiles
-    prefill_tile<DT, T>(p, f, q, kc, vc, out, tile, hq, part, (lds_char*)lds);
+    int hq;
+    const PrefillWork w = prefill_block_to_work(p, f, idx, hq);  // the fused grid is launched without split tiles
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, w, hq, (lds_char*)lds);
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;
@@ -129,8 +115,7 @@ hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, 
                                const void* v_cache, void* out, hipStream_t stream) {
   if (f.n_pre_tiles == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_PREFILL, stream);
-  const unsigned grid =
-      (unsigned)(f.n_pre_tiles - f.pre_split_tiles + f.pre_split_tiles * f.pre_parts) * p.n_q_heads;
+  const unsigned grid = (unsigned)prefill_groups(f.n_pre_tiles, f.split) * p.n_q_heads;
   FSF_LAUNCH(attn_prefill_kernel, grid)
   return hipGetLastError();
 }

@@ -139,22 +139,24 @@ __global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __rest
 }
 
 // Split prompt-chunk tiles: one wave per (row of a split tile, query head) combines the
-// pre_parts partial results of that row in the same way; lanes own two output columns each.
+// partial results of that row's parts in the same way; lanes own two output columns each.
 template <typename T>
 __global__ __launch_bounds__(64) void prefill_merge_kernel(Pass p, FastPlan f, T* __restrict__ out) {
   const int hq = blockIdx.x % p.n_q_heads;
-  const int trow = blockIdx.x / p.n_q_heads;  // tile * kPrefillTileM + row inside the tile
-  const int tile = trow / kPrefillTileM;
-  const int s = f.pre_tile_seq[tile];
-  const int i = (tile - f.pre_tile_start[s]) * kPrefillTileM + trow % kPrefillTileM;  // row of the chunk
+  const int jrow = blockIdx.x / p.n_q_heads;  // split tile number * kPrefillTileM + row inside the tile
+  const PrefillWork w = prefill_split_tile(jrow / kPrefillTileM, f.split);
+  const int row = jrow % kPrefillTileM;
+  const int s = f.pre_tile_seq[w.tile];
+  const int i = (w.tile - f.pre_tile_start[s]) * kPrefillTileM + row;  // row of the chunk
   if (i >= p.descs[s].n_new) return;
   const int lane = threadIdx.x;
-  const float* part = f.pre_part + ((int64_t)trow * p.n_q_heads + hq) * f.pre_parts * kPrefillPartRowFloats;
+  const int64_t part_stride = (int64_t)kPrefillTileM * p.n_q_heads * kPrefillPartRowFloats;  // slab to slab
+  const float* part = f.pre_part + (((int64_t)w.slab * kPrefillTileM + row) * p.n_q_heads + hq) * kPrefillPartRowFloats;
   float m = -INFINITY;
-  for (int k = 0; k < f.pre_parts; ++k) m = fmaxf(m, part[k * kPrefillPartRowFloats + kHeadDim]);
+  for (int k = 0; k < w.n_parts; ++k) m = fmaxf(m, part[k * part_stride + kHeadDim]);
   float l = 0.f, a0 = 0.f, a1 = 0.f;
-  for (int k = 0; k < f.pre_parts; ++k) {
-    const float* pk = part + k * kPrefillPartRowFloats;
+  for (int k = 0; k < w.n_parts; ++k) {
+    const float* pk = part + k * part_stride;
     const float w = fast_exp2(pk[kHeadDim] - m);
     l += pk[kHeadDim + 1] * w;
     const float2 a = *reinterpret_cast<const float2*>(pk + lane * 2);
@@ -187,9 +189,10 @@ hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStr
 }
 
 hipError_t launch_prefill_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream) {
-  if (f.pre_split_tiles == 0 || f.pre_parts < 2) return hipSuccess;
+  const int n_split = f.split.n_heavy + f.split.tail_tiles;
+  if (n_split == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_MERGE, stream);
-  const unsigned grid = (unsigned)f.pre_split_tiles * kPrefillTileM * p.n_q_heads;
+  const unsigned grid = (unsigned)n_split * kPrefillTileM * p.n_q_heads;
   if (p.dtype == FSF_BF16)
     prefill_merge_kernel<bf16_t><<<grid, 64, 0, stream>>>(p, f, (bf16_t*)out);
   else

@@ -145,14 +145,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 
-// One workgroup of 64*kPrefillWaves threads: tile = index into the pass's prefill tiles,
-// hq = query head, part = which part of the tile's key range (0 unless the tile is split),
-// lds = kPrefillLdsBytes of LDS.
+// One workgroup of 64*kPrefillWaves threads: work = tile (index into the pass's prefill tiles),
+// which part of how many of the tile's key range, and where a partial result goes; hq = query
+// head, lds = kPrefillLdsBytes of LDS.
 template <int DT, typename T>
 __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
                                              const T* __restrict__ q, const T* __restrict__ kc,
-                                             const T* __restrict__ vc, T* __restrict__ out, int tile,
-                                             int hq, int part, lds_char* lds) {
+                                             const T* __restrict__ vc, T* __restrict__ out,
+                                             const PrefillWork& work, int hq, lds_char* lds) {
   // values that are the same in every lane are told so (the compiler cannot always tell)
   auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane(x); };
   auto uni64 = [&](uint64_t x) { return ((uint64_t)uni((uint32_t)(x >> 32)) << 32) | uni((uint32_t)x); };
@@ -160,6 +160,7 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
   const int wave = uni(tid >> 6), lane = tid & 63;
   const int l32 = lane & 31, hg = lane >> 5;
   const int hk = hq / p.group;
+  const int tile = work.tile;
   const int s = f.pre_tile_seq[tile];  // written by the planning kernel
   const fsf_seq_desc sd = p.descs[s];
   const int B = p.block_size;
@@ -174,10 +175,10 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
   int key_begin = lo_t & ~(kKeysPerStep - 1);
   int n_steps = (hi_t - key_begin) / kKeysPerStep + 1;  // >= 1
   // a split tile: this workgroup walks part `part` of the steps and stores a partial result
-  const bool is_split = tile < f.pre_split_tiles;
+  const bool is_split = work.slab >= 0;
   if (is_split) {
-    const int s_lo = (int)((int64_t)part * n_steps / f.pre_parts);
-    const int s_hi = (int)((int64_t)(part + 1) * n_steps / f.pre_parts);
+    const int s_lo = (int)((int64_t)work.part * n_steps / work.n_parts);
+    const int s_hi = (int)((int64_t)(work.part + 1) * n_steps / work.n_parts);
     key_begin += s_lo * kKeysPerStep;
     n_steps = s_hi - s_lo;  // >= 1: the host keeps parts at kPrefillMinPartSteps steps or more
   }
@@ -238,8 +239,8 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
     // Q^T fragment t of the lane is d chunk 2t + hg (8 elements); its output columns are
     // 32 mt + 8 rq + 4 hg + 0..3
     const uint64_t qa = reinterpret_cast<uint64_t>(q + row + 8 * hg);
-    // a split tile's rows go to the partial-result buffer: [tile row, head, part][136 floats]
-    const int64_t prow = (((int64_t)tile * kPrefillTileM + (ic - i0)) * p.n_q_heads + hq) * f.pre_parts + part;
+    // a split tile's rows go to the partial-result buffer: [slab, row of the tile, head][136 floats]
+    const int64_t prow = ((int64_t)work.slab * kPrefillTileM + (ic - i0)) * p.n_q_heads + hq;
     const uint64_t oa = is_split ? reinterpret_cast<uint64_t>(f.pre_part + prow * kPrefillPartRowFloats + 4 * hg)
                                  : reinterpret_cast<uint64_t>(out + row + 4 * hg);
     q_ptr[2 * rb] = (uint32_t)qa;

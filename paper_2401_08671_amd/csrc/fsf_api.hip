@@ -6,6 +6,8 @@
 #include <string.h>
 
 #include <algorithm>
+#include <utility>
+#include <vector>
 
 #include "fsf_internal.h"
 
@@ -122,44 +124,85 @@ int compute_units() {
   return n;
 }
 
-// Prompt-chunk workgroups (tile x head) are started heaviest first, one per compute unit at a
-// time.  When the last round of them is less than half full (or there is less than one round),
-// the tiles of that round are cut into parts along their keys so that the round fills the
-// chip: f.pre_split_tiles tiles (the last to be started: tile indices 0 ..), f.pre_parts parts each.
-void choose_prefill_split(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs, fsf::FastPlan& f) {
-  f.pre_split_tiles = 0;
-  f.pre_parts = 1;
-  const int H = c->n_q_heads;
-  const int cus = env_int("FSF_PREFILL_SPLIT_UNITS", compute_units());  // tests force splits with a large value
-  if ((c->flags & FSF_FLAG_FUSED_LAUNCH) || f.n_pre_tiles == 0 || getenv("FSF_PREFILL_NO_SPLIT")) return;
-  const int64_t groups = (int64_t)f.n_pre_tiles * H;
-  const int64_t tail = groups % cus;  // workgroups of the last, partial round
-  if (tail == 0 || 2 * tail > cus) return;
-  // whole tiles only, and all of the partial round: an unsplit workgroup left in it would
-  // last as long as the round did before
-  int split_tiles = (int)((tail + H - 1) / H);
-  if (split_tiles > f.n_pre_tiles) split_tiles = f.n_pre_tiles;
-  int parts = std::max(2, (int)((cus + (int64_t)split_tiles * H / 2) / ((int64_t)split_tiles * H)));
-  if ((int64_t)split_tiles * H * parts > fsf::kMaxPrefillSplitUnits)
-    parts = (int)(fsf::kMaxPrefillSplitUnits / ((int64_t)split_tiles * H));
-  // no part shorter than kPrefillMinPartSteps steps: look at the shortest of the tiles to split
-  int tile = 0, min_steps = 1 << 30;
-  for (int32_t s = 0; s < n_seqs && tile < split_tiles; ++s) {
-    if (h[s].n_new == 1) continue;
-    const int n_tiles = (h[s].n_new + fsf::kPrefillTileM - 1) / fsf::kPrefillTileM;
-    for (int t = 0; t < n_tiles && tile < split_tiles; ++t, ++tile) {
-      const int i0 = t * fsf::kPrefillTileM;
-      const int i1 = std::min(i0 + fsf::kPrefillTileM, h[s].n_new);
-      int lo, hi, tmp;
-      fsf::visible_range(h[s].n_cached + i0, c->window, lo, tmp);
-      fsf::visible_range(h[s].n_cached + i1 - 1, c->window, tmp, hi);
-      min_steps = std::min(min_steps, (hi - (lo & ~63)) / 64 + 1);
-    }
+// Which prompt-chunk tiles are cut along their keys (see PrefillSplit).  n_steps[t] = 64-key
+// steps of tile t.  Workgroups (tile x head) take one compute unit each.
+//   heavy: with an even spread every unit would work `even` steps; a tile with more steps than
+//          that would run on after everything else has finished, so it is cut into parts of at
+//          most `even` steps, or, when all workgroups fit one round anyway, into as many parts
+//          as its share of the units (never shorter than kPrefillMinPartSteps); the
+//          kMaxHeavyTiles longest such tiles are taken
+//   tail:  when the last round of workgroups is at most half full, the tiles of that round are
+//          cut into as many parts as fill the round
+fsf::PrefillSplit plan_prefill_split(const std::vector<int>& n_steps, int H, int cus, bool allow) {
+  fsf::PrefillSplit sp = {};
+  const int n_tiles = (int)n_steps.size();
+  if (!allow || n_tiles == 0) return sp;
+  int64_t total = 0;
+  for (int s : n_steps) total += s;
+  const int64_t even = std::max<int64_t>((total * H + cus - 1) / cus, fsf::kPrefillMinPartSteps);
+  int budget = fsf::kMaxPrefillSplitUnits / H;  // (tile, part) groups with partial results
+  const bool one_round = (int64_t)n_tiles * H <= cus;
+  // ---- heavy tiles
+  std::vector<int> order(n_tiles);
+  for (int t = 0; t < n_tiles; ++t) order[t] = t;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return n_steps[a] > n_steps[b]; });
+  std::vector<std::pair<int, int>> heavy;  // (tile, parts)
+  for (int t : order) {
+    if ((int)heavy.size() == fsf::kMaxHeavyTiles || n_steps[t] <= even) break;
+    // several rounds of workgroups: parts of at most the even share.  Less than one round: every
+    // tile gets the share of the units that its steps are of all steps, rounded down, so that
+    // the parts still fit one round
+    int64_t want = one_round ? (int64_t)cus * n_steps[t] / (total * H) : (n_steps[t] + even - 1) / even;
+    int parts = (int)std::min<int64_t>(want, 16);
+    parts = std::min(parts, n_steps[t] / fsf::kPrefillMinPartSteps);
+    parts = std::min(parts, budget);
+    if (parts < 2) continue;
+    heavy.push_back({t, parts});
+    budget -= parts;
   }
+  std::sort(heavy.begin(), heavy.end(), [](auto a, auto b) { return a.first > b.first; });  // descending tile index
+  sp.n_heavy = (int)heavy.size();
+  for (int k = 0; k < sp.n_heavy; ++k) {
+    sp.heavy_tile[k] = heavy[k].first;
+    sp.heavy_parts[k] = heavy[k].second;
+  }
+  // ---- tail tiles: all of the partial round (an unsplit workgroup left in it would last as long
+  // as the round did before), whole tiles only
+  const int64_t groups = fsf::prefill_groups(n_tiles, sp);
+  const int64_t tail = groups * H % cus;
+  const int n_plain = n_tiles - sp.n_heavy;
+  if (tail == 0 || 2 * tail > cus || n_plain == 0 || groups * H < cus) return sp;
+  const int tail_tiles = (int)std::min<int64_t>((tail + H - 1) / H, n_plain);
+  int parts = std::max(2, (int)((cus + (int64_t)tail_tiles * H / 2) / ((int64_t)tail_tiles * H)));
+  int min_steps = 1 << 30;
+  sp.tail_tiles = tail_tiles;  // for prefill_nth_plain_tile below
+  for (int a = 0; a < tail_tiles; ++a) min_steps = std::min(min_steps, n_steps[fsf::prefill_nth_plain_tile(a, sp)]);
   parts = std::min(std::min(parts, 16), min_steps / fsf::kPrefillMinPartSteps);
-  if (parts < 2) return;
-  f.pre_split_tiles = split_tiles;
-  f.pre_parts = parts;
+  parts = std::min(parts, budget / tail_tiles);
+  if (parts < 2) {
+    sp.tail_tiles = 0;
+    return sp;
+  }
+  sp.tail_parts = parts;
+  return sp;
+}
+
+// 64-key steps of every prompt-chunk tile of the pass, in tile order (sequence order, then rows)
+std::vector<int> prefill_tile_steps_of(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs) {
+  std::vector<int> steps;
+  for (int32_t s = 0; s < n_seqs; ++s) {
+    if (h[s].n_new == 1) continue;
+    for (int i0 = 0; i0 < h[s].n_new; i0 += fsf::kPrefillTileM)
+      steps.push_back(fsf::prefill_tile_steps(h[s].n_cached, i0, std::min(i0 + fsf::kPrefillTileM, h[s].n_new),
+                                              c->window));
+  }
+  return steps;
+}
+
+fsf::PrefillSplit choose_prefill_split(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs) {
+  const int cus = env_int("FSF_PREFILL_SPLIT_UNITS", compute_units());  // tests force splits with a small value
+  const bool allow = !(c->flags & FSF_FLAG_FUSED_LAUNCH) && !getenv("FSF_PREFILL_NO_SPLIT");
+  return plan_prefill_split(prefill_tile_steps_of(c, h, n_seqs), c->n_q_heads, cus, allow);
 }
 
 }  // namespace
@@ -177,6 +220,24 @@ extern "C" const char* fsf_strerror(int status) {
 }
 
 extern "C" int fsf_version(void) { return 100; }
+
+extern "C" int32_t fsf_plan_prefill_groups(const fsf_attn_cfg* cfg, const fsf_seq_desc* descs_host,
+                                           int32_t n_seqs, int32_t compute_units_assumed,
+                                           int32_t* groups_out, int32_t cap) {
+  if (!cfg_ok(cfg) || !descs_host || n_seqs < 0 || compute_units_assumed < 1 || (cap > 0 && !groups_out))
+    return -1;
+  const std::vector<int> steps = prefill_tile_steps_of(cfg, descs_host, n_seqs);
+  const fsf::PrefillSplit sp = plan_prefill_split(steps, cfg->n_q_heads, compute_units_assumed, true);
+  const int n = fsf::prefill_groups((int)steps.size(), sp);
+  for (int g = 0; g < n && g < cap; ++g) {
+    const fsf::PrefillWork w = fsf::prefill_group_to_work(g, (int)steps.size(), sp);
+    groups_out[4 * g] = w.tile;
+    groups_out[4 * g + 1] = w.part;
+    groups_out[4 * g + 2] = w.n_parts;
+    groups_out[4 * g + 3] = w.slab;
+  }
+  return n;
+}
 
 extern "C" int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new,
                              void* k_cache, void* v_cache, const fsf_seq_desc* descs_dev,
@@ -268,7 +329,7 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.n_pre_tiles = (int32_t)n_pre;
   f.n_split_seqs = n_split;
   f.pre_part = (float*)(ws + w.pre_part);
-  choose_prefill_split(cfg, descs_host, n_seqs, f);
+  f.split = choose_prefill_split(cfg, descs_host, n_seqs);
 
   hipError_t e = fsf::launch_plan(p, f, stream);
   if (cfg->flags & FSF_FLAG_FUSED_LAUNCH) {

@@ -55,9 +55,19 @@ __device__ __forceinline__ int32_t load_uniform_i32(const int32_t* ptr) {
 constexpr int kHeadDim = 128;
 constexpr int kPrefillTileM = 256;   // query rows per prefill workgroup (4 waves x 64 rows)
 constexpr int kMaxDecodeItemsExtra = 8192;  // items beyond one per sequence (bounds the workspace)
-// Prompt-chunk tiles that would leave most compute units idle (a partial last round of
-// workgroups, or fewer workgroups than units) have their key range cut into parts, one
-// workgroup each, which store unnormalised partial results that a merge kernel combines.
+// Prompt-chunk tiles may have their key range cut into parts, one workgroup each, which store
+// unnormalised partial results that a merge kernel combines.  Two cases (decided on the host
+// from counts and step numbers, passed by value):
+//   heavy tiles  a tile that alone would outlast the rest of the pass (a short remainder of a
+//                prompt over its long cached prefix, next to the first chunk of the next
+//                prompt; or any tile when there is less than one round of workgroups):
+//                up to kMaxHeavyTiles of them, each with its own number of parts; started first
+//   tail tiles   when the last round of workgroups is at most half full, the tiles of that
+//                round (the lowest tile indices that are not heavy), the same number of parts
+//                each; started last
+// Workgroups are numbered (tile, part)-major: all parts of the heavy tiles, then the whole
+// tiles by descending tile index (within a chunk: most keys first), then the tail tiles.
+constexpr int kMaxHeavyTiles = 4;
 constexpr int kMaxPrefillSplitUnits = 512;  // (tile, head, part) workgroups with partial results (bounds the workspace)
 constexpr int kPrefillPartRowFloats = 136;  // a partial row: O 128 floats, m, l, padding to a multiple of 16 bytes
 constexpr int kPrefillMinPartSteps = 8;     // no part is shorter than this many 64-key steps
@@ -93,6 +103,95 @@ __host__ __device__ inline void seq_work(int n_new, int n_cached, int window, in
   }
 }
 
+struct PrefillSplit {
+  int32_t n_heavy;
+  int32_t heavy_tile[kMaxHeavyTiles];   // tile indices, descending
+  int32_t heavy_parts[kMaxHeavyTiles];  // >= 2 each
+  int32_t tail_tiles;                   // how many of the lowest non-heavy tile indices are split
+  int32_t tail_parts;                   // into this many parts each (>= 2 if tail_tiles > 0)
+};
+
+struct PrefillWork {
+  int tile, part, n_parts;
+  int slab;  // (tile, part) number in the partial-result buffer, -1 for an unsplit tile
+};
+
+__host__ __device__ inline int prefill_heavy_groups(const PrefillSplit& sp) {
+  int n = 0;
+  for (int k = 0; k < sp.n_heavy; ++k) n += sp.heavy_parts[k];
+  return n;
+}
+
+// a-th lowest tile index that is not a heavy tile
+__host__ __device__ inline int prefill_nth_plain_tile(int a, const PrefillSplit& sp) {
+  int tile = a;
+  for (int k = sp.n_heavy - 1; k >= 0; --k)  // ascending
+    if (sp.heavy_tile[k] <= tile) ++tile;
+  return tile;
+}
+
+// number of (tile, part) groups; workgroups = groups x query heads
+__host__ __device__ inline int prefill_groups(int n_tiles, const PrefillSplit& sp) {
+  return prefill_heavy_groups(sp) + (n_tiles - sp.n_heavy - sp.tail_tiles) + sp.tail_tiles * sp.tail_parts;
+}
+
+__host__ __device__ inline PrefillWork prefill_group_to_work(int g, int n_tiles, const PrefillSplit& sp) {
+  PrefillWork w;
+  const int heavy = prefill_heavy_groups(sp);
+  if (g < heavy) {
+    int k = 0, start = 0;
+    while (g >= start + sp.heavy_parts[k]) start += sp.heavy_parts[k++];
+    w.tile = sp.heavy_tile[k];
+    w.part = g - start;
+    w.n_parts = sp.heavy_parts[k];
+    w.slab = g;
+    return w;
+  }
+  g -= heavy;
+  const int n_plain = n_tiles - sp.n_heavy;
+  const int n_whole = n_plain - sp.tail_tiles;
+  if (g < n_whole) {  // descending tile index among the plain tiles above the tail
+    w.tile = prefill_nth_plain_tile(n_plain - 1 - g, sp);
+    w.part = 0;
+    w.n_parts = 1;
+    w.slab = -1;
+    return w;
+  }
+  g -= n_whole;
+  const int a = sp.tail_tiles - 1 - g / sp.tail_parts;  // ascending ordinal of the tail tile
+  w.tile = prefill_nth_plain_tile(a, sp);
+  w.part = g % sp.tail_parts;
+  w.n_parts = sp.tail_parts;
+  w.slab = heavy + a * sp.tail_parts + w.part;
+  return w;
+}
+
+// j-th split tile (heavy tiles first, then tail tiles ascending): its index, parts and first slab
+__host__ __device__ inline PrefillWork prefill_split_tile(int j, const PrefillSplit& sp) {
+  PrefillWork w;
+  w.part = 0;
+  if (j < sp.n_heavy) {
+    w.tile = sp.heavy_tile[j];
+    w.n_parts = sp.heavy_parts[j];
+    w.slab = 0;
+    for (int k = 0; k < j; ++k) w.slab += sp.heavy_parts[k];
+  } else {
+    const int a = j - sp.n_heavy;
+    w.tile = prefill_nth_plain_tile(a, sp);
+    w.n_parts = sp.tail_parts;
+    w.slab = prefill_heavy_groups(sp) + a * sp.tail_parts;
+  }
+  return w;
+}
+
+// 64-key steps a prompt-chunk tile walks: rows [i0, i1) of a chunk with n_cached tokens before it
+__host__ __device__ inline int prefill_tile_steps(int n_cached, int i0, int i1, int window) {
+  int lo, hi, tmp;
+  visible_range(n_cached + i0, window, lo, tmp);
+  visible_range(n_cached + i1 - 1, window, tmp, hi);
+  return (hi - (lo & ~63)) / 64 + 1;
+}
+
 struct FastPlan {
   int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of decode items per sequence
   int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
@@ -102,12 +201,11 @@ struct FastPlan {
   int32_t* split_seqs;      // [n_split_seqs] sequences whose generation row was cut into > 1 item
   float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
   float* part_acc;          // [items, n_q_heads, 128] unnormalised outputs per split
-  float* pre_part;          // [pre_split_tiles * 256 rows, n_q_heads, pre_parts, 136] partial results of split tiles
+  float* pre_part;          // [slab, 256 rows, n_q_heads, 136] partial results of split tiles
   int32_t split_blocks;     // target cache blocks per decode item
   int32_t min_item_blocks;  // no split leaves an item with fewer blocks than this
   int32_t n_dec_items, n_pre_tiles, n_split_seqs;  // host-side totals (grid sizes)
-  int32_t pre_split_tiles;  // tiles 0 .. pre_split_tiles-1 (the last to be started) are cut into
-  int32_t pre_parts;        // this many parts each (1: nothing is split)
+  PrefillSplit split;       // which prompt-chunk tiles are cut along their keys
 };
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);

@@ -205,6 +205,20 @@ class Scheduler:
             pass
 
 
+def plan_prefill_groups(cfg, descs: np.ndarray, compute_units: int = 256) -> np.ndarray:
+    """fsf_plan_prefill_groups: ``int32 [G, 4]`` rows ``(tile, part, n_parts, slab)`` in start order (host only)."""
+    L = lib()
+    L.fsf_plan_prefill_groups.restype = C.c_int32
+    d = np.ascontiguousarray(descs, dtype=np.int32)
+    n = L.fsf_plan_prefill_groups(C.byref(cfg), C.c_void_p(d.ctypes.data), len(d), compute_units, None, 0)
+    if n < 0:
+        raise FsfError(FSF_ERR_INVALID_ARG, "fsf_plan_prefill_groups")
+    out = np.zeros((n, 4), dtype=np.int32)
+    L.fsf_plan_prefill_groups(C.byref(cfg), C.c_void_p(d.ctypes.data), len(d), compute_units,
+                              C.c_void_p(out.ctypes.data), n)
+    return out
+
+
 # ------------------------------------------------------------------ per-kernel timing aid
 PHASES = ("append", "plan", "prefill", "decode", "merge", "generic", "fused")
 
