@@ -46,8 +46,42 @@ EMA_ALPHA = 0.2
 PROMPT_TOKENS_PER_S = 512.0
 
 
+class PoolStats:
+    """Occupancy of the blocked KV cache over a run (paper Sec. 2.1: fixed-size blocks handed out on
+    demand): blocks in use, tokens they hold, and how often a pass was cut short by the pool."""
+
+    def __init__(self, block_size: int, num_blocks: int, token_budget: int):
+        self.B, self.num_blocks, self.budget = block_size, num_blocks, token_budget
+        self.cached = {}              # live sequence -> tokens in the cache
+        self.passes = self.short_passes = 0
+        self.sum_used = self.sum_tokens = self.peak_used = 0
+
+    def on_pass(self, sched, descs, waiting_prompt_tokens: int):
+        for n_new, n_cached, _, sid in descs:
+            self.cached[int(sid)] = int(n_cached) + int(n_new)
+        used = self.num_blocks - sched.free_blocks()
+        self.passes += 1
+        self.sum_used += used
+        self.peak_used = max(self.peak_used, used)
+        self.sum_tokens += sum(self.cached.values())
+        n_tokens = int(sum(d[0] for d in descs))
+        # tokens were waiting, the budget was not met: the pool had no block for them
+        if n_tokens < self.budget and waiting_prompt_tokens > 0:
+            self.short_passes += 1
+
+    def retire(self, sid: int):
+        self.cached.pop(sid, None)
+
+    def summary(self):
+        used = self.sum_used / max(self.passes, 1)
+        return {"pool_blocks": self.num_blocks, "mean_blocks_in_use": used, "peak_blocks_in_use": self.peak_used,
+                "mean_pool_utilisation": used / self.num_blocks,
+                "tokens_per_allocated_slot": self.sum_tokens / max(self.sum_used * self.B, 1),
+                "passes_cut_short_by_the_pool": self.short_passes / max(self.passes, 1)}
+
+
 def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, block_size, num_blocks,
-             max_blocks=None, on_pass=None):
+             max_blocks=None, on_pass=None, pool_stats: PoolStats = None):
     """Closed loop of ``n_clients`` clients over ``requests = [(prompt_len, gen_len)]``.
 
     ``step_time(descs)`` returns the seconds a pass with descriptors ``descs`` (rows
@@ -72,6 +106,11 @@ def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, blo
             raise RuntimeError("closed loop: no request in flight")
         if on_pass is not None:
             on_pass(descs, tables)
+        if pool_stats is not None:
+            in_pass = {int(d[3]): int(d[0]) + int(d[1]) for d in descs}
+            waiting = sum(requests[i][0] - in_pass.get(i, pool_stats.cached.get(i, 0))
+                          for i in range(nxt) if len(tokens[i]) == 0)
+            pool_stats.on_pass(sched, descs, waiting)
         t = t + step_time([tuple(int(x) for x in d) for d in descs])
         n_passes += 1
         finished = 0
@@ -79,7 +118,10 @@ def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, blo
             if em:
                 sid = int(d[3])
                 tokens[sid].append(t)
-                finished += len(tokens[sid]) == requests[sid][1]
+                if len(tokens[sid]) == requests[sid][1]:
+                    finished += 1
+                    if pool_stats is not None:
+                        pool_stats.retire(sid)
         sched.step_done()
         done += finished
         for _ in range(finished):
@@ -249,13 +291,46 @@ def run(policy: str, requests, n_clients: int, token_budget: int, measured: bool
     return out
 
 
+def pool_sweep(requests, n_clients: int, token_budget: int, fractions=(1.0, 0.8, 0.6, 0.4, 0.3), block_size: int = 64):
+    """Dynamic SplitFuse with a KV pool of a fraction of what the clients' largest requests would
+    need together: throughput, occupancy, and how often the pool cut a pass short (analytic times)."""
+    full = sum(-(-(p + g) // block_size) for p, g in sorted(requests, key=lambda r: -(r[0] + r[1]))[:n_clients])
+    largest = max(-(-(p + g) // block_size) for p, g in requests)
+    out = []
+    for frac in fractions:
+        num_blocks = max(int(full * frac), largest)
+        stats = PoolStats(block_size, num_blocks, token_budget)
+        try:
+            sent, tokens, total, n_passes = simulate("splitfuse", requests, n_clients, ForwardModel(), token_budget,
+                                                     max_seqs=n_clients + 1, block_size=block_size,
+                                                     num_blocks=num_blocks, max_blocks=largest, pool_stats=stats)
+            m = metrics(requests, sent, tokens, total)
+            row = {"pool_fraction": frac, "throughput_rps": m["throughput_rps"],
+                   "mean_request_latency_s": m["mean_request_latency_s"], "passes": n_passes}
+        except fsf.FsfError as e:
+            if e.status != fsf.FSF_ERR_NO_BLOCKS:
+                raise
+            # every block is held by sequences that all need one more: without eviction (the paper
+            # describes none) the composer can schedule nothing
+            row = {"pool_fraction": frac, "stuck_without_free_blocks_after_passes": stats.passes}
+        row.update(stats.summary())
+        out.append(row)
+    return out
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--clients", type=int, nargs="+", default=[4, 16])
     ap.add_argument("--requests", type=int, default=96)
     ap.add_argument("--budget", type=int, default=2048)
     ap.add_argument("--analytic", action="store_true", help="no GPU: attention time from the kernels' rates")
+    ap.add_argument("--pool-sweep", action="store_true", help="SplitFuse under a shrinking KV pool (no GPU)")
     a = ap.parse_args(argv)
+    if a.pool_sweep:
+        rows = pool_sweep(wl.chat_requests(a.requests), a.clients[-1], a.budget)
+        for r in rows:
+            print(json.dumps(r), flush=True)
+        return rows
     if not a.analytic:
         import torch
         assert torch.cuda.is_available(), "measured attention needs a GPU (or pass --analytic)"

@@ -87,6 +87,21 @@ def test_forward_model_regimes():
     assert one_decode > fm.linear_s(1) and one_decode < fm.linear_s(1) * 1.1
 
 
+def test_pool_sweep_occupancy_and_the_stuck_case():
+    """a roomy pool is never the limit; a tight one cuts passes short but every request still
+    finishes; block-granular allocation wastes at most one block per live sequence"""
+    reqs = wl.chat_requests(40, prompt_mean=900, gen_mean=20, seed=5)
+    rows = sim.pool_sweep(reqs, 8, 512, fractions=(1.0, 0.5))
+    assert rows[0]["passes_cut_short_by_the_pool"] == 0.0 and rows[0]["peak_blocks_in_use"] <= rows[0]["pool_blocks"]
+    assert rows[1]["passes_cut_short_by_the_pool"] > 0.0 and rows[1]["throughput_rps"] <= rows[0]["throughput_rps"]
+    for r in rows:
+        assert 0.9 < r["tokens_per_allocated_slot"] <= 1.0
+    # a pool that cannot hold what the partly processed prompts and the generations need together
+    # ends with nothing schedulable: reported, not raised
+    stuck = sim.pool_sweep([(1000, 300)] * 8, 4, 256, fractions=(0.3,))[0]
+    assert "stuck_without_free_blocks_after_passes" in stuck
+
+
 @pytest.mark.gpu
 def test_measured_attention_runs_a_small_closed_loop():
     reqs = wl.chat_requests(6, prompt_mean=700, gen_mean=6, seed=3)
