@@ -175,3 +175,29 @@ def test_benchmark_shapes_reduced(k, nd):
     if k == 2:
         spec.seqs = [(448, 0)] + spec.seqs[1:]
     check_step(Step(spec), f"cfg{k} reduced")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_ragged_batches(seed, prefill_split_env):
+    """Seeded random passes: chunks of any length over any prefix next to generation rows, random
+    head grouping, window, block size and unit count (which moves the split rules around)."""
+    rng = np.random.default_rng(7000 + seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    Hq = Hkv * int(rng.choice([1, 2, 4, 8]))
+    block = int(rng.choice([64, 64, 128]))
+    window = int(rng.choice([0, 0, 0, 90, 1000]))
+    dtype = "bf16" if seed % 3 else "f16"
+    seqs = []
+    for _ in range(int(rng.integers(1, 5))):          # prompt chunks
+        n = int(rng.choice([2, 17, 64, 200, 256, 257, 600, 1100]))
+        c = int(rng.choice([0, 0, 5, 63, 64, 700, 3000]))
+        seqs.append((n, c))
+    for _ in range(int(rng.integers(0, 6))):          # generation rows
+        seqs.append((1, int(rng.choice([0, 1, 63, 64, 500, 2000]))))
+    order = rng.permutation(len(seqs))
+    seqs = [seqs[i] for i in order]
+    # keep the oracle's dense score matrices small
+    assert sum((n + c) * n for n, c in seqs) < 30_000_000
+    prefill_split_env(int(rng.choice([4, 16, 64, 256])))
+    spec = wl.BatchSpec(f"rand{seed}", Hq, Hkv, 128, block, dtype, seqs, window=window, seed=8000 + seed)
+    check_step(Step(spec, poison="nan"), f"random batch {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} {seqs}")
