@@ -104,6 +104,25 @@ int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new,
                   int32_t n_seqs, int32_t max_blocks, int32_t n_tokens, void* hip_stream);
 
 /*
+ * As fsf_kv_append, with the rotary position embedding of the served model family (paper
+ * Sec. 4.1: Llama-2) applied to K on the way into the cache.  For the row at position p and
+ * every head, element i < d/2 pairs with element i + d/2:
+ *     k'[i]       = k[i] * cos(p, i) - k[i + d/2] * sin(p, i)
+ *     k'[i + d/2] = k[i + d/2] * cos(p, i) + k[i] * sin(p, i)
+ * cos_sin_dev: device, float32 [table_positions, d/2, 2] (cos, sin), supplied by the caller;
+ * every position of the pass must be below table_positions (checked on descs_host).  The
+ * arithmetic is fixed, so that the cache contents remain reproducible bit for bit: the four
+ * products and the sum and the difference are float32 operations rounded to nearest even,
+ * never fused, and the result is rounded once to the storage type.  V is copied bit for bit.
+ * head_dim must be even.  Errors as fsf_kv_append.
+ */
+int fsf_kv_append_rotary(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new, void* k_cache,
+                         void* v_cache, const fsf_seq_desc* descs_dev, const fsf_seq_desc* descs_host,
+                         const int32_t* block_tables_dev, int32_t n_seqs, int32_t max_blocks,
+                         int32_t n_tokens, const float* cos_sin_dev, int32_t table_positions,
+                         void* hip_stream);
+
+/*
  * Bytes of device workspace fsf_ragged_attention needs for a pass of at most n_seqs
  * sequences, n_tokens tokens and max_blocks table columns.  Never zero (a small plan
  * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.  On the

@@ -81,6 +81,67 @@ def kv_append(k_cache, v_cache, k_new, v_new, descs, block_tables, block_size: i
             v_cache[blk, :, slot, :] = v_new[q_off + i]
 
 
+def f32_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float32 values to the storage type, nearest with ties to even (bf16 as uint16 bits)."""
+    assert x.dtype == np.float32
+    if dtype == "f32":
+        return x.copy()
+    if dtype == "f16":
+        return x.astype(np.float16)           # numpy rounds to nearest even
+    if dtype == "bf16":
+        bits = x.view(np.uint32).astype(np.uint64)
+        keep, drop = bits >> np.uint64(16), bits & np.uint64(0xFFFF)
+        up = (drop > 0x8000) | ((drop == 0x8000) & ((keep & np.uint64(1)) == 1))
+        return (keep + up.astype(np.uint64)).astype(np.uint16)   # finite inputs; a carry moves to the exponent
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def rotary_table(n_positions: int, head_dim: int, theta: float = 10000.0) -> np.ndarray:
+    """``float32 [n_positions, head_dim // 2, 2]``: cos and sin of ``p * theta ** (-2 i / head_dim)``,
+    evaluated in float64 and rounded once (the rotary position embedding of the Llama family,
+    which the paper's evaluation serves, Sec. 4.1)."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    ang = np.arange(n_positions, dtype=np.float64)[:, None] * theta ** (-2.0 * i / head_dim)[None, :]
+    return np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)
+
+
+def rotate_row(k_row: np.ndarray, cos_sin_p: np.ndarray, dtype: str) -> np.ndarray:
+    """Rotate one stored K row ``[Hkv, d]`` by its position's angles (half-split pairing: element
+    ``i`` pairs with ``i + d/2``)::
+
+        k'[i]       = k[i] * cos_i - k[i + d/2] * sin_i
+        k'[i + d/2] = k[i + d/2] * cos_i + k[i] * sin_i
+
+    The arithmetic is fixed so that the cache stays bit-exact: every product and the sum or
+    difference of the two products is a float32 operation rounded to nearest even (no fused
+    multiply-add), and the result is rounded once more to the storage type."""
+    d = k_row.shape[-1]
+    k = to_f64(k_row, dtype).astype(np.float32)      # exact: storage values are float32 values
+    a, b = k[..., : d // 2], k[..., d // 2:]
+    c, s = cos_sin_p[:, 0][None, :], cos_sin_p[:, 1][None, :]
+    lo = (a * c).astype(np.float32) - (b * s).astype(np.float32)
+    hi = (b * c).astype(np.float32) + (a * s).astype(np.float32)
+    return f32_to_storage(np.concatenate([lo, hi], axis=-1).astype(np.float32), dtype)
+
+
+def kv_append_rotary(k_cache, v_cache, k_new, v_new, descs, block_tables, block_size: int,
+                     cos_sin: np.ndarray, dtype: str) -> None:
+    """As :func:`kv_append`, but every K row is rotated by the angles of its position before it
+    is stored (V is copied bit for bit)."""
+    descs = np.asarray(descs)
+    for s in range(descs.shape[0]):
+        n_new = int(descs[s, DESC_N_NEW])
+        n_cached = int(descs[s, DESC_N_CACHED])
+        q_off = int(descs[s, DESC_Q_OFFSET])
+        for i in range(n_new):
+            p = n_cached + i
+            blk = int(block_tables[s, p // block_size])
+            slot = p % block_size
+            assert blk >= 0, "position falls on an unassigned block-table entry"
+            k_cache[blk, :, slot, :] = rotate_row(k_new[q_off + i], cos_sin[p], dtype)
+            v_cache[blk, :, slot, :] = v_new[q_off + i]
+
+
 def gather_history(cache, block_table_row, n_tokens: int, block_size: int) -> np.ndarray:
     """Logical history ``[n_tokens, Hkv, d]`` of one sequence, in position order."""
     n_heads, d = cache.shape[1], cache.shape[3]

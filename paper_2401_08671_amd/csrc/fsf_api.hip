@@ -254,6 +254,26 @@ extern "C" int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const v
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }
 
+extern "C" int fsf_kv_append_rotary(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new,
+                                    void* k_cache, void* v_cache, const fsf_seq_desc* descs_dev,
+                                    const fsf_seq_desc* descs_host, const int32_t* block_tables_dev,
+                                    int32_t n_seqs, int32_t max_blocks, int32_t n_tokens,
+                                    const float* cos_sin_dev, int32_t table_positions, void* hip_stream) {
+  if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1 || table_positions < 0)
+    return FSF_ERR_INVALID_ARG;
+  if (n_seqs == 0 || n_tokens == 0) return FSF_OK;
+  if (!k_new || !v_new || !k_cache || !v_cache || !descs_dev || !descs_host || !block_tables_dev || !cos_sin_dev)
+    return FSF_ERR_INVALID_ARG;
+  if (cfg->head_dim % 2) return FSF_ERR_UNSUPPORTED;
+  if (!descs_ok(cfg, descs_host, n_seqs, max_blocks, n_tokens)) return FSF_ERR_INVALID_ARG;
+  for (int32_t s = 0; s < n_seqs; ++s)  // every position must have its row of angles
+    if ((int64_t)descs_host[s].n_cached + descs_host[s].n_new > table_positions) return FSF_ERR_INVALID_ARG;
+  const Pass p = make_pass(cfg, descs_dev, block_tables_dev, n_seqs, max_blocks, n_tokens);
+  const hipError_t e = fsf::launch_kv_append_rotary(p, k_new, v_new, k_cache, v_cache, cos_sin_dev,
+                                                    (hipStream_t)hip_stream);
+  return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+}
+
 extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_seqs,
                                                        int32_t n_tokens, int32_t max_blocks) {
   if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return 0;

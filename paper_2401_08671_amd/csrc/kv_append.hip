@@ -9,7 +9,15 @@
 // k_new; in the cache head h of that row is a contiguous d-element run at
 // [blk][h][slot][:].  Threads move 16-byte (or 4-byte) units, so each head run is written
 // with whole-wave coalesced stores.
+//
+// Rotary variant: the K row is rotated by the angles of its position on the way (the rotary
+// position embedding of the Llama family the paper's evaluation serves, Sec. 4.1; half-split
+// pairing: element i with i + d/2).  The arithmetic is fixed so that the cache stays
+// bit-exact against a reference: float32 products and their sum or difference, each rounded
+// to nearest even and never fused, then one rounding to the storage type.  cos and sin come
+// from a table the caller supplies, so no transcendental is evaluated here.
 #include "fsf_internal.h"
+#include "numeric.h"
 
 namespace fsf {
 namespace {
@@ -40,7 +48,60 @@ __global__ __launch_bounds__(256) void kv_append_kernel(Pass p, const Unit* __re
   }
 }
 
+// One workgroup per token; a thread rotates one (i, i + d/2) pair of one head at a time and
+// copies the matching V elements.  T is the storage type.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_append_rotary_kernel(Pass p, const T* __restrict__ k_new,
+                                                               const T* __restrict__ v_new,
+                                                               T* __restrict__ k_cache,
+                                                               T* __restrict__ v_cache,
+                                                               const float2* __restrict__ cos_sin) {
+// Products and sums below must stay separate roundings: the compiler's default would fuse
+// them into multiply-adds (the *_rn intrinsics are plain operators and fuse as well).
+#pragma clang fp contract(off)
+  const int t = blockIdx.x;
+  const int s = find_seq(p.descs, p.n_seqs, t);
+  const fsf_seq_desc d = p.descs[s];
+  const int pos = d.n_cached + (t - d.q_offset);
+  const int64_t blk = p.block_tables[(int64_t)s * p.max_blocks + pos / p.block_size];
+  const int slot = pos % p.block_size;
+  const int half = p.head_dim / 2;
+  const float2* cs = cos_sin + (int64_t)pos * half;
+  const int64_t src = (int64_t)t * p.n_kv_heads * p.head_dim;
+  const int64_t blk_base = blk * p.n_kv_heads * (int64_t)p.block_size * p.head_dim;
+  for (int u = threadIdx.x; u < p.n_kv_heads * half; u += blockDim.x) {
+    const int h = u / half;
+    const int i = u - h * half;
+    const int64_t in = src + (int64_t)h * p.head_dim + i;
+    const int64_t dst = blk_base + ((int64_t)h * p.block_size + slot) * p.head_dim + i;
+    const float a = to_float(k_new[in]), b = to_float(k_new[in + half]);
+    const float2 c = cs[i];
+    const float ac = a * c.x, bs = b * c.y, bc = b * c.x, as = a * c.y;
+    k_cache[dst] = from_float<T>(ac - bs);
+    k_cache[dst + half] = from_float<T>(bc + as);
+    v_cache[dst] = v_new[in];
+    v_cache[dst + half] = v_new[in + half];
+  }
+}
+
 }  // namespace
+
+hipError_t launch_kv_append_rotary(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
+                                   void* v_cache, const float* cos_sin, hipStream_t stream) {
+  if (p.n_tokens == 0 || p.n_seqs == 0) return hipSuccess;
+  PhaseTimer timer(FSF_PHASE_APPEND, stream);
+  const float2* cs = reinterpret_cast<const float2*>(cos_sin);
+  if (p.dtype == FSF_F32)
+    kv_append_rotary_kernel<float><<<p.n_tokens, 256, 0, stream>>>(p, (const float*)k_new, (const float*)v_new,
+                                                                  (float*)k_cache, (float*)v_cache, cs);
+  else if (p.dtype == FSF_BF16)
+    kv_append_rotary_kernel<bf16_t><<<p.n_tokens, 256, 0, stream>>>(p, (const bf16_t*)k_new, (const bf16_t*)v_new,
+                                                                   (bf16_t*)k_cache, (bf16_t*)v_cache, cs);
+  else
+    kv_append_rotary_kernel<f16_t><<<p.n_tokens, 256, 0, stream>>>(p, (const f16_t*)k_new, (const f16_t*)v_new,
+                                                                  (f16_t*)k_cache, (f16_t*)v_cache, cs);
+  return hipGetLastError();
+}
 
 hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
                             void* v_cache, hipStream_t stream) {

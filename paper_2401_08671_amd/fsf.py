@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
     L.fsf_version.restype = C.c_int
     L.fsf_kv_append.restype = C.c_int
     L.fsf_kv_append.argtypes = [cfgp, vp, vp, vp, vp, descp, i32p, i32, i32, i32, vp]
+    L.fsf_kv_append_rotary.restype = C.c_int
+    L.fsf_kv_append_rotary.argtypes = [cfgp, vp, vp, vp, vp, descp, descp, i32p, i32, i32, i32, vp, i32, vp]
     L.fsf_ragged_attention_workspace_bytes.restype = sz
     L.fsf_ragged_attention_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
     L.fsf_ragged_attention.restype = C.c_int
@@ -125,6 +127,18 @@ def kv_append(cfg: AttnCfg, k_new, v_new, k_cache, v_cache, batch: DeviceBatch) 
                              _ptr(batch.descs_dev), _ptr(batch.bt_dev), batch.n_seqs, batch.max_blocks,
                              batch.n_tokens, _stream())
     _check(st, "fsf_kv_append")
+
+
+def kv_append_rotary(cfg: AttnCfg, k_new, v_new, k_cache, v_cache, batch: DeviceBatch, cos_sin) -> None:
+    """fsf_kv_append_rotary on torch's current stream; ``cos_sin`` is a float32 device tensor
+    [table_positions, head_dim / 2, 2]."""
+    assert cos_sin.dtype == torch.float32 and cos_sin.is_contiguous() and cos_sin.dim() == 3
+    assert cos_sin.shape[1] * 2 == cfg.head_dim and cos_sin.shape[2] == 2
+    st = lib().fsf_kv_append_rotary(C.byref(cfg), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                    _ptr(batch.descs_dev), C.c_void_p(batch.descs_host.ctypes.data),
+                                    _ptr(batch.bt_dev), batch.n_seqs, batch.max_blocks, batch.n_tokens,
+                                    _ptr(cos_sin), cos_sin.shape[0], _stream())
+    _check(st, "fsf_kv_append_rotary")
 
 
 def ragged_attention_workspace_bytes(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int) -> int:

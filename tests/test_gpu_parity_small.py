@@ -132,3 +132,68 @@ def test_empty_pass_is_a_noop():
     fsf.kv_append(cfg, None, None, None, None, batch)
     fsf.ragged_attention(cfg, None, None, None, batch, None, None)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ append with the rotary rotation fused in
+def run_rotary(step, cos_sin, with_attention=False):
+    sp = step.spec
+    cfg = fsf.make_cfg(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.block_size, sp.dtype, step.num_blocks,
+                       window=sp.window, scale=sp.scale)
+    batch = fsf.DeviceBatch(step.descs, step.block_tables, "cuda")
+    k_new = wl.from_numpy_storage(step.k_new, sp.dtype, "cuda")
+    v_new = wl.from_numpy_storage(step.v_new, sp.dtype, "cuda")
+    kc = wl.from_numpy_storage(step.k_cache0, sp.dtype, "cuda")
+    vc = wl.from_numpy_storage(step.v_cache0, sp.dtype, "cuda")
+    table = torch.from_numpy(cos_sin).cuda()
+    fsf.kv_append_rotary(cfg, k_new, v_new, kc, vc, batch, table)
+    out64 = None
+    if with_attention:
+        q = wl.from_numpy_storage(step.q, sp.dtype, "cuda")
+        out = torch.full_like(q, float("nan"))
+        ws = fsf.alloc_workspace(cfg, batch.n_seqs, batch.n_tokens, batch.max_blocks, "cuda")
+        fsf.ragged_attention(cfg, q, kc, vc, batch, out, ws)
+        out64 = out.to(torch.float64).cpu().numpy()
+    torch.cuda.synchronize()
+    return wl.to_numpy_storage(kc), wl.to_numpy_storage(vc), out64
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape", [
+    # Hq, Hkv, d, B, seqs
+    (8, 2, 128, 64, [(300, 0), (70, 130), (1, 63), (1, 64), (1, 1000), (5, 59)]),
+    (4, 4, 64, 16, [(33, 7), (1, 0), (1, 95)]),
+    (6, 3, 80, 8, [(9, 0), (1, 13)]),
+])
+def test_rotary_append_is_bit_exact(dtype, shape):
+    Hq, Hkv, d, B, seqs = shape
+    spec = wl.BatchSpec("rot", Hq, Hkv, d, B, dtype, seqs, seed=91)
+    st = Step(spec, poison="nan")
+    n_pos = max(c + n for n, c in seqs)
+    table = oa.rotary_table(n_pos, d)                       # exactly as many rows as positions in use
+    kc_o, vc_o = st.k_cache0.copy(), st.v_cache0.copy()
+    oa.kv_append_rotary(kc_o, vc_o, st.k_new, st.v_new, st.descs, st.block_tables, B, table, dtype)
+    kc_h, vc_h, _ = run_rotary(st, table)
+    assert_cache_bit_exact(kc_h, kc_o, f"rotary K {dtype} {shape[:4]}")
+    assert_cache_bit_exact(vc_h, vc_o, f"rotary V {dtype} {shape[:4]}")
+
+
+def test_rotary_append_then_attention_matches_the_oracle():
+    spec = wl.BatchSpec("rot-attn", 8, 2, 128, 64, "bf16", [(257, 0), (1, 190), (40, 90)], seed=92)
+    st = Step(spec)
+    table = oa.rotary_table(512, 128)
+    kc_o, vc_o = st.k_cache0.copy(), st.v_cache0.copy()
+    oa.kv_append_rotary(kc_o, vc_o, st.k_new, st.v_new, st.descs, st.block_tables, 64, table, "bf16")
+    ref = oa.ragged_attention(st.q, kc_o, vc_o, st.descs, st.block_tables, block_size=64, scale=spec.scale,
+                              window=0, dtype="bf16")
+    kc_h, vc_h, out = run_rotary(st, table, with_attention=True)
+    assert_cache_bit_exact(kc_h, kc_o, "K")
+    assert_outputs_close(out, ref, "bf16", "attention over the rotated cache")
+
+
+def test_rotary_append_rejects_a_table_that_is_too_short():
+    spec = wl.BatchSpec("rot-bad", 2, 2, 64, 16, "f32", [(4, 0), (1, 9)], seed=1)
+    st = Step(spec)
+    table = oa.rotary_table(9, 64)      # position 9 has no row
+    with pytest.raises(fsf.FsfError) as ei:
+        run_rotary(st, table)
+    assert ei.value.status == fsf.FSF_ERR_INVALID_ARG

@@ -314,3 +314,57 @@ def test_config1_oracle_runs_and_is_finite_under_poison():
     st = Step(wl.config(1), num_blocks=128, poison="nan")
     _, _, out = st.oracle()
     assert out.shape == (194, 4, 64) and np.isfinite(out).all()
+
+
+# ---------------------------------------------------------------------------------------
+# rotary append
+def test_f32_to_bf16_rounding_matches_torch_and_ties_go_to_even():
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(200000) * np.exp(rng.uniform(-8, 8, 200000))).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oa.f32_to_storage(x, "bf16"), want)
+    # exact ties: 1 + 2^-8 (between 1 and 1 + 2^-7) -> even mantissa 1.0; 1 + 3 * 2^-8 -> 1 + 2^-6
+    ties = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8], dtype=np.float32)
+    assert oa.f32_to_storage(ties, "bf16").tolist() == [0x3F80, 0x3F82]
+
+
+def test_rotary_table_and_rotation_closed_forms():
+    tab = oa.rotary_table(64, 8, theta=10000.0)
+    assert tab.shape == (64, 4, 2) and np.all(tab[0, :, 0] == 1.0) and np.all(tab[0, :, 1] == 0.0)
+    assert tab[5, 0, 0] == np.float32(np.cos(5.0)) and tab[5, 1, 1] == np.float32(np.sin(5.0 * 10000.0 ** (-2 / 8)))
+    k = np.random.default_rng(1).standard_normal((3, 8)).astype(np.float32)
+    # position 0 is the identity, bit for bit
+    assert np.array_equal(oa.rotate_row(k, tab[0], "f32"), k)
+    # a rotation: every pair (i, i + d/2) keeps its length, and the result matches the
+    # complex-number form computed in float64
+    r = oa.rotate_row(k, tab[7], "f32").astype(np.float64)
+    z = (k[:, :4] + 1j * k[:, 4:]) * (tab[7, :, 0] + 1j * tab[7, :, 1]).astype(np.complex128)[None, :]
+    assert np.allclose(r[:, :4], z.real, atol=1e-6) and np.allclose(r[:, 4:], z.imag, atol=1e-6)
+    assert np.allclose(r[:, :4] ** 2 + r[:, 4:] ** 2, k[:, :4].astype(np.float64) ** 2 + k[:, 4:] ** 2, rtol=1e-6)
+    # dot products depend on the position difference only (what the embedding is for)
+    q = np.random.default_rng(2).standard_normal((1, 8)).astype(np.float32)
+    d1 = (oa.rotate_row(q, tab[20], "f32").astype(np.float64) * oa.rotate_row(k[:1], tab[13], "f32")).sum()
+    d2 = (oa.rotate_row(q, tab[37], "f32").astype(np.float64) * oa.rotate_row(k[:1], tab[30], "f32")).sum()
+    assert abs(d1 - d2) < 1e-5
+
+
+def test_rotary_append_touches_k_only_and_only_addressed_slots():
+    rng = np.random.default_rng(4)
+    B, H, d = 4, 2, 8
+    k_cache = np.full((6, H, B, d), 7, dtype=np.float32)
+    v_cache = np.full((6, H, B, d), 9, dtype=np.float32)
+    k_new = rng.standard_normal((5, H, d)).astype(np.float32)
+    v_new = rng.standard_normal((5, H, d)).astype(np.float32)
+    descs = np.array([[3, 2, 0, 0], [2, 0, 3, 1]], dtype=np.int32)
+    tables = np.array([[4, 1], [0, -1]], dtype=np.int32)
+    tab = oa.rotary_table(16, d)
+    oa.kv_append_rotary(k_cache, v_cache, k_new, v_new, descs, tables, B, tab, "f32")
+    # sequence 0: positions 2, 3 -> block 4 slots 2, 3; position 4 -> block 1 slot 0
+    assert np.array_equal(v_cache[4, :, 2], v_new[0]) and np.array_equal(v_cache[1, :, 0], v_new[2])
+    assert np.array_equal(k_cache[4, :, 3], oa.rotate_row(k_new[1], tab[3], "f32"))
+    assert np.array_equal(k_cache[0, :, 0], k_new[3])                 # position 0: identity
+    touched = {(4, 2), (4, 3), (1, 0), (0, 0), (0, 1)}
+    for blk in range(6):
+        for slot in range(B):
+            if (blk, slot) not in touched:
+                assert np.all(k_cache[blk, :, slot] == 7) and np.all(v_cache[blk, :, slot] == 9)
