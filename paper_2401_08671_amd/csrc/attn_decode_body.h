@@ -35,10 +35,30 @@ struct StepBuf {
   frag8 v[8];     // [e]: V[key = (e/4)*16 + 4kg + e%4][d = n*8 ..+8]
 };
 
-template <typename T>
+// kBlock16: cache blocks of 16 tokens, so the two 16-key tiles of a step lie in two blocks (the
+// second is clamped to blk_last, the unit's last block; its keys are then masked).  Otherwise a
+// step lies inside one block (block size a multiple of 32, steps start at multiples of 32).
+template <typename T, bool kBlock16>
 __device__ __forceinline__ void load_step(StepBuf& b, const T* __restrict__ kc,
                                           const T* __restrict__ vc, const int32_t* bt, int key0,
-                                          int B, int n_kv_heads, int hk, int n, int kg) {
+                                          int B, int n_kv_heads, int hk, int n, int kg, int blk_last) {
+  if constexpr (kBlock16) {
+    const int blk_a = key0 >> 4;  // uniform; key0 is a multiple of 16
+    const int blk_b = min(blk_a + 1, blk_last);
+    const int64_t phys_a = load_uniform_i32(bt + blk_a), phys_b = load_uniform_i32(bt + blk_b);
+    const int64_t base_a = (phys_a * n_kv_heads + hk) * (16 * kHeadDim);
+    const int64_t base_b = (phys_b * n_kv_heads + hk) * (16 * kHeadDim);
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      const T* kb = kc + (tile ? base_b : base_a);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) b.k[tile][t] = load_frag8_stream(kb + n * kHeadDim + (4 * t + kg) * 8);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      b.v[e] = load_frag8_stream(vc + ((e >> 2) ? base_b : base_a) + (4 * kg + (e & 3)) * kHeadDim + n * 8);
+    return;
+  }
   const int blk = key0 / B;                      // uniform
   const int64_t phys = load_uniform_i32(bt + blk);
   const int slot0 = key0 - blk * B;
@@ -118,7 +138,7 @@ __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f
 }
 
 // One wavefront: unit = item * n_kv_heads + kv head (item = a sequence's run of cache blocks).
-template <int DT, typename T, bool kDouble = true>
+template <int DT, typename T, bool kBlock16, bool kDouble = true>
 __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
                                             const T* __restrict__ kc, const T* __restrict__ vc,
                                             T* __restrict__ out, int unit, int lane) {
@@ -140,6 +160,9 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   const int blk1 = b_lo + (int)((int64_t)(split + 1) * nblk / n_splits) - 1;
   const int key_begin = max(blk0 * B, lo & ~31);
   const int key_end = min((blk1 + 1) * B - 1, hi);  // inclusive
+  // keys this unit counts: a step may reach past them (into the next unit's blocks when the
+  // block size is 16, past the window or the last token otherwise); those scores are masked
+  const int vis_lo = max(lo, key_begin), vis_hi = key_end;
   const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
 
   const int g = p.group;
@@ -163,22 +186,22 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   StepBuf b0, b1;
   const int n_steps = (key_end - key_begin) / 32 + 1;
   int i = 0;
-  load_step(b0, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, n, kg);
+  load_step<T, kBlock16>(b0, kc, vc, bt, key_begin, B, p.n_kv_heads, hk, n, kg, blk1);
   for (; i + 2 < n_steps; i += 2) {
     const int key0 = key_begin + 32 * i;
-    load_step(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
-    compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
-    load_step(b0, kc, vc, bt, key0 + 64, B, p.n_kv_heads, hk, n, kg);
-    compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, lo, hi, kg);
+    load_step<T, kBlock16>(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg, blk1);
+    compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
+    load_step<T, kBlock16>(b0, kc, vc, bt, key0 + 64, B, p.n_kv_heads, hk, n, kg, blk1);
+    compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, vis_lo, vis_hi, kg);
   }
   {
     const int key0 = key_begin + 32 * i;
     if (n_steps - i == 2) {
-      load_step(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg);
-      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
-      compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, lo, hi, kg);
+      load_step<T, kBlock16>(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg, blk1);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
+      compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, vis_lo, vis_hi, kg);
     } else {
-      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
     }
   }
 
@@ -186,8 +209,8 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
     // one register buffer: latency is hidden by the other waves of the compute unit
     StepBuf b0;
     for (int key0 = key_begin; key0 <= key_end; key0 += 32) {
-      load_step(b0, kc, vc, bt, key0, B, p.n_kv_heads, hk, n, kg);
-      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo, hi, kg);
+      load_step<T, kBlock16>(b0, kc, vc, bt, key0, B, p.n_kv_heads, hk, n, kg, blk1);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
     }
   }
   l += __shfl_xor(l, 16);

@@ -58,13 +58,13 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastP
 
 // One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
 // which measured best on the short-sequence batches.
-template <int DT, typename T>
+template <int DT, typename T, bool kBlock16>
 __global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
                                                                 const T* __restrict__ q,
                                                                 const T* __restrict__ kc,
                                                                 const T* __restrict__ vc,
                                                                 T* __restrict__ out) {
-  decode_unit<DT, T>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x);
+  decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x);
 }
 
 template <int DT, typename T>
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;
-    decode_unit<DT, T>(p, f, q, kc, vc, out, unit, threadIdx.x & 63);
+    decode_unit<DT, T, false>(p, f, q, kc, vc, out, unit, threadIdx.x & 63);  // the host launches this kernel for blocks of 32 tokens or more only
   }
 }
 
@@ -125,12 +125,16 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
   if (f.n_dec_items == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_DECODE, stream);
   const unsigned grid = (unsigned)f.n_dec_items * p.n_kv_heads;
-  if (p.dtype == FSF_BF16)
-    attn_decode_kernel<FSF_BF16, bf16_t><<<grid, 64, 0, stream>>>(
-        p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out);
-  else
-    attn_decode_kernel<FSF_F16, f16_t><<<grid, 64, 0, stream>>>(
-        p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
+#define FSF_DECODE(DT, T, B16)                 \
+  attn_decode_kernel<DT, T, B16><<<grid, 64, 0, stream>>>(p, f, (const T*)q, (const T*)k_cache, \
+                                                          (const T*)v_cache, (T*)out)
+  const bool b16 = p.block_size == 16;
+  if (p.dtype == FSF_BF16) {
+    if (b16) FSF_DECODE(FSF_BF16, bf16_t, true); else FSF_DECODE(FSF_BF16, bf16_t, false);
+  } else {
+    if (b16) FSF_DECODE(FSF_F16, f16_t, true); else FSF_DECODE(FSF_F16, f16_t, false);
+  }
+#undef FSF_DECODE
   return hipGetLastError();
 }
 

@@ -13,8 +13,9 @@
 // and the overlap of matrix and vector work is arranged inside the wave's own instruction
 // stream instead of being left to the chance interleaving of two waves.
 //
-// Keys are taken 64 at a time ("step"; never straddling a cache block since block_size % 64
-// == 0), gathered through the block table:
+// Keys are taken 64 at a time ("step"), gathered through the block table.  Every wave copies 16
+// of a step's key rows, and those never straddle a cache block (block_size is 16 * 2^k): with
+// blocks of 16 or 32 tokens the four waves simply read their rows from different blocks.
 //   HBM/L2 -> LDS directly (global_load_lds, 16 bytes per lane, no registers, no VALU).
 //     Both tiles stay row-major [64 keys][128 d]; the lane -> global chunk mapping applies an
 //     XOR swizzle so the later reads are bank-conflict free (64 banks):
@@ -70,13 +71,14 @@ typedef __attribute__((address_space(3))) char lds_char;
 // bytes per lane, HBM/L2 -> LDS without passing registers).  Each of the 4 waves copies 16 key
 // rows with 4 instructions (4 rows x 256 B each).  The lane -> source-chunk mapping (which
 // applies the swizzle) does not change from step to step, so a lane keeps its byte offset
-// inside a (block, head) tile in a register and a copy costs a handful of scalar instructions
-// for the tile's base address.  Returns row*256 + swizzled chunk*16 of the lane's 16 bytes in
-// copy instruction i of its wave.
+// relative to the wave's first row in a register and a copy costs a handful of scalar
+// instructions for the address of that row (block, head, position inside the block).  Returns
+// row*256 + swizzled chunk*16 of the lane's 16 bytes in copy instruction i of its wave, row
+// counted from the wave's first; both swizzles depend on the row modulo 16 only.
 template <bool kIsV>
-__device__ __forceinline__ uint32_t copy_lane_offset(int wave, int lane, int i) {
+__device__ __forceinline__ uint32_t copy_lane_offset(int lane, int i) {
   const int pc = lane & 15;  // physical 16-byte chunk this lane fills
-  const int row = wave * (64 / kPrefillWaves) + i * 4 + (lane >> 4);
+  const int row = i * 4 + (lane >> 4);
   const int swz = kIsV ? ((row & 3) << 2) : (row & 15);
   return row * 256 + ((pc ^ swz) << 4);
 }
@@ -128,9 +130,10 @@ __device__ __forceinline__ uint32_t copy_lane_offset(int wave, int lane, int i) 
 //   s51 1 if the result is stored as a partial one   s[52:53] address of a V tile   s[88:89] s[54:55] lanes whose reference was raised, rb 0, 1
 //   s[56:57] s[58:59] lanes whose row exists   s60 n_steps   s61 s62 first, last active step
 //   of the wave   s63 s64 first, last step that needs no mask   s65 s66 fast_lo, fast_hi   s67
-//   last step with all 64 rows written   s68 last written key - first key of the tile   s69
-//   first key of the tile   s70 window   s71 first step's index in the sequence (key/64)   s72
-//   steps per cache block - 1   s73 log2 of steps per block   s[74:75] block table of the
+//   last step with all 64 rows written   s68 last written key of the sequence   s69
+//   first key of the tile   s70 window   s71 the wave's 16-key quarter of step 0, counted from
+//   the start of the sequence (first key/16 + wave)   s72 quarters per cache block - 1   s73
+//   log2 of quarters per block   s[74:75] block table of the
 //   sequence   s[76:77] K base of this head   s[78:79] V base   s80 bytes per cache block   s81
 //   LDS address of the wave's first copy row   s82..s87, s92, s93, s95, s96 temporaries
 //   s[90:91] s[98:99] byte offset of the tiles of steps b, b+1   s94 physical block of step
@@ -263,27 +266,33 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
       va[mt] = lds0 + kVRingBase + x * 256 + ((2 * (mt ^ (x & 3)) + (g & 1)) << 5) + ((sl & 3) << 3);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      koff[i] = copy_lane_offset<false>(wave, lane, i);
-      voff[i] = copy_lane_offset<true>(wave, lane, i);
+      koff[i] = copy_lane_offset<false>(lane, i);
+      voff[i] = copy_lane_offset<true>(lane, i);
     }
   }
 
-  // ---- copies.  Step j of the tile covers keys key_begin + 64 j .. + 63, which lie in cache block
-  // (step0 + j) / spb of the sequence (spb = 64-key steps per block, a power of two).
+  // ---- copies.  Step j of the tile covers keys key_begin + 64 j .. + 63; this wave copies the
+  // 16 rows of "quarter" q0 + 4 j (quarters = runs of 16 keys, counted from the start of the
+  // sequence), which lie in cache block quarter / qpb (qpb = quarters per block, a power of two).
+  // A quarter past the last written token is replaced by the one that holds that token: the
+  // sequence owns that block, and the rows copied from there are stand-ins for masked keys.
   const uint32_t lds_k0 = (uint32_t)(uintptr_t)lds;
   constexpr uint32_t kRowBytes = kHeadDim * sizeof(T);
   const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
-  const uint32_t step0 = (uint32_t)key_begin / kKeysPerStep;
-  const uint32_t spb = (uint32_t)B / kKeysPerStep;
-  const uint32_t spb_shift = __builtin_ctz(spb);
+  constexpr uint32_t kQuarterKeys = kKeysPerStep / kPrefillWaves;  // 16
+  const uint32_t q0 = (uint32_t)key_begin / kQuarterKeys + wave;
+  const uint32_t q_last = (uint32_t)kv_last / kQuarterKeys;
+  const uint32_t qpb = (uint32_t)B / kQuarterKeys;
+  const uint32_t qpb_shift = __builtin_ctz(qpb);
   const uint64_t blk_bytes = (uint64_t)p.n_kv_heads * B * kRowBytes;  // one cache block, all heads (< 4 GiB)
   const char* const k_head = reinterpret_cast<const char*>(kc) + (uint64_t)hk * B * kRowBytes;
   const char* const v_head = reinterpret_cast<const char*>(vc) + (uint64_t)hk * B * kRowBytes;
   // the sequence starts from the byte offsets (block and position inside it, head excluded) of
   // the tiles of steps 0 and 1 and the physical block of step 2
-  auto block_of = [&](uint32_t j) { return (uint32_t)load_uniform_i32(bt + ((step0 + j) >> spb_shift)); };
+  auto quarter_of = [&](uint32_t j) { return min(q0 + kPrefillWaves * j, q_last); };
+  auto block_of = [&](uint32_t j) { return (uint32_t)load_uniform_i32(bt + (quarter_of(j) >> qpb_shift)); };
   auto offset_of = [&](uint32_t j) {
-    return (uint64_t)block_of(j) * blk_bytes + ((step0 + j) & (spb - 1)) * (kKeysPerStep * kRowBytes);
+    return (uint64_t)block_of(j) * blk_bytes + (quarter_of(j) & (qpb - 1)) * (kQuarterKeys * kRowBytes);
   };
   uint64_t off0_s = uni64(offset_of(0));
   uint64_t off1_s = uni64(n_steps > 1 ? offset_of(1) : 0);
@@ -292,8 +301,8 @@ __device__ __forceinline__ void prefill_tile(const Pass& p, const FastPlan& f,
 
   const u32x4 s60 = {uni(n_steps), uni(j_first), uni(j_last), uni(nomask_lo)};
   const u32x4 s64 = {uni(nomask_hi), uni(fast_lo), uni(fast_hi), uni(whole_hi)};
-  const u32x4 s68 = {uni(kv_last - key_begin), uni(key_begin), uni(p.window), uni(step0)};
-  const u32x2 s72 = {uni(spb - 1), uni(spb_shift)};
+  const u32x4 s68 = {uni(kv_last), uni(key_begin), uni(p.window), uni(q0)};
+  const u32x2 s72 = {uni(qpb - 1), uni(qpb_shift)};
   const u32x2 s80 = {uni((uint32_t)blk_bytes), uni(lds_k0 + wave * (64 / kPrefillWaves) * 256)};
   const uint64_t bt_s = uni64(reinterpret_cast<uint64_t>(bt));
   const uint64_t k_head_s = uni64(reinterpret_cast<uint64_t>(k_head));

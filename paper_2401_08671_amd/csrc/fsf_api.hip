@@ -57,15 +57,14 @@ bool descs_ok(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs, int3
   return off == n_tokens;
 }
 
-// The matrix-core path takes 2-byte dtypes, head_dim 128, blocks of 64 * 2^k tokens (a 64-key
-// step never straddles a block and finds its block with a shift), up to 16 query heads per
-// KV head, and a cache block (all heads) below 4 GiB (its byte offsets are formed in 32-bit
-// scalar multiplies).
+// The matrix-core path takes 2-byte dtypes, head_dim 128, blocks of 16 * 2^k tokens (the 16
+// keys a wave copies or loads at a time never straddle a block and find their block with a
+// shift), up to 16 query heads per KV head, and a cache block (all heads) below 4 GiB (its
+// byte offsets are formed in 32-bit scalar multiplies).
 bool fast_path_ok(const fsf_attn_cfg* c) {
-  const int32_t steps_per_block = c->block_size / 64;
   return !(c->flags & FSF_FLAG_FORCE_GENERIC) && (c->dtype == FSF_BF16 || c->dtype == FSF_F16) &&
-         c->head_dim == fsf::kHeadDim && c->block_size % 64 == 0 &&
-         (steps_per_block & (steps_per_block - 1)) == 0 &&
+         c->head_dim == fsf::kHeadDim && c->block_size >= 16 &&
+         (c->block_size & (c->block_size - 1)) == 0 &&
          (uint64_t)c->n_kv_heads * c->block_size * fsf::kHeadDim * 2 < (1ull << 32) &&
          c->n_q_heads / c->n_kv_heads <= 16 && c->scale > 0.f;
 }
@@ -314,7 +313,8 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
     dec_blocks += hi / cfg->block_size - lo / cfg->block_size + 1;
   }
   const int target_waves = env_int("FSF_DECODE_TARGET_WAVES", 16384);
-  const int min_item_blocks = env_int("FSF_DECODE_MIN_ITEM_BLOCKS", 16);
+  // no item shorter than 16 blocks, or 1024 keys where blocks are smaller than 64 tokens
+  const int min_item_blocks = env_int("FSF_DECODE_MIN_ITEM_BLOCKS", cfg->block_size < 64 ? 1024 / cfg->block_size : 16);
   int64_t target_items = target_waves / cfg->n_kv_heads;
   if (target_items < 1) target_items = 1;
   if (target_items > fsf::kMaxDecodeItemsExtra) target_items = fsf::kMaxDecodeItemsExtra;
@@ -352,7 +352,7 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.split = choose_prefill_split(cfg, descs_host, n_seqs);
 
   hipError_t e = fsf::launch_plan(p, f, stream);
-  if (cfg->flags & FSF_FLAG_FUSED_LAUNCH) {
+  if ((cfg->flags & FSF_FLAG_FUSED_LAUNCH) && cfg->block_size >= 32) {
     if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
   } else {
     if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);

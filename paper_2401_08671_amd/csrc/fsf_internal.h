@@ -45,7 +45,7 @@ __device__ __forceinline__ int32_t load_uniform_i32(const int32_t* ptr) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Matrix-core path (bf16/f16, head_dim 128, block_size % 64 == 0, group <= 16).
+// Matrix-core path (bf16/f16, head_dim 128, block_size 16 * 2^k, group <= 16).
 //
 // Work is cut on the device by a one-workgroup planning kernel; the host evaluates the
 // same formulas on its copy of the descriptors to size the grids.

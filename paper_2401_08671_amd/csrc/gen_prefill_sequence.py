@@ -284,22 +284,28 @@ def copy_tile(offs, lds_imm, base, step_reg):
     clamp, done = label('clamp'), label('copied')
     L = [f's_cmp_gt_i32 {step_reg}, {S_WHOLE_HI}', f's_cbranch_scc1 {clamp}']
     L += copy4(offs, lds_imm, base) + [f's_branch {done}', f'{clamp}:']
-    L += [f's_lshl_b32 s83, {step_reg}, 6', f's_sub_i32 s83, {S_LAST_ROW}, s83']
+    # s83 = last written row counted from the wave's first row of the (clamped) quarter, >= 0
+    L += [f's_lshl2_add_u32 s83, {step_reg}, {S_STEP0}', f's_lshr_b32 s82, {S_LAST_ROW}, 4', 's_min_u32 s83, s83, s82',
+          's_lshl_b32 s83, s83, 4', f's_sub_u32 s83, {S_LAST_ROW}, s83']
     return L + copy4_clamped(offs, lds_imm, base) + [f'{done}:']
 
 
 def offset_of_step_b_plus_2():
-    """s82 = step b's index in the sequence, S_PHYS = physical block of step b+2 -> s[84:85] =
-    byte offset of its tiles (block * bytes per block + position inside the block; head excluded)"""
-    return ['s_add_u32 s83, s82, 2', f's_and_b32 s83, s83, {S_SPB_MASK}', 's_lshl_b32 s83, s83, 14',
+    """s82 = the wave's quarter (16 keys, counted from the start of the sequence) of step b,
+    S_PHYS = physical block of its quarter of step b+2 -> s[84:85] = byte offset of the wave's rows
+    of that step (block * bytes per block + position inside the block; head excluded).  A quarter
+    past the last written token is replaced by the one that holds it."""
+    return ['s_add_u32 s83, s82, 8', f's_lshr_b32 s92, {S_LAST_ROW}, 4', 's_min_u32 s83, s83, s92',
+            f's_and_b32 s83, s83, {S_SPB_MASK}', 's_lshl_b32 s83, s83, 12',
             f's_mul_hi_u32 s85, {S_PHYS}, {S_BLK_BYTES}', f's_mul_i32 s84, {S_PHYS}, {S_BLK_BYTES}',
             's_add_u32 s84, s84, s83', 's_addc_u32 s85, s85, 0']
 
 
 def prefetch_block_id():
-    """physical block of step min(b+3, n_steps-1), read through the scalar cache"""
+    """physical block of the wave's quarter of step min(b+3, n_steps-1), read through the scalar cache"""
     return [f's_add_u32 s83, {S_B}, 3', f's_sub_u32 s96, {S_NSTEPS}, 1', 's_min_u32 s83, s83, s96',
-            f's_add_u32 s83, s83, {S_STEP0}', f's_lshr_b32 s83, s83, {S_SPB_SHIFT}', 's_lshl_b32 s83, s83, 2',
+            f's_lshl2_add_u32 s83, s83, {S_STEP0}', f's_lshr_b32 s92, {S_LAST_ROW}, 4', 's_min_u32 s83, s83, s92',
+            f's_lshr_b32 s83, s83, {S_SPB_SHIFT}', 's_lshl_b32 s83, s83, 2',
             f's_add_u32 s92, s{S_BT}, s83', f's_addc_u32 s93, s{S_BT + 1}, 0',
             f's_load_dword {S_PHYS}, s[92:93], 0x0']
 
@@ -318,7 +324,7 @@ def rotate_offsets():
 
 def hand_over_begin():
     # own copies landed and own LDS reads done, then everybody's
-    return ['s_waitcnt vmcnt(0) lgkmcnt(0)', 's_barrier', f's_add_u32 s82, {S_STEP0}, {S_B}']
+    return ['s_waitcnt vmcnt(0) lgkmcnt(0)', 's_barrier', f's_lshl2_add_u32 s82, {S_B}, {S_STEP0}']
 
 
 def hand_over_steady():

@@ -16,10 +16,11 @@ length matters in addition to the token count:
                HBM rate of 512 generation rows over 2048 cached tokens and the matrix rate of
                one 4096-row chunk over 4096 cached tokens, physical blocks randomly permuted
 
-    python -m paper_2401_08671_amd.sweeps            # prints one JSON object
+    python -m paper_2401_08671_amd.sweeps [--only composition|budget|block_size]   # prints one JSON object
 """
 from __future__ import annotations
 
+import argparse
 import json
 import sys
 
@@ -50,17 +51,20 @@ def spec_of(seqs, name, block=64):
 
 
 def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--only", choices=["composition", "budget", "block_size"], default=None)
+    only = ap.parse_args().only
     assert torch.cuda.is_available(), "sweeps need a GPU"
     out = {"shape": "Hq=40 Hkv=40 d=128 block=64 bf16, one layer", "composition": [], "budget": [], "block_size": []}
     T, ctx = 2048, 1024
     n_seq = 1
-    while n_seq <= T:
+    while n_seq <= T and only in (None, "composition"):
         rows = T // n_seq
         ms = time_spec(spec_of([(rows, ctx)] * n_seq, f"comp-{n_seq}x{rows}"))
         out["composition"].append({"n_seqs": n_seq, "rows_per_seq": rows, "n_cached": ctx, "ms": ms,
                                    "tokens_per_s": T / (ms * 1e-3)})
         n_seq *= 4
-    for budget in (64, 128, 256, 512, 1024, 2048, 4096, 8192):
+    for budget in (64, 128, 256, 512, 1024, 2048, 4096, 8192) if only in (None, "budget") else ():
         row = {"forward_tokens": budget}
         for kind, seqs in (("one_chunk_ctx0", [(budget, 0)]),
                            ("decodes_ctx1024", [(1, 1024)] * budget),
@@ -68,7 +72,7 @@ def main():
             ms = time_spec(spec_of(seqs, f"budget-{kind}-{budget}"))
             row[kind] = {"ms": ms, "tokens_per_s": budget / (ms * 1e-3)}
         out["budget"].append(row)
-    for block in (64, 128, 256):
+    for block in (16, 32, 64, 128, 256) if only in (None, "block_size") else ():
         dec = spec_of([(1, 2048)] * 512, f"block-{block}-decodes", block)
         pre = spec_of([(4096, 4096)], f"block-{block}-chunk", block)
         ms_d, ms_p = time_spec(dec), time_spec(pre)

@@ -1,4 +1,4 @@
-"""Matrix-core path (bf16/f16, head_dim 128, block 64/128) vs the fp64 oracle.
+"""Matrix-core path (bf16/f16, head_dim 128, blocks of 16 * 2^k tokens) vs the fp64 oracle.
 
 Element-by-element on shapes that span several tiles and ragged tails: generation rows
 with and without KV splitting, prompt chunks with partial tiles and cached prefixes, GQA
@@ -89,8 +89,37 @@ def test_prefill_larger_blocks(block):
     check_step(Step(spec, poison="nan"), f"prefill block={block}")
 
 
+@pytest.mark.parametrize("block", [16, 32])
+@pytest.mark.parametrize("split", [(1 << 20, 1), (256, 4)])
+@pytest.mark.parametrize("window", [0, 100, 1000])
+def test_decode_rows_small_blocks(split_env, block, split, window):
+    """Blocks of 16 and 32 tokens: a 32-key step spans two blocks (16) or is one block (32); unit
+    boundaries then fall on multiples of 16 keys, inside a step."""
+    split_env(*split)
+    spec = wl.BatchSpec("decsmall", 8, 2, 128, block, "bf16", [(1, c) for c in DECODE_LENS + [15, 16, 17, 47, 48]],
+                        window=window, seed=25)
+    check_step(Step(spec, poison="nan"), f"decode B={block} split={split} window={window}")
+
+
+@pytest.mark.parametrize("block", [16, 32])
+@pytest.mark.parametrize("dtype,window", [("bf16", 0), ("f16", 70), ("bf16", 256)])
+def test_prefill_small_blocks(block, dtype, window):
+    """Blocks of 16 and 32 tokens: the four waves of a workgroup copy their 16 key rows of a step
+    from different blocks; steps past the last token fall on blocks the sequence does not have."""
+    seqs = PREFILL_SEQS + [(700, 1500), (130, 129), (17, 0), (16, 0), (1, 47), (49, 15)]
+    spec = wl.BatchSpec("presmall", 4, 2, 128, block, dtype, seqs, window=window, seed=26)
+    check_step(Step(spec, poison="nan"), f"prefill B={block} {dtype} window={window}")
+
+
+@pytest.mark.parametrize("block", [16, 32])
+def test_prefill_small_blocks_split_tiles(prefill_split_env, block):
+    prefill_split_env(64)
+    spec = wl.BatchSpec("presmallsplit", 2, 1, 128, block, "bf16", [(100, 3000), (300, 0), (1, 77)], seed=27)
+    check_step(Step(spec, poison="nan"), f"prefill split B={block}")
+
+
 def test_prefill_block_192_takes_the_generic_kernel():
-    """Blocks that are not 64 * 2^k tokens are served by the generic kernel, with the same results."""
+    """Blocks that are not 16 * 2^k tokens are served by the generic kernel, with the same results."""
     spec = wl.BatchSpec("pre192", 4, 2, 128, 192, "bf16", [(200, 300), (1, 500)], seed=22)
     check_step(Step(spec, poison="nan"), "prefill block=192")
 
