@@ -17,6 +17,10 @@
 //                                              A = V^T is built in-lane: the lane loads the
 //                                              same 8 d-columns (16 B) of its 8 keys and
 //                                              transposes 8x8 with byte permutes.
+// Results leave through a small LDS staging area, so that every store instruction writes whole
+// contiguous rows (in the accumulator layout a lane's 16 bytes sit 64 bytes apart), with
+// non-temporal stores: output writes cost this streaming kernel many times their bytes (with 8
+// query heads per KV head about 7 % of its time), and this form costs least.
 // Loads for the next step are issued before the current step is computed (two register
 // buffers).  Rows outside [lo, hi] are masked with selects, never multiplied: stale or
 // poisoned cache slots cannot leak; V rows of masked keys are zeroed.
@@ -137,11 +141,15 @@ __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f
   }
 }
 
+constexpr int kDecodeStageBytes = 16 * kHeadDim * 4;  // per wave: 16 heads x 128 floats
+
 // One wavefront: unit = item * n_kv_heads + kv head (item = a sequence's run of cache blocks).
+// stage: kDecodeStageBytes of LDS that belong to this wave alone.
 template <int DT, typename T, bool kBlock16, bool kDouble = true>
 __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
                                             const T* __restrict__ kc, const T* __restrict__ vc,
-                                            T* __restrict__ out, int unit, int lane) {
+                                            T* __restrict__ out, int unit, int lane,
+                                            __attribute__((address_space(3))) char* stage) {
   const int n = lane & 15, kg = lane >> 4;
   const int slot = unit / p.n_kv_heads;  // launch order: items with the most cache blocks first
   const int hk = unit - slot * p.n_kv_heads;
@@ -215,33 +223,56 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  if (!col_live) return;
-  // acc[c][r] is output column d = (4kg + r)*8 + c of head n
+  // acc[c][r] is output column d = (4kg + r)*8 + c of head n.  The rows of the group's g heads
+  // are adjacent in memory (out and the partial buffer alike): staged row-major in LDS, then
+  // written 16 bytes per lane, consecutive lanes to consecutive addresses.
+  typedef uint32_t stage_u4 __attribute__((ext_vector_type(4)));
+  typedef float stage_f4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) stage_u4 lds_u4;
+  typedef __attribute__((address_space(3))) stage_f4 lds_f4;
   if (n_splits == 1) {
-    const float inv = 1.f / l;
-    T* orow = out + ((int64_t)sd.q_offset * p.n_q_heads + hq) * kHeadDim;
+    if (col_live) {
+      const float inv = 1.f / l;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      uint4 w;
-      w.x = Mma<DT>::pack2(acc[0][r] * inv, acc[1][r] * inv);
-      w.y = Mma<DT>::pack2(acc[2][r] * inv, acc[3][r] * inv);
-      w.z = Mma<DT>::pack2(acc[4][r] * inv, acc[5][r] * inv);
-      w.w = Mma<DT>::pack2(acc[6][r] * inv, acc[7][r] * inv);
-      *reinterpret_cast<uint4*>(orow + (4 * kg + r) * 8) = w;
+      for (int r = 0; r < 4; ++r) {
+        stage_u4 w;
+        w.x = Mma<DT>::pack2(acc[0][r] * inv, acc[1][r] * inv);
+        w.y = Mma<DT>::pack2(acc[2][r] * inv, acc[3][r] * inv);
+        w.z = Mma<DT>::pack2(acc[4][r] * inv, acc[5][r] * inv);
+        w.w = Mma<DT>::pack2(acc[6][r] * inv, acc[7][r] * inv);
+        *reinterpret_cast<lds_u4*>(stage + n * (kHeadDim * 2) + (4 * kg + r) * 16) = w;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();  // one wave: its LDS accesses complete in program order
+    char* obase = reinterpret_cast<char*>(out + ((int64_t)sd.q_offset * p.n_q_heads + hk * g) * kHeadDim);
+    const int n_bytes = g * kHeadDim * 2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {  // 1 KB = 4 heads per instruction
+      const int off = j * 1024 + lane * 16;
+      if (off < n_bytes) __builtin_nontemporal_store(*reinterpret_cast<lds_u4*>(stage + off), reinterpret_cast<stage_u4*>(obase + off));
     }
   } else {
     const int64_t pi = (int64_t)item * p.n_q_heads + hq;
-    if (kg == 0) {
-      f.part_ml[pi * 2] = m;
-      f.part_ml[pi * 2 + 1] = l;
-    }
-    float* prow = f.part_acc + pi * kHeadDim;
+    if (col_live) {
+      if (kg == 0) {
+        f.part_ml[pi * 2] = m;
+        f.part_ml[pi * 2 + 1] = l;
+      }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float4 lo4 = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
-      float4 hi4 = {acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
-      *reinterpret_cast<float4*>(prow + (4 * kg + r) * 8) = lo4;
-      *reinterpret_cast<float4*>(prow + (4 * kg + r) * 8 + 4) = hi4;
+      for (int r = 0; r < 4; ++r) {
+        const stage_f4 lo4 = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+        const stage_f4 hi4 = {acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
+        *reinterpret_cast<lds_f4*>(stage + n * (kHeadDim * 4) + (4 * kg + r) * 32) = lo4;
+        *reinterpret_cast<lds_f4*>(stage + n * (kHeadDim * 4) + (4 * kg + r) * 32 + 16) = hi4;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    char* pbase = reinterpret_cast<char*>(f.part_acc + ((int64_t)item * p.n_q_heads + hk * g) * kHeadDim);
+    const int n_bytes = g * kHeadDim * 4;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {  // 1 KB = 2 heads per instruction
+      const int off = j * 1024 + lane * 16;
+      if (off < n_bytes) __builtin_nontemporal_store(*reinterpret_cast<lds_f4*>(stage + off), reinterpret_cast<stage_f4*>(pbase + off));
     }
   }
 }

@@ -64,7 +64,8 @@ __global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
                                                                 const T* __restrict__ kc,
                                                                 const T* __restrict__ vc,
                                                                 T* __restrict__ out) {
-  decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x);
+  __shared__ __attribute__((aligned(16))) char stage[kDecodeStageBytes];
+  decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x, (lds_char*)stage);
 }
 
 template <int DT, typename T>
@@ -92,7 +93,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
   } else {
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;
-    decode_unit<DT, T, false>(p, f, q, kc, vc, out, unit, threadIdx.x & 63);  // the host launches this kernel for blocks of 32 tokens or more only
+    // (the host launches this kernel for blocks of 32 tokens or more only)
+    decode_unit<DT, T, false>(p, f, q, kc, vc, out, unit, threadIdx.x & 63,
+                              (lds_char*)lds + (threadIdx.x >> 6) * kDecodeStageBytes);
   }
 }
 
