@@ -152,7 +152,7 @@ size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_s
  * Validation (host side): n_new >= 1, n_cached >= 0, q_offsets are the running sum of
  * n_new and end at n_tokens, ceil((n_cached+n_new)/block_size) <= max_blocks.
  * Tuning knobs (environment, read per call; defaults suit MI355X): FSF_DECODE_TARGET_WAVES
- * (about how many generation-row wave units a pass is cut into, default 16384) and
+ * (about how many generation-row wave units a pass is at least cut into, default 4096) and
  * FSF_DECODE_MIN_ITEM_BLOCKS (no KV split leaves fewer cache blocks than this per unit,
  * default 16, or 1024 tokens' worth for blocks below 64 tokens); FSF_PREFILL_NO_SPLIT (set: prompt-chunk tiles are never split along their keys)
  * and FSF_PREFILL_SPLIT_UNITS (the number of compute units the split rule assumes, default

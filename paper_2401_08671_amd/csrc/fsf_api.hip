@@ -312,7 +312,9 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
     fsf::visible_range(descs_host[s].n_cached, cfg->window, lo, hi);
     dec_blocks += hi / cfg->block_size - lo / cfg->block_size + 1;
   }
-  const int target_waves = env_int("FSF_DECODE_TARGET_WAVES", 16384);
+  // Two rounds of the chip's 2048 wave slots: with the units launched longest first that is
+  // balance enough, and every split costs partial results whose writes are expensive.
+  const int target_waves = env_int("FSF_DECODE_TARGET_WAVES", 4096);
   // no item shorter than 16 blocks, or 1024 keys where blocks are smaller than 64 tokens
   const int min_item_blocks = env_int("FSF_DECODE_MIN_ITEM_BLOCKS", cfg->block_size < 64 ? 1024 / cfg->block_size : 16);
   int64_t target_items = target_waves / cfg->n_kv_heads;
