@@ -408,13 +408,11 @@ def prologue():
     return L
 
 
-PARTIAL_ROW_FLOATS = 136     # a partial result row: O^T 128 floats, then m, l (then padding to 16 bytes x 34)
-
-
 def epilogue():
     """Normal mode: O^T / l, rounded, to the lane's output rows.  Partial mode (the tile's key
     range was split across workgroups): O^T as it is, the reference m and the sum l, in fp32, to
-    the lane's rows of the partial-result buffer.  Accumulator mt, register r of a row block is
+    the lane's rows of the partial-result buffer (a row there is O^T, 128 floats, then m and l at
+    byte 512; the caller spaces the rows).  Accumulator mt, register r of a row block is
     column 32 mt + 8 (r / 4) + 4 hg + r % 4; the row addresses already include the lane's 4 hg
     columns."""
     partial, end = label('partial'), label('end')
