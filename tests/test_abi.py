@@ -55,3 +55,26 @@ def test_argument_validation_without_gpu():
     # null tensors with work to do
     st = L.fsf_ragged_attention(ctypes.byref(cfg), None, None, None, None, None, None, 1, 1, 1, None, None, 0, None)
     assert st == fsf.FSF_ERR_INVALID_ARG
+
+
+def test_rotary_append_validation_without_gpu():
+    """fsf_kv_append_rotary checks shapes, descriptors and the table length on the host and
+    launches nothing when they are wrong (the device pointers here are never dereferenced)."""
+    import numpy as np
+    L = fsf.lib()
+    fake = ctypes.c_void_p(0x1000)      # stands in for device memory; validation fails before any launch
+    descs = np.array([[4, 0, 0, 0], [1, 9, 4, 1]], np.int32)
+    host = ctypes.c_void_p(descs.ctypes.data)
+
+    def call(cfg, table_positions, n_tokens=5, descs_host=host):
+        return L.fsf_kv_append_rotary(ctypes.byref(cfg), fake, fake, fake, fake, fake, descs_host, fake,
+                                      2, 4, n_tokens, fake, table_positions, None)
+    cfg = fsf.make_cfg(2, 2, 64, 16, "f32", 8)
+    assert call(cfg, 9) == fsf.FSF_ERR_INVALID_ARG            # position 9 needs a tenth table row
+    assert call(cfg, -1) == fsf.FSF_ERR_INVALID_ARG
+    assert call(cfg, 10, n_tokens=6) == fsf.FSF_ERR_INVALID_ARG   # descriptors do not add up to n_tokens
+    assert call(cfg, 10, descs_host=None) == fsf.FSF_ERR_INVALID_ARG
+    odd = fsf.make_cfg(2, 2, 63, 16, "f32", 8)
+    assert call(odd, 10) in (fsf.FSF_ERR_UNSUPPORTED, fsf.FSF_ERR_INVALID_ARG)
+    # an empty pass is a no-op whatever the pointers
+    assert L.fsf_kv_append_rotary(ctypes.byref(cfg), None, None, None, None, None, None, None, 0, 1, 0, None, 0, None) == fsf.FSF_OK
