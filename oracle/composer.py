@@ -30,7 +30,18 @@ R6  out of blocks: a generation that cannot get its block is skipped this pass (
     nothing fits, no later prompt is started.  No eviction or swapping.
 R7  descriptor order: generations (rotation order), then prompt chunks (arrival order);
     ``q_offset`` is the running sum of ``n_new``.
-R8  if requests exist but nothing can be scheduled the composer reports "no blocks".
+R8  if requests exist but nothing can be scheduled the composer reports "no blocks"
+    (``exhaustion="stall"``, the default).
+R9  ``exhaustion="preempt_newest"``: in the situation of R8 the sequence that arrived last
+    among those holding blocks gives its blocks back (to the back of the free list, in
+    logical order) and starts over: its cache is gone, so the ``n_cached`` tokens it had
+    processed plus the generated token it was about to feed become a prompt of
+    ``n_cached + 1`` tokens (a partly processed prompt simply restarts), queued by its
+    arrival order; tokens it has emitted stay emitted.  The decision is then taken again,
+    and again, until something can be scheduled.  If the only sequence holding blocks is
+    stuck there is nothing to take from: "no blocks" as in R8.  (The paper does not say
+    what happens when the pool runs dry; recomputation is the simplest policy that keeps
+    a full pool from stopping the server, and the oldest sequence always makes progress.)
 
 Two further policies serve the scheduling simulator as points of comparison.  They are the
 batch decisions the paper sets Dynamic SplitFuse against (Sec. 2.2 continuous batching with
@@ -63,6 +74,7 @@ class _Seq:
     max_new_tokens: int
     n_cached: int = 0
     emitted: int = 0
+    arrival: int = 0
     blocks: list = field(default_factory=list)
 
 
@@ -71,14 +83,19 @@ def _ceil_div(a: int, b: int) -> int:
 
 
 POLICIES = ("splitfuse", "prompt_first", "whole_prompt_joins")
+EXHAUSTION = ("stall", "preempt_newest")
 
 
 class SplitFuseComposer:
     def __init__(self, token_budget: int, max_seqs: int, block_size: int, num_blocks: int,
-                 free_list_order=None, policy: str = "splitfuse"):
+                 free_list_order=None, policy: str = "splitfuse", exhaustion: str = "stall"):
         assert token_budget >= 1 and max_seqs >= 1 and block_size >= 1 and num_blocks >= 1
-        assert policy in POLICIES
+        assert policy in POLICIES and exhaustion in EXHAUSTION
         self.policy = policy
+        self.exhaustion = exhaustion
+        self.n_arrived = 0
+        self.n_preemptions = 0          # R9 statistics
+        self.tokens_discarded = 0
         self.token_budget = token_budget
         self.max_seqs = max_seqs
         self.block_size = block_size
@@ -92,7 +109,8 @@ class SplitFuseComposer:
     # ------------------------------------------------------------------ requests
     def add_request(self, seq_id: int, prompt_len: int, max_new_tokens: int) -> None:
         assert prompt_len >= 1 and max_new_tokens >= 1
-        self.prompts.append(_Seq(seq_id, prompt_len, max_new_tokens))
+        self.prompts.append(_Seq(seq_id, prompt_len, max_new_tokens, arrival=self.n_arrived))
+        self.n_arrived += 1
 
     def n_free_blocks(self) -> int:
         return len(self.free)
@@ -109,8 +127,45 @@ class SplitFuseComposer:
         ``emits[k]`` is 1 if descriptor ``k`` produces a token in this pass.
         """
         assert self.pending is None, "previous pass not committed"
+        while True:
+            batch = self._decide()
+            if batch or self.n_live() == 0:
+                break
+            if self.exhaustion == "stall" or not self._preempt_newest():      # R8, R9
+                raise NoBlocksError("requests are waiting but no KV block is free")
+
+        descs, tables, emits = [], [], []
+        q_off = 0
+        for seq, n_new, em, _ in batch:        # generations were placed before prompts (R7)
+            descs.append((n_new, seq.n_cached, q_off, seq.seq_id))
+            tables.append(list(seq.blocks))
+            emits.append(em)
+            q_off += n_new
+        self.pending = batch
+        return descs, tables, emits
+
+    def _preempt_newest(self) -> bool:
+        """R9.  False if there is nothing to take blocks from."""
+        holders = [s for s in list(self.prompts) + self.decodes if s.blocks]
+        if len(holders) < 2:
+            return False
+        victim = max(holders, key=lambda s: s.arrival)
+        self.n_preemptions += 1
+        self.tokens_discarded += victim.n_cached
+        self._retire(victim)
+        if any(s is victim for s in self.decodes):
+            self.decodes = [s for s in self.decodes if s is not victim]
+            victim.prompt_len = victim.n_cached + 1
+            later = [i for i, s in enumerate(self.prompts) if s.arrival > victim.arrival]
+            self.prompts.insert(later[0] if later else len(self.prompts), victim)
+        victim.n_cached = 0
+        return True
+
+    def _decide(self):
+        """One batch decision on the current state: list of (seq, n_new, emits, is_decode);
+        blocks of the scheduled sequences are taken from the free list."""
         B = self.block_size
-        batch = []                  # (seq, n_new, emits, is_decode)
+        batch = []
         budget_left = self.token_budget
         seqs_left = self.max_seqs
 
@@ -177,18 +232,7 @@ class SplitFuseComposer:
             if take < want:
                 break
 
-        if not batch and self.n_live() > 0:
-            raise NoBlocksError("requests are waiting but no KV block is free")
-
-        descs, tables, emits = [], [], []
-        q_off = 0
-        for seq, n_new, em, _ in batch:        # generations were placed before prompts (R7)
-            descs.append((n_new, seq.n_cached, q_off, seq.seq_id))
-            tables.append(list(seq.blocks))
-            emits.append(em)
-            q_off += n_new
-        self.pending = batch
-        return descs, tables, emits
+        return batch
 
     def step_done(self) -> None:
         """Commit the composed pass: advance caches, start/finish generations (R4, R5)."""

@@ -263,3 +263,110 @@ def test_comparison_policies_invariants(policy, seed):
             if len(prompts) > 1:
                 assert sum(n for n, *_ in prompts) <= budget
     assert seen_prompt == set(prompt_len)
+
+
+# ------------------------------------------------------------------ pool exhaustion: preempt the newest (R9)
+def test_preempt_newest_hand_worked_schedule():
+    """Budget 8, blocks of 4 tokens, a pool of 4 blocks, requests A = (prompt 6, generate 6) and
+    B = (6, 6).  Worked by hand:
+      pass 1  A takes its 6 prompt tokens (blocks 0, 1) and emits; B gets the 2 tokens left (block 2)
+      pass 2  A generates (position 6, no new block); B finishes its prompt (4 tokens, block 3), emits
+      pass 3  both generate (positions 7 and 6)
+      pass 4  A needs a third block for position 8, none is free: skipped; B generates (position 7)
+      pass 5  A needs a block, B needs a block (position 8): nothing can run.  Stall: "no blocks".
+              Preempt-newest: B arrived last, gives blocks 2, 3 back and restarts as a prompt of
+              8 + 1 = 9 tokens (3 of its 6 tokens already emitted); A generates with block 2,
+              B's first chunk is the 4 tokens that fit block 3
+      pass 6, 7  A generates (positions 9, 10; no new block) and retires with 6 tokens emitted;
+              B cannot get room for a single token
+      pass 8  B takes its remaining 5 tokens with blocks 0, 1 and emits its 4th token
+      pass 9, 10  B generates (positions 9, 10) and retires with 6 tokens emitted."""
+    want = [
+        ([(6, 0, 0, 0), (2, 0, 6, 1)], [[0, 1], [2]], [1, 0]),
+        ([(1, 6, 0, 0), (4, 2, 1, 1)], [[0, 1], [2, 3]], [1, 1]),
+        ([(1, 7, 0, 0), (1, 6, 1, 1)], [[0, 1], [2, 3]], [1, 1]),
+        ([(1, 7, 0, 1)], [[2, 3]], [1]),
+        ([(1, 8, 0, 0), (4, 0, 1, 1)], [[0, 1, 2], [3]], [1, 0]),
+        ([(1, 9, 0, 0)], [[0, 1, 2]], [1]),
+        ([(1, 10, 0, 0)], [[0, 1, 2]], [1]),
+        ([(5, 4, 0, 1)], [[3, 0, 1]], [1]),
+        ([(1, 9, 0, 1)], [[3, 0, 1]], [1]),
+        ([(1, 10, 0, 1)], [[3, 0, 1]], [1]),
+    ]
+    c = SplitFuseComposer(8, 4, 4, 4, exhaustion="preempt_newest")
+    c.add_request(0, 6, 6)
+    c.add_request(1, 6, 6)
+    for k, (descs, tables, emits) in enumerate(want):
+        got = c.compose()
+        assert got == (descs, tables, emits), f"pass {k + 1}: {got}"
+        c.step_done()
+    assert c.n_live() == 0 and c.n_free_blocks() == 4
+    assert (c.n_preemptions, c.tokens_discarded) == (1, 8)
+    # the default stalls at pass 5
+    c = SplitFuseComposer(8, 4, 4, 4)
+    c.add_request(0, 6, 6)
+    c.add_request(1, 6, 6)
+    for _ in range(4):
+        c.compose()
+        c.step_done()
+    with pytest.raises(NoBlocksError):
+        c.compose()
+
+
+def test_preempt_newest_cannot_help_a_sequence_that_alone_exceeds_the_pool():
+    c = SplitFuseComposer(8, 4, 4, 2, exhaustion="preempt_newest")     # 8 token slots in all
+    c.add_request(0, 6, 6)                                               # needs 11
+    for _ in range(3):
+        c.compose()
+        c.step_done()
+    with pytest.raises(NoBlocksError):
+        c.compose()
+    assert c.n_preemptions == 0
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_preempt_newest_always_finishes_every_request(seed):
+    """Any pool that can hold the largest single sequence serves every request to its last token:
+    exactly max_new_tokens emissions each, within the budget in every pass, blocks never shared
+    and all returned; a restarted sequence starts again from an empty cache and is otherwise
+    consistent from pass to pass."""
+    rng = np.random.default_rng(900 + seed)
+    budget = int(rng.integers(4, 64))
+    B = int(rng.choice([1, 4, 16]))
+    reqs = [(int(rng.integers(1, 4 * budget)), int(rng.integers(1, 40))) for _ in range(int(rng.integers(2, 14)))]
+    largest = max(-(-(p + g) // B) for p, g in reqs)
+    num_blocks = largest + int(rng.integers(0, 3))
+    c = SplitFuseComposer(budget, 8, B, num_blocks, rng.permutation(num_blocks), exhaustion="preempt_newest")
+    for sid, (p, g) in enumerate(reqs):
+        c.add_request(sid, p, g)
+    emitted = [0] * len(reqs)
+    cached = [0] * len(reqs)
+    passes = 0
+    while c.n_live() > 0:
+        descs, tables, emits = c.compose()
+        passes += 1
+        assert passes < 100000
+        assert descs and sum(d[0] for d in descs) <= budget
+        held = [b for t in tables for b in t]
+        assert len(held) == len(set(held))
+        for (n_new, n_cached, _, sid), tab, em in zip(descs, tables, emits):
+            assert n_cached in (cached[sid], 0)                  # continues, or restarted from nothing
+            assert len(tab) == -(-(n_cached + n_new) // B)
+            cached[sid] = n_cached + n_new
+            emitted[sid] += em
+        c.step_done()
+    assert emitted == [g for _, g in reqs]
+    assert c.n_free_blocks() == num_blocks
+    if seed % 3 == 0:
+        # with room for everything the policy never acts and the schedule is the default one
+        roomy = sum(-(-(p + g) // B) for p, g in reqs)
+        a = SplitFuseComposer(budget, 8, B, roomy, exhaustion="preempt_newest")
+        b = SplitFuseComposer(budget, 8, B, roomy)
+        for sid, (p, g) in enumerate(reqs):
+            a.add_request(sid, p, g)
+            b.add_request(sid, p, g)
+        while b.n_live() > 0:
+            assert a.compose() == b.compose()
+            a.step_done()
+            b.step_done()
+        assert a.n_preemptions == 0
