@@ -177,7 +177,7 @@ int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_c
  * takes min(remaining prompt, remaining budget); blocks are popped from the front of
  * the free list and returned to its back when a sequence retires; without free blocks
  * a generation is skipped for the pass and a prompt chunk shrinks to what fits, after
- * which no later prompt is started; there is no eviction.
+ * which no later prompt is started; nothing is evicted unless fsf_sched_set_exhaustion says so.
  */
 typedef struct fsf_sched fsf_sched;
 
@@ -205,6 +205,30 @@ typedef enum {
   FSF_POLICY_WHOLE_PROMPT_JOINS = 2
 } fsf_policy;
 int fsf_sched_set_policy(fsf_sched* s, int32_t policy);
+
+/*
+ * What fsf_compose_batch does when requests wait but nothing can be scheduled because the
+ * block pool is used up (the paper describes the blocked cache, Sec. 2.1, but no policy for a
+ * full pool).  To be chosen before the first request.
+ *   FSF_EXHAUST_STALL           (default) report FSF_ERR_NO_BLOCKS and change nothing
+ *   FSF_EXHAUST_PREEMPT_NEWEST  the sequence that arrived last among those holding blocks gives
+ *                               them back (to the end of the free list, in logical order) and
+ *                               starts over: its n_cached processed tokens plus the generated
+ *                               token it was about to feed become a prompt of n_cached + 1
+ *                               tokens, queued by its arrival order; emitted tokens stay
+ *                               emitted.  The decision is taken again until something can be
+ *                               scheduled.  The caller sees the restart as a descriptor with
+ *                               n_cached = 0 for a known seq_id and must feed that sequence's
+ *                               tokens from its beginning again.  FSF_ERR_NO_BLOCKS remains for
+ *                               the case that fewer than two sequences hold blocks (a sequence
+ *                               that alone exceeds the pool).  Preemptions made before an
+ *                               error is returned are not undone.
+ * fsf_sched_preemptions reports how many sequences were restarted so far and how many cached
+ * tokens that discarded.
+ */
+typedef enum { FSF_EXHAUST_STALL = 0, FSF_EXHAUST_PREEMPT_NEWEST = 1 } fsf_exhaustion;
+int fsf_sched_set_exhaustion(fsf_sched* s, int32_t mode);
+int fsf_sched_preemptions(const fsf_sched* s, int64_t* n_preemptions_out, int64_t* tokens_discarded_out);
 
 /* Queue a request: prompt_len >= 1 tokens to read, max_new_tokens >= 1 tokens to emit.
  * The sequence emits its first token in the pass that consumes its last prompt token,

@@ -33,10 +33,11 @@ EMA_ALPHA = 0.2
 PROMPT_TOKENS_PER_S = 512.0
 
 
-def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, block_size, num_blocks):
+def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, block_size, num_blocks,
+             exhaustion="stall"):
     """requests: list of (prompt_len, gen_len).  Returns (log, total_time, n_passes) with
     log[i] = dict(sent=..., tokens=[time of every emitted token])."""
-    comp = SplitFuseComposer(token_budget, max_seqs, block_size, num_blocks, policy=policy)
+    comp = SplitFuseComposer(token_budget, max_seqs, block_size, num_blocks, policy=policy, exhaustion=exhaustion)
     log = [None] * len(requests)
     nxt = 0
     t = 0.0

@@ -17,6 +17,14 @@
 //                      the generations and lets waiting prompts join whole, unsplit
 // Neither splits a prompt; both use the same block allocator and rotation.
 //
+// When the pool runs dry the paper is silent.  By default a pass in which nothing can be
+// scheduled is reported as FSF_ERR_NO_BLOCKS.  With FSF_EXHAUST_PREEMPT_NEWEST the sequence
+// that arrived last among those holding blocks gives them back and starts over as a prompt of
+// the tokens it had processed plus the generated token it was about to feed (its emitted
+// tokens stay emitted), and the decision is taken again; the oldest sequence therefore always
+// makes progress, and only a sequence that alone exceeds the pool still ends in
+// FSF_ERR_NO_BLOCKS.
+//
 // Pure host code: no HIP calls.  Sequences live in a slab indexed by small integers;
 // the two queues hold slab indices.  compose() works in two phases, plan then apply, so
 // an error leaves the scheduler untouched.
@@ -35,6 +43,7 @@ struct Seq {
   int32_t max_new = 0;
   int32_t n_cached = 0;
   int32_t emitted = 0;
+  int64_t arrival = 0;  // order of fsf_sched_add_request calls
   bool live = false;
   std::vector<int32_t> blocks;
 };
@@ -64,7 +73,52 @@ struct fsf_sched {
   std::vector<Planned> pending;
   bool has_pending = false;
   int32_t policy = FSF_POLICY_SPLITFUSE;
+  int32_t exhaustion = FSF_EXHAUST_STALL;
+  int64_t n_arrived = 0;
+  int64_t n_preemptions = 0;
+  int64_t tokens_discarded = 0;
 };
+
+namespace {
+
+// FSF_EXHAUST_PREEMPT_NEWEST: take the blocks of the newest sequence that holds any.  False
+// if fewer than two sequences hold blocks (nothing to take from).
+bool preempt_newest(fsf_sched* s) {
+  int32_t victim = -1, holders = 0;
+  bool victim_decodes = false;
+  auto look = [&](int32_t slot, bool is_decode) {
+    const Seq& q = s->slab[slot];
+    if (q.blocks.empty()) return;
+    ++holders;
+    if (victim < 0 || q.arrival > s->slab[victim].arrival) {
+      victim = slot;
+      victim_decodes = is_decode;
+    }
+  };
+  for (int32_t slot : s->prompts) look(slot, false);
+  for (int32_t slot : s->decodes) look(slot, true);
+  if (holders < 2) return false;
+  Seq& q = s->slab[victim];
+  ++s->n_preemptions;
+  s->tokens_discarded += q.n_cached;
+  for (int32_t b : q.blocks) s->free_blocks.push_back(b);
+  q.blocks.clear();
+  if (victim_decodes) {
+    for (auto it = s->decodes.begin(); it != s->decodes.end(); ++it)
+      if (*it == victim) {
+        s->decodes.erase(it);
+        break;
+      }
+    q.prompt_len = q.n_cached + 1;
+    auto pos = s->prompts.begin();
+    while (pos != s->prompts.end() && s->slab[*pos].arrival < q.arrival) ++pos;
+    s->prompts.insert(pos, victim);
+  }
+  q.n_cached = 0;
+  return true;
+}
+
+}  // namespace
 
 extern "C" int fsf_sched_create(fsf_sched** out, int32_t token_budget, int32_t max_seqs,
                                 int32_t block_size, int64_t num_blocks,
@@ -101,6 +155,20 @@ extern "C" int fsf_sched_set_policy(fsf_sched* s, int32_t policy) {
   return FSF_OK;
 }
 
+extern "C" int fsf_sched_set_exhaustion(fsf_sched* s, int32_t mode) {
+  if (!s || (mode != FSF_EXHAUST_STALL && mode != FSF_EXHAUST_PREEMPT_NEWEST)) return FSF_ERR_INVALID_ARG;
+  if (s->has_pending || !s->prompts.empty() || !s->decodes.empty()) return FSF_ERR_INVALID_ARG;
+  s->exhaustion = mode;
+  return FSF_OK;
+}
+
+extern "C" int fsf_sched_preemptions(const fsf_sched* s, int64_t* n_preemptions_out, int64_t* tokens_discarded_out) {
+  if (!s || !n_preemptions_out || !tokens_discarded_out) return FSF_ERR_INVALID_ARG;
+  *n_preemptions_out = s->n_preemptions;
+  *tokens_discarded_out = s->tokens_discarded;
+  return FSF_OK;
+}
+
 extern "C" int fsf_sched_add_request(fsf_sched* s, int32_t seq_id, int32_t prompt_len,
                                      int32_t max_new_tokens) {
   if (!s || prompt_len < 1 || max_new_tokens < 1) return FSF_ERR_INVALID_ARG;
@@ -118,6 +186,7 @@ extern "C" int fsf_sched_add_request(fsf_sched* s, int32_t seq_id, int32_t promp
   q.max_new = max_new_tokens;
   q.n_cached = 0;
   q.emitted = 0;
+  q.arrival = s->n_arrived++;
   q.live = true;
   q.blocks.clear();
   s->prompts.push_back(slot);
@@ -133,10 +202,12 @@ extern "C" int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t*
   if (s->has_pending) return FSF_ERR_INVALID_ARG;
 
   const int64_t B = s->block_size;
+  std::vector<Planned> plan;
+  for (;;) {  // taken again after every preemption
+  plan.clear();
   int64_t free_left = static_cast<int64_t>(s->free_blocks.size());
   int32_t budget_left = s->token_budget;
   int32_t seqs_left = s->max_seqs;
-  std::vector<Planned> plan;
 
   // ---- the comparison policies never split a prompt
   bool prompt_pass = false;
@@ -208,10 +279,17 @@ extern "C" int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t*
     if (take < want) break;  // blocks ran out: start no later prompt
   }
 
+  if (!plan.empty() || (s->prompts.empty() && s->decodes.empty())) break;
+  if (s->exhaustion != FSF_EXHAUST_PREEMPT_NEWEST || !preempt_newest(s)) {
+    *n_seqs_out = 0;
+    *n_tokens_out = 0;
+    return FSF_ERR_NO_BLOCKS;
+  }
+  }  // for (;;)
+
   if (plan.empty()) {
     *n_seqs_out = 0;
     *n_tokens_out = 0;
-    if (!s->prompts.empty() || !s->decodes.empty()) return FSF_ERR_NO_BLOCKS;
     s->pending.clear();
     s->has_pending = true;  // an empty pass still pairs with step_done()
     return FSF_OK;

@@ -67,6 +67,10 @@ def lib() -> C.CDLL:
     L.fsf_sched_create.argtypes = [C.POINTER(vp), i32, i32, i32, i64, vp]
     L.fsf_sched_destroy.restype = None
     L.fsf_sched_destroy.argtypes = [vp]
+    L.fsf_sched_set_exhaustion.restype = C.c_int
+    L.fsf_sched_set_exhaustion.argtypes = [vp, i32]
+    L.fsf_sched_preemptions.restype = C.c_int
+    L.fsf_sched_preemptions.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
     L.fsf_sched_add_request.restype = C.c_int
     L.fsf_sched_add_request.argtypes = [vp, i32, i32, i32]
     L.fsf_compose_batch.restype = C.c_int
@@ -163,6 +167,7 @@ def alloc_workspace(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int, d
 
 
 FSF_POLICY_SPLITFUSE, FSF_POLICY_PROMPT_FIRST, FSF_POLICY_WHOLE_PROMPT_JOINS = 0, 1, 2
+FSF_EXHAUST_STALL, FSF_EXHAUST_PREEMPT_NEWEST = 0, 1
 
 
 class Scheduler:
@@ -184,6 +189,15 @@ class Scheduler:
 
     def set_policy(self, policy: int) -> None:
         _check(lib().fsf_sched_set_policy(self._h, policy), "fsf_sched_set_policy")
+
+    def set_exhaustion(self, mode: int) -> None:
+        _check(lib().fsf_sched_set_exhaustion(self._h, mode), "fsf_sched_set_exhaustion")
+
+    def preemptions(self):
+        """(sequences restarted so far, cached tokens that discarded)"""
+        n, tok = C.c_int64(0), C.c_int64(0)
+        _check(lib().fsf_sched_preemptions(self._h, C.byref(n), C.byref(tok)), "fsf_sched_preemptions")
+        return int(n.value), int(tok.value)
 
     def add_request(self, seq_id: int, prompt_len: int, max_new_tokens: int) -> None:
         _check(lib().fsf_sched_add_request(self._h, seq_id, prompt_len, max_new_tokens), "fsf_sched_add_request")

@@ -54,6 +54,7 @@ class PoolStats:
         self.B, self.num_blocks, self.budget = block_size, num_blocks, token_budget
         self.cached = {}              # live sequence -> tokens in the cache
         self.passes = self.short_passes = 0
+        self.preemptions = self.tokens_discarded = 0   # sequences restarted by the exhaustion policy
         self.sum_used = self.sum_tokens = self.peak_used = 0
 
     def on_pass(self, sched, descs, waiting_prompt_tokens: int):
@@ -77,11 +78,12 @@ class PoolStats:
         return {"pool_blocks": self.num_blocks, "mean_blocks_in_use": used, "peak_blocks_in_use": self.peak_used,
                 "mean_pool_utilisation": used / self.num_blocks,
                 "tokens_per_allocated_slot": self.sum_tokens / max(self.sum_used * self.B, 1),
-                "passes_cut_short_by_the_pool": self.short_passes / max(self.passes, 1)}
+                "passes_cut_short_by_the_pool": self.short_passes / max(self.passes, 1),
+                "sequences_restarted": self.preemptions, "cached_tokens_discarded": self.tokens_discarded}
 
 
 def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, block_size, num_blocks,
-             max_blocks=None, on_pass=None, pool_stats: PoolStats = None):
+             max_blocks=None, on_pass=None, pool_stats: PoolStats = None, exhaustion: int = fsf.FSF_EXHAUST_STALL):
     """Closed loop of ``n_clients`` clients over ``requests = [(prompt_len, gen_len)]``.
 
     ``step_time(descs)`` returns the seconds a pass with descriptors ``descs`` (rows
@@ -92,6 +94,7 @@ def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, blo
         max_blocks = max(-(-(p + g) // block_size) for p, g in requests)
     sched = fsf.Scheduler(token_budget, max_seqs, block_size, num_blocks, max_blocks)
     sched.set_policy(POLICIES[policy])
+    sched.set_exhaustion(exhaustion)
     R = len(requests)
     sent = np.zeros(R)
     tokens = [[] for _ in range(R)]
@@ -107,6 +110,7 @@ def simulate(policy, requests, n_clients, step_time, token_budget, max_seqs, blo
         if on_pass is not None:
             on_pass(descs, tables)
         if pool_stats is not None:
+            pool_stats.preemptions, pool_stats.tokens_discarded = sched.preemptions()
             in_pass = {int(d[3]): int(d[0]) + int(d[1]) for d in descs}
             waiting = sum(requests[i][0] - in_pass.get(i, pool_stats.cached.get(i, 0))
                           for i in range(nxt) if len(tokens[i]) == 0)
@@ -291,9 +295,12 @@ def run(policy: str, requests, n_clients: int, token_budget: int, measured: bool
     return out
 
 
-def pool_sweep(requests, n_clients: int, token_budget: int, fractions=(1.0, 0.8, 0.6, 0.4, 0.3), block_size: int = 64):
+def pool_sweep(requests, n_clients: int, token_budget: int, fractions=(1.0, 0.8, 0.6, 0.4, 0.3), block_size: int = 64,
+               exhaustion: int = fsf.FSF_EXHAUST_STALL):
     """Dynamic SplitFuse with a KV pool of a fraction of what the clients' largest requests would
-    need together: throughput, occupancy, and how often the pool cut a pass short (analytic times)."""
+    need together: throughput, occupancy, and how often the pool cut a pass short (analytic times).
+    ``exhaustion``: what the composer does when nothing can be scheduled (stall, or restart the
+    newest sequence and recompute it)."""
     full = sum(-(-(p + g) // block_size) for p, g in sorted(requests, key=lambda r: -(r[0] + r[1]))[:n_clients])
     largest = max(-(-(p + g) // block_size) for p, g in requests)
     out = []
@@ -303,16 +310,19 @@ def pool_sweep(requests, n_clients: int, token_budget: int, fractions=(1.0, 0.8,
         try:
             sent, tokens, total, n_passes = simulate("splitfuse", requests, n_clients, ForwardModel(), token_budget,
                                                      max_seqs=n_clients + 1, block_size=block_size,
-                                                     num_blocks=num_blocks, max_blocks=largest, pool_stats=stats)
+                                                     num_blocks=num_blocks, max_blocks=largest, pool_stats=stats,
+                                                     exhaustion=exhaustion)
             m = metrics(requests, sent, tokens, total)
-            row = {"pool_fraction": frac, "throughput_rps": m["throughput_rps"],
+            row = {"pool_fraction": frac, "exhaustion": "preempt_newest" if exhaustion else "stall",
+                   "throughput_rps": m["throughput_rps"],
                    "mean_request_latency_s": m["mean_request_latency_s"], "passes": n_passes}
         except fsf.FsfError as e:
             if e.status != fsf.FSF_ERR_NO_BLOCKS:
                 raise
             # every block is held by sequences that all need one more: without eviction (the paper
             # describes none) the composer can schedule nothing
-            row = {"pool_fraction": frac, "stuck_without_free_blocks_after_passes": stats.passes}
+            row = {"pool_fraction": frac, "exhaustion": "preempt_newest" if exhaustion else "stall",
+                   "stuck_without_free_blocks_after_passes": stats.passes}
         row.update(stats.summary())
         out.append(row)
     return out
@@ -327,7 +337,10 @@ def main(argv=None):
     ap.add_argument("--pool-sweep", action="store_true", help="SplitFuse under a shrinking KV pool (no GPU)")
     a = ap.parse_args(argv)
     if a.pool_sweep:
-        rows = pool_sweep(wl.chat_requests(a.requests), a.clients[-1], a.budget)
+        rows = []
+        for mode in (fsf.FSF_EXHAUST_STALL, fsf.FSF_EXHAUST_PREEMPT_NEWEST):
+            rows += pool_sweep(wl.chat_requests(a.requests), a.clients[-1], a.budget,
+                               fractions=(1.0, 0.8, 0.6, 0.4, 0.3, 0.2, 0.1), exhaustion=mode)
         for r in rows:
             print(json.dumps(r), flush=True)
         return rows

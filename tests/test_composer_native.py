@@ -12,12 +12,13 @@ POLICY_ID = {"splitfuse": fsf.FSF_POLICY_SPLITFUSE, "prompt_first": fsf.FSF_POLI
 
 
 def run_both(budget, max_seqs, B, num_blocks, arrivals, n_steps, free_order=None, max_blocks=None,
-             policy="splitfuse"):
+             policy="splitfuse", exhaustion="stall"):
     if max_blocks is None:
         max_blocks = num_blocks
-    ref = SplitFuseComposer(budget, max_seqs, B, num_blocks, free_order, policy=policy)
+    ref = SplitFuseComposer(budget, max_seqs, B, num_blocks, free_order, policy=policy, exhaustion=exhaustion)
     nat = fsf.Scheduler(budget, max_seqs, B, num_blocks, max_blocks, free_order)
     nat.set_policy(POLICY_ID[policy])
+    nat.set_exhaustion(fsf.FSF_EXHAUST_PREEMPT_NEWEST if exhaustion == "preempt_newest" else fsf.FSF_EXHAUST_STALL)
     steps = 0
     for step in range(n_steps):
         for sid, plen, gen in arrivals.get(step, []):
@@ -38,6 +39,7 @@ def run_both(budget, max_seqs, B, num_blocks, arrivals, n_steps, free_order=None
         ref.step_done()
         nat.step_done()
         assert nat.free_blocks() == ref.n_free_blocks() and nat.live_seqs() == ref.n_live()
+        assert nat.preemptions() == (ref.n_preemptions, ref.tokens_discarded)
         steps += 1
         if step > max(arrivals, default=0) and ref.n_live() == 0:
             break
@@ -62,6 +64,43 @@ def test_equal_schedules_random_streams(seed, policy):
     num_blocks = max(tot, 1) if seed % 2 == 0 else max(tot // 6, 8)
     order = rng.permutation(num_blocks)
     run_both(budget, max_seqs, B, num_blocks, arrivals, 20000, order, policy=policy)
+
+
+@pytest.mark.parametrize("policy", ["splitfuse", "prompt_first", "whole_prompt_joins"])
+@pytest.mark.parametrize("seed", range(8))
+def test_equal_schedules_with_preemption_in_tight_pools(seed, policy):
+    """Pools a few blocks larger than the largest single sequence: the preempt-newest policy acts
+    often; the native composer must take the same victims and produce the same passes."""
+    rng = np.random.default_rng(300 + seed)
+    budget = int(rng.integers(4, 200))
+    B = int(rng.choice([1, 4, 16, 64]))
+    arrivals, sid, largest = {}, 0, 1
+    for step in range(60):
+        for _ in range(rng.poisson(0.4)):
+            plen, gen = int(rng.integers(1, 4 * budget)), int(rng.integers(1, 60))
+            arrivals.setdefault(step, []).append((sid, plen, gen))
+            largest = max(largest, -(-(plen + gen) // B))
+            sid += 1
+    num_blocks = largest + int(rng.integers(0, 4))
+    steps = run_both(budget, 16, B, num_blocks, arrivals, 100000, rng.permutation(num_blocks), policy=policy,
+                     exhaustion="preempt_newest")
+    assert steps > 0
+
+
+def test_preempt_newest_hand_worked_case_natively():
+    s = fsf.Scheduler(8, 4, 4, 4, max_blocks=4)
+    s.set_exhaustion(fsf.FSF_EXHAUST_PREEMPT_NEWEST)
+    s.add_request(0, 6, 6)
+    s.add_request(1, 6, 6)
+    for _ in range(4):
+        s.compose_batch()
+        s.step_done()
+    d, t, e = s.compose_batch()         # A needs a block, B needs a block: B restarts as a 9-token prompt
+    assert d.tolist() == [[1, 8, 0, 0], [4, 0, 1, 1]] and e.tolist() == [1, 0]
+    assert t.tolist() == [[0, 1, 2, -1], [3, -1, -1, -1]]
+    assert s.preemptions() == (1, 8)
+    with pytest.raises(fsf.FsfError):
+        s.set_exhaustion(fsf.FSF_EXHAUST_STALL)      # fixed once requests exist
 
 
 def test_policy_is_fixed_once_requests_exist():

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import policy_sim as ref
+from paper_2401_08671_amd import fsf
 from paper_2401_08671_amd import policy_sim as sim
 from paper_2401_08671_amd import workloads as wl
 
@@ -78,6 +79,21 @@ def test_native_simulation_equals_oracle(policy, n_clients):
         assert m[k] == pytest.approx(m_ref[k], rel=1e-12, abs=1e-15), k
 
 
+def test_native_simulation_equals_oracle_with_preemption():
+    """a pool of the largest request plus two blocks: sequences are restarted, natively and in the oracle alike"""
+    reqs = wl.chat_requests(24, prompt_mean=300, gen_mean=12, seed=7)
+    B = 16
+    blocks = max(-(-(p + g) // B) for p, g in reqs) + 2
+    log, total, n_passes = ref.simulate("splitfuse", reqs, 5, toy_step_time, 128, 6, B, blocks, exhaustion="preempt_newest")
+    stats = sim.PoolStats(B, blocks, 128)
+    sent, tokens, total2, n_passes2 = sim.simulate("splitfuse", reqs, 5, toy_step_time, 128, 6, B, blocks,
+                                                   pool_stats=stats, exhaustion=fsf.FSF_EXHAUST_PREEMPT_NEWEST)
+    assert total2 == total and n_passes2 == n_passes
+    for a, r in zip(tokens, log):
+        assert a.tolist() == r["tokens"]
+    assert stats.summary()["sequences_restarted"] > 0
+
+
 def test_forward_model_regimes():
     """few tokens: the pass costs a read of the weights; many: their flops (Sec. 3.1)"""
     fm = sim.ForwardModel()
@@ -100,6 +116,9 @@ def test_pool_sweep_occupancy_and_the_stuck_case():
     # ends with nothing schedulable: reported, not raised
     stuck = sim.pool_sweep([(1000, 300)] * 8, 4, 256, fractions=(0.3,))[0]
     assert "stuck_without_free_blocks_after_passes" in stuck
+    # the same pool with the preempt-newest policy serves every request, at the price of recomputation
+    served = sim.pool_sweep([(1000, 300)] * 8, 4, 256, fractions=(0.3,), exhaustion=fsf.FSF_EXHAUST_PREEMPT_NEWEST)[0]
+    assert served["throughput_rps"] > 0 and served["sequences_restarted"] > 0 and served["cached_tokens_discarded"] > 0
 
 
 @pytest.mark.gpu
