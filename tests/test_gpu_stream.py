@@ -83,3 +83,58 @@ def test_stream_200_passes():
         for b0 in range(0, run.num_blocks, 1024):
             assert np.array_equal(wl.to_numpy_storage(dev[b0:b0 + 1024]), host[b0:b0 + 1024]), f"{name} blocks {b0}.."
     print(f"stream: {total_tokens} tokens in 200 passes, {checked} rows checked, worst max-abs {worst:.2e}")
+
+
+def test_tight_pool_with_restarts_every_pass_checked():
+    """A small closed loop on a pool two blocks larger than the largest request, with the
+    preempt-newest policy: sequences are restarted, their blocks go to other sequences still
+    holding the previous owner's data, and restarted sequences are processed again from an empty
+    cache.  Every pass is checked in full against the oracle, the cache bit for bit."""
+    from paper_2401_08671_amd import fsf
+    Hq, Hkv, d, B, budget = 4, 2, 128, 64, 256
+    rng = np.random.default_rng(11)
+    reqs = [(int(rng.integers(100, 600)), int(rng.integers(5, 30))) for _ in range(10)]
+    largest = max(-(-(p + g) // B) for p, g in reqs)
+    num_blocks = largest + 2
+    sched = fsf.Scheduler(budget, 6, B, num_blocks, largest, rng.permutation(num_blocks))
+    sched.set_exhaustion(fsf.FSF_EXHAUST_PREEMPT_NEWEST)
+    cfg = fsf.make_cfg(Hq, Hkv, d, B, "bf16", num_blocks)
+    kc = wl.from_numpy_storage(np.full((num_blocks, Hkv, B, d), 0x7FC0, np.uint16), "bf16", "cuda")   # NaN everywhere
+    vc = kc.clone()
+    k_host, v_host = wl.to_numpy_storage(kc).copy(), wl.to_numpy_storage(vc).copy()
+    nxt, emitted, passes, worst = 0, [0] * len(reqs), 0, 0.0
+    for _ in range(4):
+        sched.add_request(nxt, *reqs[nxt])
+        nxt += 1
+    while sched.live_seqs() > 0:
+        descs, tables, emits = sched.compose_batch()
+        T = int(descs[:, 0].sum())
+        assert 0 < T <= budget
+        q = wl.randn((T, Hq, d), "bf16", 1.0, 5000 + 3 * passes, "cuda")
+        k_new = wl.randn((T, Hkv, d), "bf16", 1.0, 5001 + 3 * passes, "cuda")
+        v_new = wl.randn((T, Hkv, d), "bf16", 1.0, 5002 + 3 * passes, "cuda")
+        batch = fsf.DeviceBatch(descs, tables, "cuda")
+        out = torch.full_like(q, float("nan"))
+        ws = fsf.alloc_workspace(cfg, batch.n_seqs, batch.n_tokens, batch.max_blocks, "cuda")
+        fsf.kv_append(cfg, k_new, v_new, kc, vc, batch)
+        fsf.ragged_attention(cfg, q, kc, vc, batch, out, ws)
+        oa.kv_append(k_host, v_host, wl.to_numpy_storage(k_new), wl.to_numpy_storage(v_new), descs, tables, B)
+        ref = oa.ragged_attention(wl.to_numpy_storage(q), k_host, v_host, descs, tables, block_size=B,
+                                  scale=d ** -0.5, dtype="bf16")
+        torch.cuda.synchronize()
+        mx, _ = assert_outputs_close(out.to(torch.float64).cpu().numpy(), ref, "bf16", f"pass {passes}: {descs.tolist()}")
+        worst = max(worst, mx)
+        assert np.array_equal(wl.to_numpy_storage(kc), k_host) and np.array_equal(wl.to_numpy_storage(vc), v_host)
+        for dsc, em in zip(descs, emits):
+            emitted[int(dsc[3])] += int(em)
+        sched.step_done()
+        passes += 1
+        assert passes < 2000
+        while nxt < len(reqs) and sched.live_seqs() < 4:
+            sched.add_request(nxt, *reqs[nxt])
+            nxt += 1
+    restarted, discarded = sched.preemptions()
+    sched.close()
+    assert emitted == [g for _, g in reqs]
+    assert restarted > 0
+    print(f"tight pool: {passes} passes, {restarted} restarts ({discarded} cached tokens recomputed), worst max-abs {worst:.2e}")
