@@ -161,6 +161,14 @@ def test_prefill_tiles_split_along_keys(prefill_split_env, units, window, dtype)
     check_step(Step(spec, poison="nan"), f"prefill split units={units} window={window} {dtype}")
 
 
+@pytest.mark.parametrize("window", [0, 5000])
+def test_very_long_contexts(window):
+    """A generation row over 200 000 cached tokens (cut into many units and merged) and a 300-row
+    chunk over 150 000: long block tables, large offsets, thousands of steps per tile."""
+    spec = wl.BatchSpec("long", 2, 1, 128, 64, "bf16", [(1, 200_000), (300, 150_000), (1, 70_001)], window=window, seed=34)
+    check_step(Step(spec), f"long contexts window={window}")
+
+
 @pytest.mark.parametrize("flags", [0, fsf.FSF_FLAG_FUSED_LAUNCH])
 def test_mixed_batch_order_independent(flags):
     """Chunks and generations interleaved in any order (the kernels may not assume chunks come first);
