@@ -238,3 +238,41 @@ def test_random_ragged_batches(seed, prefill_split_env):
     prefill_split_env(int(rng.choice([4, 16, 64, 256])))
     spec = wl.BatchSpec(f"rand{seed}", Hq, Hkv, 128, block, dtype, seqs, window=window, seed=8000 + seed)
     check_step(Step(spec, poison="nan"), f"random batch {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} {seqs}")
+
+
+def test_a_pass_can_be_captured_in_a_graph_and_replayed():
+    """Append + attention of a mixed pass recorded into a HIP graph (the library allocates nothing,
+    clears nothing with memset and waits for nothing): every replay, with eager work and
+    synchronisation in between, gives the bits of the eager run, which is checked against the oracle."""
+    from paper_2401_08671_amd.harness import DeviceStep
+    spec = wl.BatchSpec("graph", 8, 2, 128, 64, "bf16", [(300, 100), (1, 2000), (1, 63), (700, 0), (1, 5000)], seed=35)
+    ds = DeviceStep(spec)
+    ds.step()
+    torch.cuda.synchronize()
+    eager = ds.out.clone()
+    k_after, v_after = ds.k_cache.clone(), ds.v_cache.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on the capture stream
+        ds.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ds.step()
+    torch.cuda.synchronize()
+    for r in range(4):
+        ds.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ds.out, eager), f"replay {r}"
+        assert torch.equal(ds.k_cache, k_after) and torch.equal(ds.v_cache, v_after)
+        assert float(ds.q.float().abs().sum()) > 0      # eager work between the replays
+    # and the eager result itself is right
+    kc = wl.to_numpy_storage(ds.k_cache)
+    vc = wl.to_numpy_storage(ds.v_cache)
+    from oracle import attention as oa
+    ref = oa.ragged_attention(wl.to_numpy_storage(ds.q), kc, vc, ds.descs, ds.block_tables, block_size=64,
+                              scale=spec.scale, window=0, dtype="bf16")
+    assert_outputs_close(eager.to(torch.float64).cpu().numpy(), ref, "bf16", "graph pass")
