@@ -112,7 +112,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
   }
 }
 
-// One wave per (split sequence, query head); lanes own two output columns each.
+// One wave per (split sequence, query head).  Maximum and sum: lane k takes splits k, k + 64, ...
+// and the wave reduces; outputs: lanes own two columns each and walk the splits four at a time,
+// so that the loads of several splits are in flight together (the walk is latency-bound: a long
+// sequence alone in a pass has a hundred splits and nothing else to hide behind).
 template <typename T>
 __global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __restrict__ out) {
   const int s = f.split_seqs[blockIdx.x / p.n_q_heads];
@@ -120,15 +123,37 @@ __global__ __launch_bounds__(64) void merge_kernel(Pass p, FastPlan f, T* __rest
   const int item0 = f.dec_item_start[s];
   const int n_splits = f.dec_item_start[s + 1] - item0;
   const int lane = threadIdx.x;
+  const float* ml = f.part_ml + ((int64_t)item0 * p.n_q_heads + hq) * 2;
+  const int64_t ml_stride = (int64_t)p.n_q_heads * 2;  // split to split
   float m = -INFINITY;
-  for (int k = 0; k < n_splits; ++k)
-    m = fmaxf(m, f.part_ml[((int64_t)(item0 + k) * p.n_q_heads + hq) * 2]);
-  float l = 0.f, a0 = 0.f, a1 = 0.f;
-  for (int k = 0; k < n_splits; ++k) {
-    const int64_t pi = (int64_t)(item0 + k) * p.n_q_heads + hq;
-    const float w = fast_exp2(f.part_ml[pi * 2] - m);
-    l += f.part_ml[pi * 2 + 1] * w;
-    const float2 a = *reinterpret_cast<const float2*>(f.part_acc + pi * kHeadDim + lane * 2);
+  for (int k = lane; k < n_splits; k += 64) m = fmaxf(m, ml[k * ml_stride]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  float l = 0.f;
+  for (int k = lane; k < n_splits; k += 64) l += ml[k * ml_stride + 1] * fast_exp2(ml[k * ml_stride] - m);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+  const float* acc = f.part_acc + ((int64_t)item0 * p.n_q_heads + hq) * kHeadDim + lane * 2;
+  const int64_t acc_stride = (int64_t)p.n_q_heads * kHeadDim;
+  float a0 = 0.f, a1 = 0.f;
+  int k = 0;
+  for (; k + 4 <= n_splits; k += 4) {
+    float2 a[4];
+    float w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a[u] = *reinterpret_cast<const float2*>(acc + (k + u) * acc_stride);
+      w[u] = fast_exp2(ml[(k + u) * ml_stride] - m);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a0 += a[u].x * w[u];
+      a1 += a[u].y * w[u];
+    }
+  }
+  for (; k < n_splits; ++k) {
+    const float2 a = *reinterpret_cast<const float2*>(acc + k * acc_stride);
+    const float w = fast_exp2(ml[k * ml_stride] - m);
     a0 += a.x * w;
     a1 += a.y * w;
   }

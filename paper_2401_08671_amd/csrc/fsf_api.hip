@@ -338,13 +338,24 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   f.min_item_blocks = min_item_blocks;
   int64_t n_dec = 0, n_pre = 0;
   int32_t n_split = 0;
-  for (int32_t s = 0; s < n_seqs; ++s) {
-    int d, t;
-    fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
-                  f.split_blocks, f.min_item_blocks, d, t);
-    n_dec += d;
-    n_pre += t;
-    n_split += d > 1;
+  auto count_work = [&] {
+    n_dec = n_pre = 0;
+    n_split = 0;
+    for (int32_t s = 0; s < n_seqs; ++s) {
+      int d, t;
+      fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
+                    f.split_blocks, f.min_item_blocks, d, t);
+      n_dec += d;
+      n_pre += t;
+      n_split += d > 1;
+    }
+  };
+  count_work();
+  // A pass with so few generation rows that not even every compute unit gets a wave (one
+  // long sequence alone, say) is bound by the latency of its longest unit: cut four times finer.
+  if (n_dec * cfg->n_kv_heads < compute_units() && !getenv("FSF_DECODE_MIN_ITEM_BLOCKS")) {
+    f.min_item_blocks = std::max(1, min_item_blocks / 4);
+    count_work();
   }
   if (n_dec > (int64_t)n_seqs + fsf::kMaxDecodeItemsExtra) return FSF_ERR_WORKSPACE;  // cannot happen
   f.n_dec_items = (int32_t)n_dec;
