@@ -22,11 +22,26 @@ namespace {
 
 constexpr int kPlanThreads = 1024;
 
+// Inclusive prefix sum over the workgroup's kPlanThreads values (one per thread): shuffles inside
+// each wave, then the 16 wave totals through LDS.  `totals` holds one int per wave.
+__device__ __forceinline__ int block_inclusive_scan(int v, int* totals) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int a = __shfl_up(v, off);
+    if (lane >= off) v += a;
+  }
+  __syncthreads();  // totals may still be read from the previous scan
+  if (lane == 63) totals[wave] = v;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += totals[w];
+  return v + before;
+}
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) {
-  __shared__ int s_dec[kPlanThreads];
-  __shared__ int s_pre[kPlanThreads];
-  __shared__ int s_spl[kPlanThreads];
   __shared__ int s_bucket[kPlanThreads];  // decode items per block count, largest count first
+  __shared__ int s_totals[3][kPlanThreads / 64];
   const int tid = threadIdx.x;
   s_bucket[tid] = 0;
   const int per = (p.n_seqs + kPlanThreads - 1) / kPlanThreads;
@@ -40,25 +55,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
     pre += t;
     spl += d > 1;
   }
-  s_dec[tid] = dec;
-  s_pre[tid] = pre;
-  s_spl[tid] = spl;
-  __syncthreads();
-  // inclusive scan over the per-thread sums
-  for (int off = 1; off < kPlanThreads; off <<= 1) {
-    int a = 0, b = 0, c = 0;
-    if (tid >= off) {
-      a = s_dec[tid - off];
-      b = s_pre[tid - off];
-      c = s_spl[tid - off];
-    }
-    __syncthreads();
-    s_dec[tid] += a;
-    s_pre[tid] += b;
-    s_spl[tid] += c;
-    __syncthreads();
-  }
-  int dec_run = s_dec[tid] - dec, pre_run = s_pre[tid] - pre, spl_run = s_spl[tid] - spl;  // exclusive
+  // inclusive scans over the per-thread sums
+  const int dec_incl = block_inclusive_scan(dec, s_totals[0]);
+  const int pre_incl = block_inclusive_scan(pre, s_totals[1]);
+  const int spl_incl = block_inclusive_scan(spl, s_totals[2]);
+  int dec_run = dec_incl - dec, pre_run = pre_incl - pre, spl_run = spl_incl - spl;  // exclusive
   for (int s = s0; s < s1; ++s) {
     f.dec_item_start[s] = dec_run;
     f.pre_tile_start[s] = pre_run;
@@ -71,8 +72,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
     pre_run += t;
   }
   if (tid == kPlanThreads - 1) {
-    f.dec_item_start[p.n_seqs] = s_dec[tid];
-    f.pre_tile_start[p.n_seqs] = s_pre[tid];
+    f.dec_item_start[p.n_seqs] = dec_incl;
+    f.pre_tile_start[p.n_seqs] = pre_incl;
   }
   // ---- launch order of the decode items: counting sort, most blocks first
   auto bucket_of = [&](int s, int d) {  // all d items of a sequence hold about nblk / d blocks
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
     return kPlanThreads - 1 - min(per_item, kPlanThreads - 1);
   };
   __syncthreads();  // s_bucket zeroed by every thread above
-  dec_run = s_dec[tid] - dec;
+  dec_run = dec_incl - dec;
   for (int s = s0; s < s1; ++s) {
     int d, t;
     seq_work(p.descs[s].n_new, p.descs[s].n_cached, p.window, p.block_size, f.split_blocks, f.min_item_blocks, d, t);
@@ -90,16 +91,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
   }
   __syncthreads();
   const int mine = s_bucket[tid];
-  __syncthreads();
-  for (int off = 1; off < kPlanThreads; off <<= 1) {  // inclusive scan over the buckets
-    const int a = tid >= off ? s_bucket[tid - off] : 0;
-    __syncthreads();
-    s_bucket[tid] += a;
-    __syncthreads();
-  }
-  const int start = s_bucket[tid] - mine;
-  __syncthreads();
-  s_bucket[tid] = start;  // next free launch slot of the bucket
+  const int start = block_inclusive_scan(mine, s_totals[0]) - mine;  // scan over the buckets
+  s_bucket[tid] = start;  // next free launch slot of the bucket (every thread touches its own entry only)
   __syncthreads();
   for (int s = s0; s < s1; ++s) {
     int d, t;
