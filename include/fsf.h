@@ -155,7 +155,8 @@ size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_s
  * (about how many generation-row wave units a pass is at least cut into, default 4096) and
  * FSF_DECODE_MIN_ITEM_BLOCKS (no KV split leaves fewer cache blocks than this per unit,
  * default 16, or 1024 tokens' worth for blocks below 64 tokens, a quarter of that in passes
- * with fewer wave units than compute units); FSF_PREFILL_NO_SPLIT (set:
+ * with fewer wave units than compute units); FSF_DECODE_NO_HOLD (set: generation-row results
+ * are stored as every unit finishes instead of at the end of its wave); FSF_PREFILL_NO_SPLIT (set:
  * prompt-chunk tiles are never split along their keys) and FSF_PREFILL_SPLIT_UNITS (the
  * number of compute units the split rule assumes, default the device's).
  * Fast paths: bf16/f16 with head_dim 128 and block_size 16 * 2^k; every other

@@ -17,10 +17,11 @@
 //                                              A = V^T is built in-lane: the lane loads the
 //                                              same 8 d-columns (16 B) of its 8 keys and
 //                                              transposes 8x8 with byte permutes.
-// Results leave through a small LDS staging area, so that every store instruction writes whole
-// contiguous rows (in the accumulator layout a lane's 16 bytes sit 64 bytes apart), with
-// non-temporal stores: output writes cost this streaming kernel many times their bytes (with 8
-// query heads per KV head about 7 % of its time), and this form costs least.
+// Results leave through LDS, so that every store instruction writes whole contiguous rows (in
+// the accumulator layout a lane's 16 bytes sit 64 bytes apart), with non-temporal stores, and
+// a wave that walks several units keeps their rows there until it is done: writes sprinkled into
+// the saturated read stream cost this kernel many times their bytes (with 8 query heads per KV
+// head about 7 % of its time).
 // Loads for the next step are issued before the current step is computed (two register
 // buffers).  Rows outside [lo, hi] are masked with selects, never multiplied: stale or
 // poisoned cache slots cannot leak; V rows of masked keys are zeroed.
@@ -143,13 +144,27 @@ __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f
 
 constexpr int kDecodeStageBytes = 16 * kHeadDim * 4;  // per wave: 16 heads x 128 floats
 
+typedef __attribute__((address_space(3))) char decode_lds_char;
+
+// n_bytes of finished rows from LDS to global memory, 16 bytes per lane, consecutive lanes to
+// consecutive addresses, non-temporal
+__device__ __forceinline__ void store_rows(char* dst, decode_lds_char* src, int n_bytes, int lane) {
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) u4 lds_u4;
+  for (int off = lane * 16; off < n_bytes; off += 1024)
+    __builtin_nontemporal_store(*reinterpret_cast<lds_u4*>(src + off), reinterpret_cast<u4*>(dst + off));
+}
+
 // One wavefront: unit = item * n_kv_heads + kv head (item = a sequence's run of cache blocks).
-// stage: kDecodeStageBytes of LDS that belong to this wave alone.
+// stage: kDecodeStageBytes of LDS that belong to this wave alone.  hold: if not null, the
+// finished rows of an unsplit unit (g heads x 256 bytes) are left there instead of being
+// stored, and the byte offset in `out` where they belong is returned for the caller to store
+// them later; otherwise, and for units that write partial results, -1.
 template <int DT, typename T, bool kBlock16, bool kDouble = true>
-__device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
-                                            const T* __restrict__ kc, const T* __restrict__ vc,
-                                            T* __restrict__ out, int unit, int lane,
-                                            __attribute__((address_space(3))) char* stage) {
+__device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
+                                               const T* __restrict__ kc, const T* __restrict__ vc,
+                                               T* __restrict__ out, int unit, int lane,
+                                               decode_lds_char* stage, decode_lds_char* hold) {
   const int n = lane & 15, kg = lane >> 4;
   const int slot = unit / p.n_kv_heads;  // launch order: items with the most cache blocks first
   const int hk = unit - slot * p.n_kv_heads;
@@ -231,6 +246,7 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
   typedef __attribute__((address_space(3))) stage_u4 lds_u4;
   typedef __attribute__((address_space(3))) stage_f4 lds_f4;
   if (n_splits == 1) {
+    decode_lds_char* rows = hold ? hold : stage;
     if (col_live) {
       const float inv = 1.f / l;
 #pragma unroll
@@ -240,17 +256,13 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
         w.y = Mma<DT>::pack2(acc[2][r] * inv, acc[3][r] * inv);
         w.z = Mma<DT>::pack2(acc[4][r] * inv, acc[5][r] * inv);
         w.w = Mma<DT>::pack2(acc[6][r] * inv, acc[7][r] * inv);
-        *reinterpret_cast<lds_u4*>(stage + n * (kHeadDim * 2) + (4 * kg + r) * 16) = w;
+        *reinterpret_cast<lds_u4*>(rows + n * (kHeadDim * 2) + (4 * kg + r) * 16) = w;
       }
     }
     __builtin_amdgcn_wave_barrier();  // one wave: its LDS accesses complete in program order
-    char* obase = reinterpret_cast<char*>(out + ((int64_t)sd.q_offset * p.n_q_heads + hk * g) * kHeadDim);
-    const int n_bytes = g * kHeadDim * 2;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {  // 1 KB = 4 heads per instruction
-      const int off = j * 1024 + lane * 16;
-      if (off < n_bytes) __builtin_nontemporal_store(*reinterpret_cast<lds_u4*>(stage + off), reinterpret_cast<stage_u4*>(obase + off));
-    }
+    const int64_t dst = ((int64_t)sd.q_offset * p.n_q_heads + hk * g) * kHeadDim * (int64_t)sizeof(T);
+    if (hold) return dst;
+    store_rows(reinterpret_cast<char*>(out) + dst, rows, g * kHeadDim * 2, lane);
   } else {
     const int64_t pi = (int64_t)item * p.n_q_heads + hq;
     if (col_live) {
@@ -275,6 +287,7 @@ __device__ __forceinline__ void decode_unit(const Pass& p, const FastPlan& f, co
       if (off < n_bytes) __builtin_nontemporal_store(*reinterpret_cast<lds_f4*>(stage + off), reinterpret_cast<stage_f4*>(pbase + off));
     }
   }
+  return -1;
 }
 
 

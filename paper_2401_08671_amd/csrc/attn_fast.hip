@@ -58,14 +58,46 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastP
 
 // One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
 // which measured best on the short-sequence batches.
+// hold_slots == 0: one unit per workgroup, results stored at once.  hold_slots > 0: the grid
+// is one round of resident waves, every wave walks its share of the units (in launch order,
+// back and forth over the rounds so that every wave gets long and short ones) and keeps the
+// finished rows of up to hold_slots units in LDS; they are stored when the wave is done (or the
+// slots are full).  The rows' writes then come at the end of the kernel, when the reads thin
+// out, instead of being sprinkled into the read stream, where they cost several times their bytes.
 template <int DT, typename T, bool kBlock16>
 __global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
                                                                 const T* __restrict__ q,
                                                                 const T* __restrict__ kc,
                                                                 const T* __restrict__ vc,
-                                                                T* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) char stage[kDecodeStageBytes];
-  decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x, (lds_char*)stage);
+                                                                T* __restrict__ out, int hold_slots) {
+  extern __shared__ __attribute__((aligned(16))) char decode_lds[];
+  lds_char* stage = (lds_char*)decode_lds;
+  if (hold_slots == 0) {
+    decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x, stage, nullptr);
+    return;
+  }
+  const int row_bytes = p.group * kHeadDim * (int)sizeof(T);
+  lds_char* hold = stage + kDecodeStageBytes;
+  auto* dst = reinterpret_cast<__attribute__((address_space(3))) int64_t*>(hold + hold_slots * row_bytes);
+  const int n_units = f.n_dec_items * p.n_kv_heads;
+  const int G = gridDim.x, lane = threadIdx.x;
+  int held = 0;
+  auto flush = [&] {
+    for (int s = 0; s < held; ++s) store_rows(reinterpret_cast<char*>(out) + dst[s], hold + s * row_bytes, row_bytes, lane);
+    held = 0;
+  };
+  for (int round = 0; round * G < n_units; ++round) {
+    const int unit = round * G + ((round & 1) ? G - 1 - (int)blockIdx.x : (int)blockIdx.x);
+    if (unit >= n_units) continue;
+    const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, unit, lane, stage, hold + held * row_bytes);
+    if (d >= 0) {  // the same in every lane
+      if (lane == 0) dst[held] = d;
+      ++held;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (held == hold_slots) flush();
+  }
+  flush();
 }
 
 template <int DT, typename T>
@@ -95,8 +127,19 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
     if (unit >= f.n_dec_items * p.n_kv_heads) return;
     // (the host launches this kernel for blocks of 32 tokens or more only)
     decode_unit<DT, T, false>(p, f, q, kc, vc, out, unit, threadIdx.x & 63,
-                              (lds_char*)lds + (threadIdx.x >> 6) * kDecodeStageBytes);
+                              (lds_char*)lds + (threadIdx.x >> 6) * kDecodeStageBytes, nullptr);
   }
+}
+
+int decode_compute_units() {
+  static int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
+      cu = 256;
+    return cu;
+  }();
+  return n;
 }
 
 unsigned decode_groups(const Pass& p, const FastPlan& f) {
@@ -127,10 +170,22 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
                               const void* v_cache, void* out, hipStream_t stream) {
   if (f.n_dec_items == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_DECODE, stream);
-  const unsigned grid = (unsigned)f.n_dec_items * p.n_kv_heads;
+  const unsigned n_units = (unsigned)f.n_dec_items * p.n_kv_heads;
+  // With more units than wave slots (two waves per SIMD): one round of waves that hold their
+  // results back.  LDS per wave: the staging area, up to 10 KB of finished rows, their addresses.
+  unsigned grid = n_units;
+  int hold_slots = 0;
+  const unsigned slots = 8u * (unsigned)decode_compute_units();
+  const int row_bytes = p.group * kHeadDim * 2;
+  if (n_units > slots && !getenv("FSF_DECODE_NO_HOLD")) {
+    grid = slots;
+    const int per_wave = (int)((n_units + slots - 1) / slots);
+    hold_slots = std::min(per_wave, (10 * 1024) / row_bytes);
+  }
+  const size_t lds_bytes = kDecodeStageBytes + (size_t)hold_slots * (row_bytes + 8);
 #define FSF_DECODE(DT, T, B16)                 \
-  attn_decode_kernel<DT, T, B16><<<grid, 64, 0, stream>>>(p, f, (const T*)q, (const T*)k_cache, \
-                                                          (const T*)v_cache, (T*)out)
+  attn_decode_kernel<DT, T, B16><<<grid, 64, lds_bytes, stream>>>(p, f, (const T*)q, (const T*)k_cache, \
+                                                                  (const T*)v_cache, (T*)out, hold_slots)
   const bool b16 = p.block_size == 16;
   if (p.dtype == FSF_BF16) {
     if (b16) FSF_DECODE(FSF_BF16, bf16_t, true); else FSF_DECODE(FSF_BF16, bf16_t, false);
