@@ -161,8 +161,9 @@ def test_prefill_tiles_split_along_keys(prefill_split_env, units, window, dtype)
     check_step(Step(spec, poison="nan"), f"prefill split units={units} window={window} {dtype}")
 
 
-@pytest.mark.parametrize("heads,n_rows", [((16, 1), 5000), ((8, 4), 1300), ((4, 4), 700)])
-def test_more_generation_row_units_than_wave_slots(heads, n_rows):
+@pytest.mark.parametrize("heads,n_rows,block,dtype", [((16, 1), 5000, 64, "bf16"), ((8, 4), 1300, 64, "bf16"),
+                                                      ((4, 4), 700, 64, "bf16"), ((8, 4), 1300, 16, "f16")])
+def test_more_generation_row_units_than_wave_slots(heads, n_rows, block, dtype):
     """With more units than resident waves the generation-row kernel runs as one round of waves
     that walk several units each and hold their results in LDS until the end: 16 heads per KV head
     leave room for two held units (stored whenever both slots are full), 2 heads for all of them;
@@ -171,8 +172,8 @@ def test_more_generation_row_units_than_wave_slots(heads, n_rows):
     rng = np.random.default_rng(36)
     seqs = [(1, int(c)) for c in rng.integers(0, 200, size=n_rows)]
     seqs[7] = (1, 5000)                       # one long row: cut into units with partial results
-    spec = wl.BatchSpec("manyunits", Hq, Hkv, 128, 64, "bf16", seqs, seed=36)
-    check_step(Step(spec, poison="nan"), f"{n_rows} rows, heads {heads}")
+    spec = wl.BatchSpec("manyunits", Hq, Hkv, 128, block, dtype, seqs, seed=36)
+    check_step(Step(spec, poison="nan"), f"{n_rows} rows, heads {heads}, block {block}, {dtype}")
 
 
 @pytest.mark.parametrize("window", [0, 5000])
