@@ -176,6 +176,15 @@ def test_more_generation_row_units_than_wave_slots(heads, n_rows, block, dtype):
     check_step(Step(spec, poison="nan"), f"{n_rows} rows, heads {heads}, block {block}, {dtype}")
 
 
+def test_fifty_thousand_sequences():
+    """A pass of 50 000 short generation rows and two chunks: the planning kernel's prefix sums and
+    counting sort over many sequences per thread, 100 000 units for 2048 wave slots."""
+    rng = np.random.default_rng(5)
+    seqs = [(1, int(c)) for c in rng.integers(0, 16, size=50000)] + [(40, 3), (300, 0)]
+    spec = wl.BatchSpec("many", 2, 2, 128, 16, "bf16", seqs, seed=9)
+    check_step(Step(spec, poison="nan"), "50000 sequences")
+
+
 @pytest.mark.parametrize("window", [0, 5000])
 def test_very_long_contexts(window):
     """A generation row over 200 000 cached tokens (cut into many units and merged) and a 300-row
