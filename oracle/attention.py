@@ -142,6 +142,18 @@ def kv_append_rotary(k_cache, v_cache, k_new, v_new, descs, block_tables, block_
             v_cache[blk, :, slot, :] = v_new[q_off + i]
 
 
+def rotate_queries(q, descs, cos_sin: np.ndarray, dtype: str) -> np.ndarray:
+    """The pass's query rows ``[T, Hq, d]`` rotated like the keys (:func:`rotate_row`): row ``i`` of
+    sequence ``s`` by the angles of its position ``n_cached + i``.  Returns a new array."""
+    descs = np.asarray(descs)
+    out = np.empty_like(q)
+    for s in range(descs.shape[0]):
+        n_new, n_cached, q_off = int(descs[s, DESC_N_NEW]), int(descs[s, DESC_N_CACHED]), int(descs[s, DESC_Q_OFFSET])
+        for i in range(n_new):
+            out[q_off + i] = rotate_row(q[q_off + i], cos_sin[n_cached + i], dtype)
+    return out
+
+
 def gather_history(cache, block_table_row, n_tokens: int, block_size: int) -> np.ndarray:
     """Logical history ``[n_tokens, Hkv, d]`` of one sequence, in position order."""
     n_heads, d = cache.shape[1], cache.shape[3]

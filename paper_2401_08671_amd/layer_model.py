@@ -9,7 +9,13 @@ the linear part instead of a model, this module times the layer's GEMMs (QKV, ou
 gated MLP) with random bf16 weights of a Llama-2-13B-shaped layer through the vendor GEMM library
 (torch.matmul: hipBLASLt) for a grid of token counts.  Nothing here is part of the attention path.
 
-    python -m paper_2401_08671_amd.layer_model        # prints one JSON object
+`measure_layer` runs a whole layer of a Dynamic SplitFuse pass in order: the three projections,
+the rotation of Q (torch) and of K (fused into this library's append), the ragged attention, the
+output projection and the gated MLP, for a grid of token budgets; the budget's tokens are a fixed
+number of generation rows plus one prompt chunk that fills the rest (Sec. 3.2).
+
+    python -m paper_2401_08671_amd.layer_model            # the GEMMs alone; prints one JSON object
+    python -m paper_2401_08671_amd.layer_model --layer    # the whole layer with attention
 """
 from __future__ import annotations
 
@@ -61,6 +67,63 @@ def measure_linear(shape=SHAPE_13B, grid=TOKEN_GRID, reps: int = 5, device="cuda
     return out
 
 
+def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations: int = 64, context: int = 2048,
+                  shape=SHAPE_13B, reps: int = 5, device="cuda"):
+    """One Llama-2-13B-shaped layer of a SplitFuse pass per token budget: n_generations generation
+    rows over `context` cached tokens plus one chunk of the remaining tokens of a prompt that has
+    `context` tokens cached already.  Returns rows of dict(budget, layer_ms, gemm_ms, attention_ms)."""
+    import numpy as np
+
+    from . import fsf
+    from . import workloads as wl
+    from .harness import DeviceStep
+    h, H, d, mlp = shape["hidden"], shape["n_heads"], shape["head_dim"], shape["mlp"]
+    g = torch.Generator(device=device).manual_seed(5)
+    mk = lambda *s: (torch.randn(*s, generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    layers = [dict(wq=mk(h, h), wk=mk(h, h), wv=mk(h, h), wo=mk(h, h), wgu=mk(h, 2 * mlp), wd=mk(mlp, h)) for _ in range(3)]
+    n_pos = context + max(budgets) + 1
+    inv = 10000.0 ** (-torch.arange(0, d // 2, dtype=torch.float64, device=device) * 2.0 / d)
+    ang = torch.arange(n_pos, dtype=torch.float64, device=device)[:, None] * inv[None, :]
+    cos_sin = torch.stack([ang.cos(), ang.sin()], dim=-1).to(torch.float32).contiguous()
+    rows = []
+    for T in budgets:
+        n_dec = min(n_generations, T // 2)
+        spec = wl.BatchSpec(f"layer-{T}", H, H, d, 64, "bf16", [(1, context)] * n_dec + [(T - n_dec, context)], seed=7)
+        ds = DeviceStep(spec)
+        pos = torch.from_numpy(np.concatenate([np.arange(c, c + n) for n, c in spec.seqs])).to(device)
+        cs_q = cos_sin[pos]                                   # [T, d/2, 2]
+        x = mk(T, h)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        best = None
+        for r in range(reps + 2):
+            w = layers[r % 3]
+            ev[0].record()
+            q = (x @ w["wq"]).view(T, H, d)
+            k = (x @ w["wk"]).view(T, H, d)
+            v = (x @ w["wv"]).view(T, H, d)
+            qf = q.float()
+            a, b = qf[..., : d // 2], qf[..., d // 2:]
+            c, s = cs_q[:, None, :, 0], cs_q[:, None, :, 1]
+            q = torch.cat([a * c - b * s, b * c + a * s], dim=-1).to(torch.bfloat16)
+            ev[1].record()
+            fsf.kv_append_rotary(ds.cfg, k, v, ds.k_cache, ds.v_cache, ds.batch, cos_sin)
+            fsf.ragged_attention(ds.cfg, q, ds.k_cache, ds.v_cache, ds.batch, ds.out, ds.ws)
+            ev[2].record()
+            o = ds.out.view(T, h) @ w["wo"]
+            gu = o @ w["wgu"]
+            y = (torch.nn.functional.silu(gu[:, :mlp]) * gu[:, mlp:]) @ w["wd"]
+            ev[3].record()
+            torch.cuda.synchronize()
+            t = [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
+            if r >= 2 and (best is None or sum(t) < sum(best)):
+                best = t
+        del ds, y, gu, o, q, k, v
+        rows.append(dict(budget=T, generation_rows=n_dec, chunk_rows=T - n_dec, layer_ms=sum(best),
+                         gemm_ms=best[0] + best[2], attention_ms=best[1],
+                         tokens_per_s_whole_model=T / (sum(best) * 1e-3 * shape["n_layers"])))
+    return rows
+
+
 class MeasuredLinear:
     """seconds of the linear part of a pass of n tokens: table of measure_linear, interpolated"""
 
@@ -83,6 +146,10 @@ class MeasuredLinear:
 
 def main():
     assert torch.cuda.is_available(), "needs a GPU"
+    if "--layer" in sys.argv[1:]:
+        json.dump(dict(shape=SHAPE_13B, rows=measure_layer()), sys.stdout)
+        print()
+        return
     table = measure_linear()
     fl, by = layer_gemm_flops(), layer_weight_bytes()
     rows = [dict(tokens=T, layer_ms=s * 1e3, tflops=T * fl / s / 1e12, weight_gbs=by / s / 1e9,

@@ -368,3 +368,25 @@ def test_rotary_append_touches_k_only_and_only_addressed_slots():
         for slot in range(B):
             if (blk, slot) not in touched:
                 assert np.all(k_cache[blk, :, slot] == 7) and np.all(v_cache[blk, :, slot] == 9)
+
+
+def test_rotated_queries_and_keys_score_by_distance_only():
+    """End to end through the two rotating functions: with the same content in every row, the score
+    of query row i of a chunk against the key at cache position j depends on (n_cached + i) - j
+    only - which pins the position each query row is rotated by to n_cached + i."""
+    d, B = 64, 4
+    rng = np.random.default_rng(3)
+    q_row = rng.standard_normal((1, d)).astype(np.float32)
+    k_row = rng.standard_normal((1, d)).astype(np.float32)
+    table = oa.rotary_table(64, d)
+    descs = np.array([[5, 7, 0, 0], [3, 20, 5, 1]], np.int32)        # positions 7..11 and 20..22
+    q = np.repeat(q_row[None], 8, axis=0)                              # [T=8, 1, d]
+    qr = oa.rotate_queries(q, descs, table, "f32")
+    keys = np.stack([oa.rotate_row(k_row, table[j], "f32") for j in range(23)])     # key content at every position
+    score = lambda t, j: float(qr[t, 0].astype(np.float64) @ keys[j, 0].astype(np.float64))
+    pos = [7, 8, 9, 10, 11, 20, 21, 22]
+    for dist in (0, 1, 5):
+        vals = [score(t, pos[t] - dist) for t in range(8)]
+        assert np.allclose(vals, vals[0], rtol=0, atol=2e-4), (dist, vals)
+    assert abs(score(0, 7) - score(0, 6)) > 1e-3                       # and it does depend on the distance
+    assert np.array_equal(oa.rotate_queries(q[:1], np.array([[1, 0, 0, 0]], np.int32), table, "f32"), q[:1])  # position 0
