@@ -123,6 +123,18 @@ int fsf_kv_append_rotary(const fsf_attn_cfg* cfg, const void* k_new, const void*
                          void* hip_stream);
 
 /*
+ * The rotation of fsf_kv_append_rotary applied in place to the pass's query rows
+ * (device, [n_tokens, n_q_heads, d]): row i of a sequence by the angles of position
+ * n_cached + i, the position its key is stored at; same pairing, same fixed arithmetic, same
+ * table.  Scores of rotated queries against rotated keys then depend on the distance between
+ * the two positions only (the property the Llama family's attention relies on, paper Sec. 4.1).
+ * Errors as fsf_kv_append_rotary (block tables are not needed).
+ */
+int fsf_rotary_q(const fsf_attn_cfg* cfg, void* q, const fsf_seq_desc* descs_dev,
+                 const fsf_seq_desc* descs_host, int32_t n_seqs, int32_t n_tokens,
+                 const float* cos_sin_dev, int32_t table_positions, void* hip_stream);
+
+/*
  * Bytes of device workspace fsf_ragged_attention needs for a pass of at most n_seqs
  * sequences, n_tokens tokens and max_blocks table columns.  Never zero (a small plan
  * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.  On the

@@ -273,6 +273,21 @@ extern "C" int fsf_kv_append_rotary(const fsf_attn_cfg* cfg, const void* k_new, 
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }
 
+extern "C" int fsf_rotary_q(const fsf_attn_cfg* cfg, void* q, const fsf_seq_desc* descs_dev,
+                            const fsf_seq_desc* descs_host, int32_t n_seqs, int32_t n_tokens,
+                            const float* cos_sin_dev, int32_t table_positions, void* hip_stream) {
+  if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || table_positions < 0) return FSF_ERR_INVALID_ARG;
+  if (n_seqs == 0 || n_tokens == 0) return FSF_OK;
+  if (!q || !descs_dev || !descs_host || !cos_sin_dev) return FSF_ERR_INVALID_ARG;
+  if (cfg->head_dim % 2) return FSF_ERR_UNSUPPORTED;
+  if (!descs_ok(cfg, descs_host, n_seqs, INT32_MAX, n_tokens)) return FSF_ERR_INVALID_ARG;
+  for (int32_t s = 0; s < n_seqs; ++s)
+    if ((int64_t)descs_host[s].n_cached + descs_host[s].n_new > table_positions) return FSF_ERR_INVALID_ARG;
+  const Pass p = make_pass(cfg, descs_dev, nullptr, n_seqs, 1, n_tokens);
+  const hipError_t e = fsf::launch_rotary_q(p, q, cos_sin_dev, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+}
+
 extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_seqs,
                                                        int32_t n_tokens, int32_t max_blocks) {
   if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return 0;

@@ -233,6 +233,7 @@ hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new,
                             void* v_cache, hipStream_t stream);
 hipError_t launch_kv_append_rotary(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
                                    void* v_cache, const float* cos_sin, hipStream_t stream);
+hipError_t launch_rotary_q(const Pass& p, void* q, const float* cos_sin, hipStream_t stream);
 
 hipError_t launch_attn_generic(const Pass& p, const void* q, const void* k_cache,
                                const void* v_cache, void* out, hipStream_t stream);

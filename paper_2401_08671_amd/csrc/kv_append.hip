@@ -84,7 +84,43 @@ __global__ __launch_bounds__(256) void kv_append_rotary_kernel(Pass p, const T* 
   }
 }
 
+// The same rotation applied in place to the query rows [T, n_q_heads, d]: one workgroup per
+// token, a thread per (head, pair).
+template <typename T>
+__global__ __launch_bounds__(256) void rotary_q_kernel(Pass p, T* __restrict__ q, const float2* __restrict__ cos_sin) {
+#pragma clang fp contract(off)
+  const int t = blockIdx.x;
+  const int s = find_seq(p.descs, p.n_seqs, t);
+  const fsf_seq_desc d = p.descs[s];
+  const int pos = d.n_cached + (t - d.q_offset);
+  const int half = p.head_dim / 2;
+  const float2* cs = cos_sin + (int64_t)pos * half;
+  T* row = q + (int64_t)t * p.n_q_heads * p.head_dim;
+  for (int u = threadIdx.x; u < p.n_q_heads * half; u += blockDim.x) {
+    const int h = u / half;
+    const int i = u - h * half;
+    T* x = row + h * p.head_dim + i;
+    const float a = to_float(x[0]), b = to_float(x[half]);
+    const float2 c = cs[i];
+    const float ac = a * c.x, bs = b * c.y, bc = b * c.x, as = a * c.y;
+    x[0] = from_float<T>(ac - bs);
+    x[half] = from_float<T>(bc + as);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_rotary_q(const Pass& p, void* q, const float* cos_sin, hipStream_t stream) {
+  if (p.n_tokens == 0 || p.n_seqs == 0) return hipSuccess;
+  const float2* cs = reinterpret_cast<const float2*>(cos_sin);
+  if (p.dtype == FSF_F32)
+    rotary_q_kernel<float><<<p.n_tokens, 256, 0, stream>>>(p, (float*)q, cs);
+  else if (p.dtype == FSF_BF16)
+    rotary_q_kernel<bf16_t><<<p.n_tokens, 256, 0, stream>>>(p, (bf16_t*)q, cs);
+  else
+    rotary_q_kernel<f16_t><<<p.n_tokens, 256, 0, stream>>>(p, (f16_t*)q, cs);
+  return hipGetLastError();
+}
 
 hipError_t launch_kv_append_rotary(const Pass& p, const void* k_new, const void* v_new, void* k_cache,
                                    void* v_cache, const float* cos_sin, hipStream_t stream) {

@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
     L.fsf_kv_append.argtypes = [cfgp, vp, vp, vp, vp, descp, i32p, i32, i32, i32, vp]
     L.fsf_kv_append_rotary.restype = C.c_int
     L.fsf_kv_append_rotary.argtypes = [cfgp, vp, vp, vp, vp, descp, descp, i32p, i32, i32, i32, vp, i32, vp]
+    L.fsf_rotary_q.restype = C.c_int
+    L.fsf_rotary_q.argtypes = [cfgp, vp, descp, descp, i32, i32, vp, i32, vp]
     L.fsf_ragged_attention_workspace_bytes.restype = sz
     L.fsf_ragged_attention_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
     L.fsf_ragged_attention.restype = C.c_int
@@ -143,6 +145,14 @@ def kv_append_rotary(cfg: AttnCfg, k_new, v_new, k_cache, v_cache, batch: Device
                                     _ptr(batch.bt_dev), batch.n_seqs, batch.max_blocks, batch.n_tokens,
                                     _ptr(cos_sin), cos_sin.shape[0], _stream())
     _check(st, "fsf_kv_append_rotary")
+
+
+def rotary_q(cfg: AttnCfg, q, batch: DeviceBatch, cos_sin) -> None:
+    """fsf_rotary_q on torch's current stream: q is rotated in place."""
+    assert cos_sin.dtype == torch.float32 and cos_sin.is_contiguous() and cos_sin.shape[1] * 2 == cfg.head_dim
+    st = lib().fsf_rotary_q(C.byref(cfg), _ptr(q), _ptr(batch.descs_dev), C.c_void_p(batch.descs_host.ctypes.data),
+                            batch.n_seqs, batch.n_tokens, _ptr(cos_sin), cos_sin.shape[0], _stream())
+    _check(st, "fsf_rotary_q")
 
 
 def ragged_attention_workspace_bytes(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int) -> int:

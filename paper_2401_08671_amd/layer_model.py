@@ -10,7 +10,7 @@ gated MLP) with random bf16 weights of a Llama-2-13B-shaped layer through the ve
 (torch.matmul: hipBLASLt) for a grid of token counts.  Nothing here is part of the attention path.
 
 `measure_layer` runs a whole layer of a Dynamic SplitFuse pass in order: the three projections,
-the rotation of Q (torch) and of K (fused into this library's append), the ragged attention, the
+the rotation of Q and of K (this library: in place, and fused into the append), the ragged attention, the
 output projection and the gated MLP, for a grid of token budgets; the budget's tokens are a fixed
 number of generation rows plus one prompt chunk that fills the rest (Sec. 3.2).
 
@@ -72,8 +72,6 @@ def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations
     """One Llama-2-13B-shaped layer of a SplitFuse pass per token budget: n_generations generation
     rows over `context` cached tokens plus one chunk of the remaining tokens of a prompt that has
     `context` tokens cached already.  Returns rows of dict(budget, layer_ms, gemm_ms, attention_ms)."""
-    import numpy as np
-
     from . import fsf
     from . import workloads as wl
     from .harness import DeviceStep
@@ -90,8 +88,6 @@ def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations
         n_dec = min(n_generations, T // 2)
         spec = wl.BatchSpec(f"layer-{T}", H, H, d, 64, "bf16", [(1, context)] * n_dec + [(T - n_dec, context)], seed=7)
         ds = DeviceStep(spec)
-        pos = torch.from_numpy(np.concatenate([np.arange(c, c + n) for n, c in spec.seqs])).to(device)
-        cs_q = cos_sin[pos]                                   # [T, d/2, 2]
         x = mk(T, h)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         best = None
@@ -101,11 +97,8 @@ def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations
             q = (x @ w["wq"]).view(T, H, d)
             k = (x @ w["wk"]).view(T, H, d)
             v = (x @ w["wv"]).view(T, H, d)
-            qf = q.float()
-            a, b = qf[..., : d // 2], qf[..., d // 2:]
-            c, s = cs_q[:, None, :, 0], cs_q[:, None, :, 1]
-            q = torch.cat([a * c - b * s, b * c + a * s], dim=-1).to(torch.bfloat16)
             ev[1].record()
+            fsf.rotary_q(ds.cfg, q, ds.batch, cos_sin)
             fsf.kv_append_rotary(ds.cfg, k, v, ds.k_cache, ds.v_cache, ds.batch, cos_sin)
             fsf.ragged_attention(ds.cfg, q, ds.k_cache, ds.v_cache, ds.batch, ds.out, ds.ws)
             ev[2].record()

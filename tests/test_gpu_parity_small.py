@@ -177,6 +177,22 @@ def test_rotary_append_is_bit_exact(dtype, shape):
     assert_cache_bit_exact(vc_h, vc_o, f"rotary V {dtype} {shape[:4]}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_rotary_q_is_bit_exact(dtype):
+    spec = wl.BatchSpec("rotq", 6, 3, 128 if dtype != "f32" else 80, 16, dtype, [(40, 100), (1, 0), (1, 511), (7, 3)], seed=93)
+    st = Step(spec)
+    table = oa.rotary_table(512, spec.head_dim)
+    want = oa.rotate_queries(st.q, st.descs, table, dtype)
+    cfg = fsf.make_cfg(spec.n_q_heads, spec.n_kv_heads, spec.head_dim, 16, dtype, st.num_blocks)
+    batch = fsf.DeviceBatch(st.descs, st.block_tables, "cuda")
+    q = wl.from_numpy_storage(st.q, dtype, "cuda")
+    fsf.rotary_q(cfg, q, batch, torch.from_numpy(table).cuda())
+    torch.cuda.synchronize()
+    assert_cache_bit_exact(wl.to_numpy_storage(q), want, f"rotated Q {dtype}")
+    with pytest.raises(fsf.FsfError):
+        fsf.rotary_q(cfg, q, batch, torch.from_numpy(oa.rotary_table(512 - 1, spec.head_dim)).cuda())   # position 511 missing
+
+
 def test_rotary_append_then_attention_matches_the_oracle():
     spec = wl.BatchSpec("rot-attn", 8, 2, 128, 64, "bf16", [(257, 0), (1, 190), (40, 90)], seed=92)
     st = Step(spec)
