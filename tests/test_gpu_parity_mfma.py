@@ -300,3 +300,30 @@ def test_a_pass_can_be_captured_in_a_graph_and_replayed():
     ref = oa.ragged_attention(wl.to_numpy_storage(ds.q), kc, vc, ds.descs, ds.block_tables, block_size=64,
                               scale=spec.scale, window=0, dtype="bf16")
     assert_outputs_close(eager.to(torch.float64).cpu().numpy(), ref, "bf16", "graph pass")
+
+
+@pytest.mark.parametrize("seed", range(100, 112))
+def test_random_passes_over_block_sizes_groups_and_unit_counts(seed, prefill_split_env, split_env):
+    """Seeded random passes over the whole matrix-core envelope: 1 to 16 query heads per KV head,
+    blocks of 16 to 128 tokens, windows, no to thousands of generation rows (one unit per workgroup,
+    or one round of waves holding their results), forced fine or no cuts of the rows."""
+    rng = np.random.default_rng(seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    Hq = Hkv * int(rng.choice([1, 2, 4, 8, 16]))
+    block = int(rng.choice([16, 32, 64, 128]))
+    window = int(rng.choice([0, 0, 90, 1000]))
+    dtype = "bf16" if seed % 3 else "f16"
+    seqs = []
+    for _ in range(int(rng.integers(0, 4))):
+        seqs.append((int(rng.choice([2, 17, 64, 200, 256, 257, 600])), int(rng.choice([0, 5, 63, 64, 700, 3000]))))
+    n_dec = int(rng.choice([0, 3, 40, 700, 2500]))
+    seqs += [(1, int(c)) for c in rng.integers(0, int(rng.choice([40, 300, 3000])), size=n_dec)]
+    if not seqs:
+        seqs = [(1, 5)]
+    order = rng.permutation(len(seqs))
+    seqs = [seqs[i] for i in order]
+    prefill_split_env(int(rng.choice([4, 16, 64, 256])))
+    if rng.random() < 0.3:
+        split_env(int(rng.choice([64, 100000])), 16)
+    spec = wl.BatchSpec(f"wide{seed}", Hq, Hkv, 128, block, dtype, seqs, window=window, seed=9000 + seed)
+    check_step(Step(spec, poison="nan"), f"seed {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} n_seqs={len(seqs)}")
