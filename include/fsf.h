@@ -60,7 +60,36 @@ typedef enum { FSF_F32 = 0, FSF_BF16 = 1, FSF_F16 = 2 } fsf_dtype;
 /* fsf_attn_cfg.flags */
 #define FSF_FLAG_FORCE_GENERIC 1    /* run the generic fp32 kernel even where a fast path exists     */
 #define FSF_FLAG_FUSED_LAUNCH 2     /* matrix-core path: launch prompt-chunk and generation-row work  */
-                                    /* as one fused grid instead of two kernels                       */
+                                    /* as one fused grid instead of two kernels.  Needs cache blocks  */
+                                    /* of 32 tokens or more (ignored otherwise), and a fused pass     */
+                                    /* never cuts prompt-chunk tiles along their keys                 */
+
+/*
+ * Tuning of fsf_ragged_attention's work partition, passed by value through fsf_attn_cfg.tuning
+ * (NULL: every default).  It is read during the call and may be freed or changed afterwards.  A
+ * field that is 0 takes its default; the defaults suit MI355X.  Results stay within the stated
+ * tolerance for every setting; the partition (and with it the summation order) changes.
+ * struct_bytes = sizeof(fsf_tuning) as the caller compiled it; fields beyond it take defaults.
+ */
+typedef struct {
+  int32_t struct_bytes;
+  int32_t decode_target_waves;     /* about how many streaming wave units a pass is at least cut into   */
+                                   /* (default 4096 = two rounds of the chip's wave slots)              */
+  int32_t decode_min_item_blocks;  /* no cut of a row's keys leaves fewer cache blocks than this per     */
+                                   /* unit (default 16, or 1024 tokens' worth for blocks below 64        */
+                                   /* tokens; a quarter of that in passes with fewer units than compute   */
+                                   /* units, unless set here)                                            */
+  int32_t decode_hold;             /* -1: store every unit's result as it finishes; default (0, 1): with */
+                                   /* more units than wave slots, waves keep finished rows in LDS and     */
+                                   /* store them at the end                                              */
+  int32_t prefill_split;           /* -1: never cut prompt-chunk tiles along their keys; default: cut    */
+                                   /* tiles that would outlast the pass or sit in a half-empty last round */
+  int32_t compute_units;           /* compute units the cutting rules assume (default: the device's)     */
+  int32_t max_decode_items_extra;  /* bounds the workspace: streaming units beyond one per sequence and  */
+                                   /* KV head that may hold partial results (default 8192)               */
+  int32_t max_prefill_split_units; /* bounds the workspace: (tile, head, part) workgroups with partial    */
+                                   /* results, 139 KB each (default 512)                                 */
+} fsf_tuning;
 
 /* One sequence of the pass (paper Sec. 2: tokens processed now vs tokens in the cache). */
 typedef struct {
@@ -80,6 +109,7 @@ typedef struct {
   int32_t dtype;      /* fsf_dtype of q, k_new, v_new, both caches and out                  */
   int32_t flags;      /* 0, or FSF_FLAG_* bits                                              */
   int64_t num_blocks; /* physical blocks in each cache                                      */
+  const fsf_tuning* tuning; /* host; NULL = defaults (see fsf_tuning)                        */
 } fsf_attn_cfg;
 
 const char* fsf_strerror(int status);
@@ -97,11 +127,31 @@ int fsf_version(void);
  *   k_cache, v_cache    device, [num_blocks, n_kv_heads, block_size, d]
  *   descs_dev           device, [n_seqs]
  *   block_tables_dev    device, [n_seqs, max_blocks]
- * n_seqs == 0 or n_tokens == 0 is a no-op.  Requires head_dim * sizeof(element) % 4 == 0.
+ * n_seqs == 0 or n_tokens == 0 is a no-op.  Requires head_dim * sizeof(element) % 4 == 0 and
+ * 4-byte aligned tensors (16-byte aligned ones are copied in 16-byte units).
+ * This call sees only the device copies of the descriptors and block tables and trusts them:
+ * n_tokens must equal the sum of n_new, and every position must have its table entry.  A
+ * caller that cannot vouch for them runs fsf_validate_pass on its host copies first.
  */
 int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new, void* k_cache,
                   void* v_cache, const fsf_seq_desc* descs_dev, const int32_t* block_tables_dev,
                   int32_t n_seqs, int32_t max_blocks, int32_t n_tokens, void* hip_stream);
+
+/*
+ * Host-side check of a pass before it is enqueued (optional; the device calls trust block ids,
+ * because checking them on the device would cost a synchronisation).  Verifies on the host
+ * copies what fsf_ragged_attention verifies (n_new >= 1, n_cached >= 0, q_offsets the running
+ * sum of n_new ending at n_tokens, ceil((n_cached + n_new) / block_size) <= max_blocks) and, for
+ * every table entry the pass will dereference (columns 0 .. ceil((n_cached+n_new)/block_size)-1 of
+ * each row), that 0 <= id < num_blocks and that no block is named twice in the pass (paper
+ * Sec. 2.1: a block belongs to one sequence).  Returns FSF_OK, or FSF_ERR_INVALID_ARG with the
+ * first offending sequence and table column in *bad_seq_out / *bad_column_out (either may be
+ * NULL; -1 where the fault is not tied to one).  O(table entries) time, num_blocks bits of host
+ * memory; no device call.
+ */
+int fsf_validate_pass(const fsf_attn_cfg* cfg, const fsf_seq_desc* descs_host,
+                      const int32_t* block_tables_host, int32_t n_seqs, int32_t max_blocks,
+                      int32_t n_tokens, int32_t* bad_seq_out, int32_t* bad_column_out);
 
 /*
  * As fsf_kv_append, with the rotary position embedding of the served model family (paper
@@ -163,17 +213,14 @@ size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, int32_t n_s
  *                       contents are scratch, not preserved, no initialisation needed
  * Validation (host side): n_new >= 1, n_cached >= 0, q_offsets are the running sum of
  * n_new and end at n_tokens, ceil((n_cached+n_new)/block_size) <= max_blocks.
- * Tuning knobs (environment, read per call; defaults suit MI355X): FSF_DECODE_TARGET_WAVES
- * (about how many generation-row wave units a pass is at least cut into, default 4096) and
- * FSF_DECODE_MIN_ITEM_BLOCKS (no KV split leaves fewer cache blocks than this per unit,
- * default 16, or 1024 tokens' worth for blocks below 64 tokens, a quarter of that in passes
- * with fewer wave units than compute units); FSF_DECODE_NO_HOLD (set: generation-row results
- * are stored as every unit finishes instead of at the end of its wave); FSF_PREFILL_NO_SPLIT (set:
- * prompt-chunk tiles are never split along their keys) and FSF_PREFILL_SPLIT_UNITS (the
- * number of compute units the split rule assumes, default the device's).
- * Fast paths: bf16/f16 with head_dim 128 and block_size 16 * 2^k; every other
- * supported shape (any dtype, head_dim <= 256 and a multiple of 4/sizeof-ratio, any
- * block_size) runs a generic fp32 kernel.
+ * The work partition is tuned through cfg->tuning (fsf_tuning); the library reads no
+ * environment variable.
+ * Fast paths: bf16/f16 with head_dim 128, block_size 16 * 2^k and at most 16 query heads per KV
+ * head; every other supported shape (any dtype, head_dim <= 256 and a multiple of
+ * 4/sizeof-ratio, any block_size) runs a generic fp32 kernel, one wavefront per (row, head)
+ * with scalar dot products: correct, and meant for small or odd shapes only (the 194-token
+ * fp32 example pass takes about 0.1 ms; at benchmark sizes it is two to three orders of
+ * magnitude below either roofline).
  */
 int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
                          const void* v_cache, const fsf_seq_desc* descs_dev,
@@ -267,59 +314,6 @@ int fsf_compose_batch(fsf_sched* s, fsf_seq_desc* descs_out, int32_t* block_tabl
 /* Commit the pending pass: advance n_cached, turn finished prompts into generations,
  * retire sequences that emitted max_new_tokens and free their blocks. */
 int fsf_sched_step_done(fsf_sched* s);
-
-/*
- * Profiling aid (host state, not thread safe; off by default).  While enabled, every
- * kernel the library launches is bracketed by a pair of HIP events on the caller's
- * stream.  fsf_profile_read() waits for the recorded events, adds the elapsed
- * milliseconds and launch counts per phase into ms_out[FSF_N_PHASES] /
- * launches_out[FSF_N_PHASES] (host arrays, overwritten), and clears the record.
- * Events are ordinary host-side HIP objects; no device memory is allocated.
- */
-typedef enum {
-  FSF_PHASE_APPEND = 0,  /* fsf_kv_append kernel                                  */
-  FSF_PHASE_PLAN = 1,    /* work planning (prefix sums over the descriptors)      */
-  FSF_PHASE_PREFILL = 2, /* prompt-chunk attention (matrix cores)                 */
-  FSF_PHASE_DECODE = 3,  /* generation-row split-KV attention                     */
-  FSF_PHASE_MERGE = 4,   /* merge of split partial results                        */
-  FSF_PHASE_GENERIC = 5, /* generic fp32 attention kernel                         */
-  FSF_PHASE_FUSED = 6,   /* prompt-chunk + generation-row attention in one launch  */
-  FSF_N_PHASES = 7
-} fsf_phase;
-int fsf_profile_enable(int on);
-int fsf_profile_read(double* ms_out, int64_t* launches_out);
-
-/*
- * Measurement aids: what the device sustains with nothing else in the way, to set beside the
- * published peaks the roofline fractions use.  Both run synchronously (they time themselves with
- * HIP events on hip_stream and wait) and write only to `scratch` (device, >= 4096 bytes).
- *   fsf_ceiling_mfma_bf16  a register-resident loop of 32x32x16 bf16 MFMAs, two waves per SIMD;
- *                          `operands` (device, >= 16 MiB, read once) supplies the fragment values:
- *                          the rate depends on them, because the clock the chip holds does.
- *                          iters: MFMAs per wave / 8.  Outputs (host): TFLOP/s and the shader clock
- *                          in MHz seen inside the kernel.
- *   fsf_ceiling_hbm_read   every wave streams 32 scattered 16 KB tiles of `buf` (device, `bytes`
- *                          long, >= 512 KiB; the largest power-of-two tile count that fits is
- *                          used), with non-temporal loads if nontemporal != 0.  Output: GB/s.
- * Return FSF_ERR_INVALID_ARG on null or too small buffers, FSF_ERR_HIP on a runtime error.
- */
-int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters, void* scratch,
-                          double* tflops_out, double* mhz_out, void* hip_stream);
-int fsf_ceiling_hbm_read(const void* buf, int64_t bytes, int32_t nontemporal, void* scratch,
-                         double* gbs_out, void* hip_stream);
-
-/*
- * Introspection (host only, no device call): how fsf_ragged_attention would cut the prompt
- * chunks of a pass into workgroups on a device with compute_units_assumed compute units.  A
- * chunk is tiled 256 rows at a time (tiles are numbered in descriptor order); a tile may be
- * cut into parts along its keys (a tile that would outlast the rest of the pass, or the tiles
- * of a last round of workgroups that is at most half full).  Writes up to cap entries of
- * (tile, part, n_parts, slab) in start order (slab: number of the (tile, part) in the
- * partial-result buffer, -1 for an unsplit tile); one workgroup per entry and query head.
- * Returns the number of entries, or -1 on invalid arguments.
- */
-int32_t fsf_plan_prefill_groups(const fsf_attn_cfg* cfg, const fsf_seq_desc* descs_host, int32_t n_seqs,
-                                int32_t compute_units_assumed, int32_t* groups_out, int32_t cap);
 
 /* Introspection (host): free blocks, live sequences (waiting prompts + generations). */
 int64_t fsf_sched_free_blocks(const fsf_sched* s);

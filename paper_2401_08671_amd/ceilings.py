@@ -14,6 +14,22 @@ import torch
 from . import fsf
 
 
+def mfma_probe(device="cuda", iters: int = 20_000, seed: int = 11):
+    """A short run of the register-resident bf16 MFMA loop on normally distributed operands:
+    ``{"TFLOPs", "shader_clock_MHz"}`` as the device holds them right now."""
+    L = fsf.lib()
+    L.fsf_ceiling_mfma_bf16.restype = C.c_int
+    L.fsf_ceiling_mfma_bf16.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    n = 16 << 20
+    g = torch.Generator(device=device).manual_seed(seed)
+    ops = torch.randn(n // 2, generator=g, device=device).to(torch.bfloat16)
+    scratch = torch.zeros(4096, dtype=torch.uint8, device=device)
+    tf, mhz = C.c_double(0), C.c_double(0)
+    fsf._check(L.fsf_ceiling_mfma_bf16(ops.data_ptr(), n, iters, scratch.data_ptr(), C.byref(tf), C.byref(mhz),
+                                       C.c_void_p(torch.cuda.current_stream().cuda_stream)), "fsf_ceiling_mfma_bf16")
+    return {"TFLOPs": tf.value, "shader_clock_MHz": mhz.value}
+
+
 def measure(device="cuda", hbm_bytes: int = 8 << 30, mfma_iters: int = 200_000):
     L = fsf.lib()
     L.fsf_ceiling_mfma_bf16.restype = C.c_int

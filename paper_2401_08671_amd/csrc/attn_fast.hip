@@ -24,14 +24,6 @@ __device__ __forceinline__ PrefillWork prefill_block_to_work(const Pass& p, cons
   return prefill_group_to_work(g, f.n_pre_tiles, f.split);
 }
 
-#ifdef FSF_CLOCK_PROBE
-// Developer aid (build with -DFSF_CLOCK_PROBE): the first 2048 prompt-chunk workgroups record
-// how many shader-clock ticks they ran for and when, on the constant 100 MHz counter, they
-// started and ended: the clock the chip actually held inside the kernel, and the timeline of
-// the launch (rounds, tail).
-constexpr int kClockProbeSlots = 2048;
-__device__ unsigned long long g_clock_probe[3 * kClockProbeSlots];
-#endif
 
 template <int DT, typename T>
 __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastPlan f,
@@ -42,18 +34,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastP
   __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
   int hq;
   const PrefillWork w = prefill_block_to_work(p, f, blockIdx.x, hq);
-#ifdef FSF_CLOCK_PROBE
-  const uint64_t c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
-#endif
   prefill_tile<DT, T>(p, f, q, kc, vc, out, w, hq, (lds_char*)lds);
-#ifdef FSF_CLOCK_PROBE
-  const uint64_t c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
-  if (threadIdx.x == 0 && blockIdx.x < kClockProbeSlots) {
-    g_clock_probe[3 * blockIdx.x] = c1 - c0;
-    g_clock_probe[3 * blockIdx.x + 1] = r0;
-    g_clock_probe[3 * blockIdx.x + 2] = r1;
-  }
-#endif
 }
 
 // One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
@@ -177,7 +158,7 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
   int hold_slots = 0;
   const unsigned slots = 8u * (unsigned)decode_compute_units();
   const int row_bytes = p.group * kHeadDim * 2;
-  if (n_units > slots && !getenv("FSF_DECODE_NO_HOLD")) {
+  if (n_units > slots && f.decode_hold) {
     grid = slots;
     const int per_wave = (int)((n_units + slots - 1) / slots);
     hold_slots = std::min(per_wave, (10 * 1024) / row_bytes);
@@ -209,11 +190,3 @@ hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, co
 
 }  // namespace fsf
 
-#ifdef FSF_CLOCK_PROBE
-// host buffer of 3 * 2048 uint64: (shader ticks, start, end on the 100 MHz counter) per workgroup of
-// the last launch
-extern "C" int fsf_dbg_clock_read(unsigned long long* host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fsf::g_clock_probe),
-                                  sizeof(unsigned long long) * 3 * fsf::kClockProbeSlots);
-}
-#endif

@@ -10,7 +10,7 @@
 
 #include <stdint.h>
 
-#include "fsf.h"
+#include "fsf_measure.h"
 
 namespace {
 

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "fsf_internal.h"
+#include "fsf_measure.h"
 
 namespace {
 
@@ -76,8 +77,36 @@ struct WsLayout {
   size_t dec_item_start, pre_tile_start, dec_item_seq, dec_order, pre_tile_seq, split_seqs, part_ml, part_acc, pre_part, total;
 };
 
-WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
-  const size_t items_cap = (size_t)n_seqs + fsf::kMaxDecodeItemsExtra;
+// The caller's fsf_tuning with every default filled in.  Reads only the fields the caller's
+// struct_bytes covers.
+struct Tuning {
+  int decode_target_waves, decode_min_item_blocks;
+  bool min_item_blocks_given, decode_hold, prefill_split;
+  int compute_units;  // 0: ask the device (only when a launch needs it)
+  int max_decode_items_extra, max_prefill_split_units;
+};
+
+Tuning resolve_tuning(const fsf_attn_cfg* c) {
+  fsf_tuning t = {};
+  if (c->tuning && c->tuning->struct_bytes > 0)
+    memcpy(&t, c->tuning, std::min<size_t>(sizeof(t), (size_t)c->tuning->struct_bytes));
+  Tuning r;
+  r.decode_target_waves = t.decode_target_waves > 0 ? t.decode_target_waves : 4096;
+  r.min_item_blocks_given = t.decode_min_item_blocks > 0;
+  // no item shorter than 16 blocks, or 1024 keys where blocks are smaller than 64 tokens
+  r.decode_min_item_blocks = r.min_item_blocks_given ? t.decode_min_item_blocks
+                                                     : (c->block_size < 64 ? std::max(1, 1024 / c->block_size) : 16);
+  r.decode_hold = t.decode_hold >= 0;
+  r.prefill_split = t.prefill_split >= 0;
+  r.compute_units = t.compute_units > 0 ? t.compute_units : 0;
+  r.max_decode_items_extra = t.max_decode_items_extra > 0 ? t.max_decode_items_extra : fsf::kMaxDecodeItemsExtra;
+  r.max_prefill_split_units = t.max_prefill_split_units > 0 ? std::min(t.max_prefill_split_units, fsf::kMaxPrefillSplitUnits)
+                                                            : fsf::kMaxPrefillSplitUnits;
+  return r;
+}
+
+WsLayout ws_layout(const fsf_attn_cfg* c, const Tuning& tn, int32_t n_seqs, int32_t n_tokens) {
+  const size_t items_cap = (size_t)n_seqs + tn.max_decode_items_extra;
   const size_t tiles_cap = (size_t)n_seqs + (size_t)n_tokens / fsf::kPrefillTileM;
   WsLayout w;
   size_t off = 0;
@@ -98,18 +127,11 @@ WsLayout ws_layout(const fsf_attn_cfg* c, int32_t n_seqs, int32_t n_tokens) {
   w.part_acc = off;
   off += align256(items_cap * c->n_q_heads * fsf::kHeadDim * sizeof(float));
   // partial results of split prompt-chunk tiles: at most kMaxPrefillSplitUnits (tile, head, part) workgroups
-  const size_t split_units = std::min<size_t>(fsf::kMaxPrefillSplitUnits, tiles_cap * c->n_q_heads * 16);
+  const size_t split_units = std::min<size_t>(tn.max_prefill_split_units, tiles_cap * c->n_q_heads * 16);
   w.pre_part = off;
   off += align256(split_units * fsf::kPrefillTileM * fsf::kPrefillPartRowFloats * sizeof(float));
   w.total = off;
   return w;
-}
-
-int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  if (!v || !*v) return dflt;
-  const int x = atoi(v);
-  return x > 0 ? x : dflt;
 }
 
 int compute_units() {
@@ -132,14 +154,15 @@ int compute_units() {
 //          kMaxHeavyTiles longest such tiles are taken
 //   tail:  when the last round of workgroups is at most half full, the tiles of that round are
 //          cut into as many parts as fill the round
-fsf::PrefillSplit plan_prefill_split(const std::vector<int>& n_steps, int H, int cus, bool allow) {
+fsf::PrefillSplit plan_prefill_split(const std::vector<int>& n_steps, int H, int cus, bool allow,
+                                     int max_split_units = fsf::kMaxPrefillSplitUnits) {
   fsf::PrefillSplit sp = {};
   const int n_tiles = (int)n_steps.size();
   if (!allow || n_tiles == 0) return sp;
   int64_t total = 0;
   for (int s : n_steps) total += s;
   const int64_t even = std::max<int64_t>((total * H + cus - 1) / cus, fsf::kPrefillMinPartSteps);
-  int budget = fsf::kMaxPrefillSplitUnits / H;  // (tile, part) groups with partial results
+  int budget = max_split_units / H;  // (tile, part) groups with partial results
   const bool one_round = (int64_t)n_tiles * H <= cus;
   // ---- heavy tiles
   std::vector<int> order(n_tiles);
@@ -198,10 +221,13 @@ std::vector<int> prefill_tile_steps_of(const fsf_attn_cfg* c, const fsf_seq_desc
   return steps;
 }
 
-fsf::PrefillSplit choose_prefill_split(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs) {
-  const int cus = env_int("FSF_PREFILL_SPLIT_UNITS", compute_units());  // tests force splits with a small value
-  const bool allow = !(c->flags & FSF_FLAG_FUSED_LAUNCH) && !getenv("FSF_PREFILL_NO_SPLIT");
-  return plan_prefill_split(prefill_tile_steps_of(c, h, n_seqs), c->n_q_heads, cus, allow);
+// one fused grid is launched only for blocks of 32 tokens or more, and never with split tiles
+bool fused_launch(const fsf_attn_cfg* c) { return (c->flags & FSF_FLAG_FUSED_LAUNCH) && c->block_size >= 32; }
+
+fsf::PrefillSplit choose_prefill_split(const fsf_attn_cfg* c, const Tuning& tn, const fsf_seq_desc* h, int32_t n_seqs) {
+  const int cus = tn.compute_units ? tn.compute_units : compute_units();  // tests force splits with a small value
+  const bool allow = !fused_launch(c) && tn.prefill_split;
+  return plan_prefill_split(prefill_tile_steps_of(c, h, n_seqs), c->n_q_heads, cus, allow, tn.max_prefill_split_units);
 }
 
 }  // namespace
@@ -238,6 +264,40 @@ extern "C" int32_t fsf_plan_prefill_groups(const fsf_attn_cfg* cfg, const fsf_se
   return n;
 }
 
+extern "C" int fsf_validate_pass(const fsf_attn_cfg* cfg, const fsf_seq_desc* descs_host,
+                                 const int32_t* block_tables_host, int32_t n_seqs, int32_t max_blocks,
+                                 int32_t n_tokens, int32_t* bad_seq_out, int32_t* bad_column_out) {
+  auto bad = [&](int32_t s, int32_t col) {
+    if (bad_seq_out) *bad_seq_out = s;
+    if (bad_column_out) *bad_column_out = col;
+    return (int)FSF_ERR_INVALID_ARG;
+  };
+  if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return bad(-1, -1);
+  if (n_seqs == 0) return n_tokens == 0 ? (int)FSF_OK : bad(-1, -1);
+  if (!descs_host || !block_tables_host) return bad(-1, -1);
+  int64_t off = 0;
+  for (int32_t s = 0; s < n_seqs; ++s) {  // descriptors tile [0, n_tokens) and fit the table
+    const fsf_seq_desc& d = descs_host[s];
+    const int64_t total = (int64_t)d.n_new + d.n_cached;
+    if (d.n_new < 1 || d.n_cached < 0 || d.q_offset != off || (total + cfg->block_size - 1) / cfg->block_size > max_blocks)
+      return bad(s, -1);
+    off += d.n_new;
+  }
+  if (off != n_tokens) return bad(-1, -1);
+  // every table entry the pass dereferences names a block of the pool, and none is named twice
+  std::vector<bool> seen((size_t)cfg->num_blocks, false);
+  for (int32_t s = 0; s < n_seqs; ++s) {
+    const int64_t total = (int64_t)descs_host[s].n_new + descs_host[s].n_cached;
+    const int32_t used = (int32_t)((total + cfg->block_size - 1) / cfg->block_size);
+    for (int32_t b = 0; b < used; ++b) {
+      const int32_t id = block_tables_host[(int64_t)s * max_blocks + b];
+      if (id < 0 || id >= cfg->num_blocks || seen[(size_t)id]) return bad(s, b);
+      seen[(size_t)id] = true;
+    }
+  }
+  return FSF_OK;
+}
+
 extern "C" int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const void* v_new,
                              void* k_cache, void* v_cache, const fsf_seq_desc* descs_dev,
                              const int32_t* block_tables_dev, int32_t n_seqs, int32_t max_blocks,
@@ -247,6 +307,7 @@ extern "C" int fsf_kv_append(const fsf_attn_cfg* cfg, const void* k_new, const v
   if (!k_new || !v_new || !k_cache || !v_cache || !descs_dev || !block_tables_dev)
     return FSF_ERR_INVALID_ARG;
   if ((cfg->head_dim * elem_size(cfg)) % 4) return FSF_ERR_UNSUPPORTED;
+  if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)k_cache | (uintptr_t)v_cache) & 3) return FSF_ERR_INVALID_ARG;
   const Pass p = make_pass(cfg, descs_dev, block_tables_dev, n_seqs, max_blocks, n_tokens);
   const hipError_t e =
       fsf::launch_kv_append(p, k_new, v_new, k_cache, v_cache, (hipStream_t)hip_stream);
@@ -292,7 +353,7 @@ extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, 
                                                        int32_t n_tokens, int32_t max_blocks) {
   if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return 0;
   if (!fast_path_ok(cfg)) return 256;
-  return ws_layout(cfg, n_seqs, n_tokens).total;
+  return ws_layout(cfg, resolve_tuning(cfg), n_seqs, n_tokens).total;
 }
 
 extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
@@ -329,16 +390,16 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   }
   // Two rounds of the chip's 2048 wave slots: with the units launched longest first that is
   // balance enough, and every split costs partial results whose writes are expensive.
-  const int target_waves = env_int("FSF_DECODE_TARGET_WAVES", 4096);
-  // no item shorter than 16 blocks, or 1024 keys where blocks are smaller than 64 tokens
-  const int min_item_blocks = env_int("FSF_DECODE_MIN_ITEM_BLOCKS", cfg->block_size < 64 ? 1024 / cfg->block_size : 16);
-  int64_t target_items = target_waves / cfg->n_kv_heads;
+  const Tuning tn = resolve_tuning(cfg);
+  const int cus = tn.compute_units ? tn.compute_units : compute_units();
+  const int min_item_blocks = tn.decode_min_item_blocks;
+  int64_t target_items = tn.decode_target_waves / cfg->n_kv_heads;
   if (target_items < 1) target_items = 1;
-  if (target_items > fsf::kMaxDecodeItemsExtra) target_items = fsf::kMaxDecodeItemsExtra;
+  if (target_items > tn.max_decode_items_extra) target_items = tn.max_decode_items_extra;
   int64_t sb = (dec_blocks + target_items - 1) / target_items;
   if (sb < 1) sb = 1;
 
-  const WsLayout w = ws_layout(cfg, n_seqs, n_tokens);
+  const WsLayout w = ws_layout(cfg, tn, n_seqs, n_tokens);
   char* ws = (char*)workspace;
   fsf::FastPlan f;
   f.dec_item_start = (int32_t*)(ws + w.dec_item_start);
@@ -368,19 +429,20 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   count_work();
   // A pass with so few generation rows that not even every compute unit gets a wave (one
   // long sequence alone, say) is bound by the latency of its longest unit: cut four times finer.
-  if (n_dec * cfg->n_kv_heads < compute_units() && !getenv("FSF_DECODE_MIN_ITEM_BLOCKS")) {
+  if (n_dec * cfg->n_kv_heads < cus && !tn.min_item_blocks_given) {
     f.min_item_blocks = std::max(1, min_item_blocks / 4);
     count_work();
   }
-  if (n_dec > (int64_t)n_seqs + fsf::kMaxDecodeItemsExtra) return FSF_ERR_WORKSPACE;  // cannot happen
+  if (n_dec > (int64_t)n_seqs + tn.max_decode_items_extra) return FSF_ERR_WORKSPACE;  // cannot happen
   f.n_dec_items = (int32_t)n_dec;
   f.n_pre_tiles = (int32_t)n_pre;
   f.n_split_seqs = n_split;
   f.pre_part = (float*)(ws + w.pre_part);
-  f.split = choose_prefill_split(cfg, descs_host, n_seqs);
+  f.split = choose_prefill_split(cfg, tn, descs_host, n_seqs);
+  f.decode_hold = tn.decode_hold;
 
   hipError_t e = fsf::launch_plan(p, f, stream);
-  if ((cfg->flags & FSF_FLAG_FUSED_LAUNCH) && cfg->block_size >= 32) {
+  if (fused_launch(cfg)) {
     if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
   } else {
     if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);

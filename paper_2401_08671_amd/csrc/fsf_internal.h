@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "fsf.h"
+#include "fsf_measure.h"
 
 namespace fsf {
 
@@ -206,6 +207,7 @@ struct FastPlan {
   int32_t min_item_blocks;  // no split leaves an item with fewer blocks than this
   int32_t n_dec_items, n_pre_tiles, n_split_seqs;  // host-side totals (grid sizes)
   PrefillSplit split;       // which prompt-chunk tiles are cut along their keys
+  int32_t decode_hold;      // host side: streaming waves may hold finished rows back (see attn_decode_kernel)
 };
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);

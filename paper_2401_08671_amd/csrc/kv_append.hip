@@ -145,7 +145,8 @@ hipError_t launch_kv_append(const Pass& p, const void* k_new, const void* v_new,
   PhaseTimer timer(FSF_PHASE_APPEND, stream);
   const int esize = p.dtype == FSF_F32 ? 4 : 2;
   const int head_bytes = p.head_dim * esize;
-  if (head_bytes % 16 == 0) {
+  const uintptr_t all = (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)k_cache | (uintptr_t)v_cache;
+  if (head_bytes % 16 == 0 && (all & 15) == 0) {  // 16-byte units need 16-byte aligned tensors
     kv_append_kernel<uint4><<<p.n_tokens, 256, 0, stream>>>(
         p, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache, (uint4*)v_cache,
         head_bytes / 16);

@@ -2,6 +2,7 @@
 #include <vector>
 
 #include "fsf_internal.h"
+#include "fsf_measure.h"
 
 namespace {
 
@@ -39,7 +40,11 @@ PhaseTimer::PhaseTimer(int phase, hipStream_t stream)
 PhaseTimer::~PhaseTimer() {
   if (!on_) return;
   hipEvent_t stop = get_event();
-  if (!stop || hipEventRecord(stop, stream_) != hipSuccess) return;
+  if (!stop || hipEventRecord(stop, stream_) != hipSuccess) {  // drop the measurement, keep the events
+    g_pool.push_back(start_);
+    if (stop) g_pool.push_back(stop);
+    return;
+  }
   g_recs.push_back({start_, stop, phase_});
 }
 

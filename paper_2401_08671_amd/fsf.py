@@ -27,10 +27,23 @@ class SeqDesc(C.Structure):
     _fields_ = [("n_new", C.c_int32), ("n_cached", C.c_int32), ("q_offset", C.c_int32), ("seq_id", C.c_int32)]
 
 
+class Tuning(C.Structure):
+    """fsf_tuning: 0 = default for every field (see include/fsf.h)."""
+    _fields_ = [("struct_bytes", C.c_int32), ("decode_target_waves", C.c_int32),
+                ("decode_min_item_blocks", C.c_int32), ("decode_hold", C.c_int32),
+                ("prefill_split", C.c_int32), ("compute_units", C.c_int32),
+                ("max_decode_items_extra", C.c_int32), ("max_prefill_split_units", C.c_int32)]
+
+    def __init__(self, **kw):
+        super().__init__(**kw)
+        self.struct_bytes = C.sizeof(Tuning)
+
+
 class AttnCfg(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("block_size", C.c_int32), ("window", C.c_int32), ("scale", C.c_float),
-                ("dtype", C.c_int32), ("flags", C.c_int32), ("num_blocks", C.c_int64)]
+                ("dtype", C.c_int32), ("flags", C.c_int32), ("num_blocks", C.c_int64),
+                ("tuning", C.POINTER(Tuning))]
 
 
 class FsfError(RuntimeError):
@@ -57,6 +70,8 @@ def lib() -> C.CDLL:
     L.fsf_version.restype = C.c_int
     L.fsf_kv_append.restype = C.c_int
     L.fsf_kv_append.argtypes = [cfgp, vp, vp, vp, vp, descp, i32p, i32, i32, i32, vp]
+    L.fsf_validate_pass.restype = C.c_int
+    L.fsf_validate_pass.argtypes = [cfgp, vp, vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     L.fsf_kv_append_rotary.restype = C.c_int
     L.fsf_kv_append_rotary.argtypes = [cfgp, vp, vp, vp, vp, descp, descp, i32p, i32, i32, i32, vp, i32, vp]
     L.fsf_rotary_q.restype = C.c_int
@@ -95,10 +110,15 @@ def version() -> int:
     return lib().fsf_version()
 
 
-def make_cfg(n_q_heads, n_kv_heads, head_dim, block_size, dtype, num_blocks, window=0, scale=None, flags=0) -> AttnCfg:
+def make_cfg(n_q_heads, n_kv_heads, head_dim, block_size, dtype, num_blocks, window=0, scale=None, flags=0,
+             tuning: Tuning | None = None) -> AttnCfg:
     if scale is None:
         scale = head_dim ** -0.5
-    return AttnCfg(n_q_heads, n_kv_heads, head_dim, block_size, window, scale, DTYPE_CODE[dtype], flags, num_blocks)
+    cfg = AttnCfg(n_q_heads, n_kv_heads, head_dim, block_size, window, scale, DTYPE_CODE[dtype], flags, num_blocks)
+    if tuning is not None:
+        cfg.tuning = C.pointer(tuning)
+        cfg._tuning_ref = tuning          # the struct must outlive the calls that read it
+    return cfg
 
 
 def _ptr(t):
@@ -125,6 +145,17 @@ class DeviceBatch:
         self.n_tokens = int(self.descs_host[:, 0].sum()) if self.n_seqs else 0
         self.descs_dev = torch.from_numpy(self.descs_host).to(device)
         self.bt_dev = torch.from_numpy(self.bt_host).to(device)
+
+
+def validate_pass(cfg: AttnCfg, descs: np.ndarray, block_tables: np.ndarray):
+    """fsf_validate_pass on host arrays: None if the pass is sound, else (bad sequence, bad table column)."""
+    d = np.ascontiguousarray(descs, dtype=np.int32).reshape(-1, 4)
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    bs, bc = C.c_int32(-2), C.c_int32(-2)
+    st = lib().fsf_validate_pass(C.byref(cfg), C.c_void_p(d.ctypes.data), C.c_void_p(bt.ctypes.data), len(d),
+                                 bt.shape[1] if bt.ndim == 2 else 1, int(d[:, 0].sum()) if len(d) else 0,
+                                 C.byref(bs), C.byref(bc))
+    return None if st == FSF_OK else (bs.value, bc.value)
 
 
 def kv_append(cfg: AttnCfg, k_new, v_new, k_cache, v_cache, batch: DeviceBatch) -> None:

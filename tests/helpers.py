@@ -75,3 +75,25 @@ class Step:
 def t2f64(t: torch.Tensor) -> np.ndarray:
     """Device/host tensor -> float64 numpy, exactly."""
     return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def plant_dominant_key(step: Step, s: int, row: int, q_head: int, position: int, logit: float = 34.0):
+    """Make key ``position`` of sequence ``s`` dominate the softmax of (row ``row`` of that
+    sequence, query head ``q_head``): its K row becomes a multiple of that query, scaled so that
+    the logit is ``logit`` (random keys give logits of a few units at most).  The row's output is
+    then that key's V row to ~1e-12, so a unit, part or split that drops or doubles the key moves
+    the output by O(1).  Edits ``k_cache0`` (cached positions) or ``k_new`` (this pass's
+    tokens) in place; returns the planted key's V row as float64 ``[d]``."""
+    sp = step.spec
+    n_new, n_cached, q_off, _ = (int(x) for x in step.descs[s])
+    assert 0 <= row < n_new and 0 <= position <= n_cached + row
+    hk = q_head // (sp.n_q_heads // sp.n_kv_heads)
+    q = oa.to_f64(step.q[q_off + row, q_head], sp.dtype)
+    k = (q * (logit / (sp.scale * float(q @ q)))).astype(np.float32)
+    k_bits = oa.f32_to_storage(k, sp.dtype)
+    if position < n_cached:
+        blk = int(step.block_tables[s, position // sp.block_size])
+        step.k_cache0[blk, hk, position % sp.block_size] = k_bits
+        return oa.to_f64(step.v_cache0[blk, hk, position % sp.block_size], sp.dtype)
+    step.k_new[q_off + position - n_cached, hk] = k_bits
+    return oa.to_f64(step.v_new[q_off + position - n_cached, hk], sp.dtype)

@@ -10,11 +10,16 @@ from paper_2401_08671_amd import fsf
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "fsf.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(fsf_[a-z_0-9]+)\s*\(", text)
-    return sorted(set(names))
+HEADERS = ("fsf.h", "fsf_measure.h")
+
+
+def declared_functions(headers=HEADERS):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(fsf_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_three_named_calls():
@@ -29,10 +34,67 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), f"{name} declared in fsf.h but not exported"
 
 
+def struct_fields(name):
+    """Field names of a struct typedef in fsf.h, in order."""
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "fsf.h")).read(), flags=re.S)
+    body = re.search(r"typedef struct \{([^}]*)\}\s*" + name + ";", text).group(1)
+    return [re.findall(r"(\w+)\s*$", decl.strip())[0] for decl in body.split(";") if decl.strip()]
+
+
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(fsf.SeqDesc) == 16
-    assert ctypes.sizeof(fsf.AttnCfg) == 40
-    assert fsf.AttnCfg.num_blocks.offset == 32
+    assert ctypes.sizeof(fsf.AttnCfg) == 48
+    assert fsf.AttnCfg.num_blocks.offset == 32 and fsf.AttnCfg.tuning.offset == 40
+    assert [f[0] for f in fsf.AttnCfg._fields_] == struct_fields("fsf_attn_cfg")
+    # the tuning struct: int32 fields in the header's order, its own size in the first
+    assert [f[0] for f in fsf.Tuning._fields_] == struct_fields("fsf_tuning")
+    assert all(f[1] is ctypes.c_int32 for f in fsf.Tuning._fields_)
+    assert ctypes.sizeof(fsf.Tuning) == 4 * len(fsf.Tuning._fields_)
+    assert fsf.Tuning(compute_units=7).struct_bytes == ctypes.sizeof(fsf.Tuning)
+
+
+def test_the_product_header_holds_no_measurement_aid_and_the_library_reads_no_environment():
+    names = declared_functions(("fsf.h",))
+    assert not [n for n in names if n.startswith(("fsf_profile", "fsf_ceiling", "fsf_plan_"))]
+    csrc = os.path.join(ROOT, "paper_2401_08671_amd", "csrc")
+    for f in os.listdir(csrc):
+        if f.endswith((".hip", ".cpp", ".h")):
+            assert "getenv" not in open(os.path.join(csrc, f)).read(), f
+
+
+def test_tuning_bounds_the_workspace():
+    """max_decode_items_extra and max_prefill_split_units size the partial-result areas."""
+    big = fsf.make_cfg(32, 8, 128, 64, "bf16", 1000)
+    small = fsf.make_cfg(32, 8, 128, 64, "bf16", 1000,
+                         tuning=fsf.Tuning(max_decode_items_extra=256, max_prefill_split_units=32))
+    nb, ns = (fsf.ragged_attention_workspace_bytes(c, 300, 2048, 70) for c in (big, small))
+    assert 0 < ns < nb and ns < 32 << 20 < nb
+    # a caller compiled against a shorter struct: the missing fields take their defaults
+    short = fsf.Tuning(max_decode_items_extra=256, max_prefill_split_units=32)
+    short.struct_bytes = 8
+    assert fsf.ragged_attention_workspace_bytes(fsf.make_cfg(32, 8, 128, 64, "bf16", 1000, tuning=short), 300, 2048, 70) == nb
+
+
+def test_validate_pass_finds_bad_descriptors_and_block_ids():
+    import numpy as np
+    cfg = fsf.make_cfg(4, 2, 64, 16, "f32", 10)
+    descs = np.array([[20, 0, 0, 0], [1, 31, 20, 1], [3, 5, 21, 2]], np.int32)
+    bt = np.array([[4, 7, -1], [0, 1, -1], [9, -1, -1]], np.int32)
+    assert fsf.validate_pass(cfg, descs, bt) is None
+    bad = bt.copy(); bad[1, 1] = 10                       # beyond the pool
+    assert fsf.validate_pass(cfg, descs, bad) == (1, 1)
+    bad = bt.copy(); bad[0, 1] = -1                       # a position without its block
+    assert fsf.validate_pass(cfg, descs, bad) == (0, 1)
+    bad = bt.copy(); bad[2, 0] = 7                        # one block in two sequences
+    assert fsf.validate_pass(cfg, descs, bad) == (2, 0)
+    bad = bt.copy(); bad[2, 1] = 99                       # unused entries are never looked at
+    assert fsf.validate_pass(cfg, descs, bad) is None
+    d2 = descs.copy(); d2[2, 2] = 22                      # q_offset is not the running sum
+    assert fsf.validate_pass(cfg, d2, bt) == (2, -1)
+    d2 = descs.copy(); d2[1, 1] = 48                      # needs a fourth table column
+    assert fsf.validate_pass(cfg, d2, bt) == (1, -1)
+    d2 = descs.copy(); d2[0, 0] = 0
+    assert fsf.validate_pass(cfg, d2, bt)[0] == 0
 
 
 def test_strerror_and_version():

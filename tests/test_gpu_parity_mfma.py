@@ -4,8 +4,6 @@ Element-by-element on shapes that span several tiles and ragged tails: generatio
 with and without KV splitting, prompt chunks with partial tiles and cached prefixes, GQA
 groups 1..16, sliding windows cutting blocks, poisoned unwritten slots.
 """
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -13,29 +11,27 @@ import torch
 from paper_2401_08671_amd import fsf
 from paper_2401_08671_amd import workloads as wl
 from tests.gpu_util import assert_cache_bit_exact, assert_outputs_close, run_hip
-from tests.helpers import Step
+from tests.helpers import Step, plant_dominant_key
 
 pytestmark = pytest.mark.gpu
 
 
-def check_step(step, what="", flags=0):
+def check_step(step, what="", flags=0, tuning=None):
     kc_o, vc_o, out_o = step.oracle()
-    kc_h, vc_h, out_h = run_hip(step, flags=flags)
+    kc_h, vc_h, out_h = run_hip(step, flags=flags, tuning=tuning)
     assert_cache_bit_exact(kc_h, kc_o, what + " K")
     assert_cache_bit_exact(vc_h, vc_o, what + " V")
     return assert_outputs_close(out_h, out_o, step.spec.dtype, what)
 
 
-@pytest.fixture
-def split_env():
-    """Force fine KV splits so the merge path runs even on short sequences."""
-    old = {k: os.environ.get(k) for k in ("FSF_DECODE_TARGET_WAVES", "FSF_DECODE_MIN_ITEM_BLOCKS")}
-    yield lambda waves, mins: os.environ.update(FSF_DECODE_TARGET_WAVES=str(waves), FSF_DECODE_MIN_ITEM_BLOCKS=str(mins))
-    for k, v in old.items():
-        if v is None:
-            os.environ.pop(k, None)
-        else:
-            os.environ[k] = v
+def cut_rows(waves, min_blocks):
+    """Tuning that forces fine cuts of the generation rows, so that the merge runs on short sequences too."""
+    return fsf.Tuning(decode_target_waves=waves, decode_min_item_blocks=min_blocks)
+
+
+def assume_units(units):
+    """Tuning that pretends the chip has this many compute units, so that small batches get split tiles."""
+    return fsf.Tuning(compute_units=units)
 
 
 DECODE_LENS = [0, 1, 30, 31, 32, 33, 63, 64, 65, 127, 128, 200, 511, 512, 513, 1000, 2049]
@@ -52,10 +48,9 @@ def test_decode_rows(dtype, heads, poison):
 
 @pytest.mark.parametrize("split", [(1 << 20, 1), (1 << 20, 2), (64, 4)])
 @pytest.mark.parametrize("window", [0, 100, 128, 1000])
-def test_decode_rows_split_and_window(split_env, split, window):
-    split_env(*split)
+def test_decode_rows_split_and_window(split, window):
     spec = wl.BatchSpec("decw", 8, 2, 128, 64, "bf16", [(1, c) for c in DECODE_LENS], window=window, seed=10)
-    check_step(Step(spec, poison="nan"), f"decode split={split} window={window}")
+    check_step(Step(spec, poison="nan"), f"decode split={split} window={window}", tuning=cut_rows(*split))
 
 
 def test_decode_block_128():
@@ -92,13 +87,12 @@ def test_prefill_larger_blocks(block):
 @pytest.mark.parametrize("block", [16, 32])
 @pytest.mark.parametrize("split", [(1 << 20, 1), (256, 4)])
 @pytest.mark.parametrize("window", [0, 100, 1000])
-def test_decode_rows_small_blocks(split_env, block, split, window):
+def test_decode_rows_small_blocks(block, split, window):
     """Blocks of 16 and 32 tokens: a 32-key step spans two blocks (16) or is one block (32); unit
     boundaries then fall on multiples of 16 keys, inside a step."""
-    split_env(*split)
     spec = wl.BatchSpec("decsmall", 8, 2, 128, block, "bf16", [(1, c) for c in DECODE_LENS + [15, 16, 17, 47, 48]],
                         window=window, seed=25)
-    check_step(Step(spec, poison="nan"), f"decode B={block} split={split} window={window}")
+    check_step(Step(spec, poison="nan"), f"decode B={block} split={split} window={window}", tuning=cut_rows(*split))
 
 
 @pytest.mark.parametrize("block", [16, 32])
@@ -112,10 +106,9 @@ def test_prefill_small_blocks(block, dtype, window):
 
 
 @pytest.mark.parametrize("block", [16, 32])
-def test_prefill_small_blocks_split_tiles(prefill_split_env, block):
-    prefill_split_env(64)
+def test_prefill_small_blocks_split_tiles(block):
     spec = wl.BatchSpec("presmallsplit", 2, 1, 128, block, "bf16", [(100, 3000), (300, 0), (1, 77)], seed=27)
-    check_step(Step(spec, poison="nan"), f"prefill split B={block}")
+    check_step(Step(spec, poison="nan"), f"prefill split B={block}", tuning=assume_units(64))
 
 
 def test_prefill_block_192_takes_the_generic_kernel():
@@ -139,26 +132,14 @@ def test_prefill_window_inside_long_prefix(window):
     check_step(Step(spec, poison="nan"), f"prefill window={window} over a long prefix")
 
 
-@pytest.fixture
-def prefill_split_env():
-    """Pretend the chip has this many compute units, so that small batches get split tiles."""
-    old = os.environ.get("FSF_PREFILL_SPLIT_UNITS")
-    yield lambda units: os.environ.update(FSF_PREFILL_SPLIT_UNITS=str(units))
-    if old is None:
-        os.environ.pop("FSF_PREFILL_SPLIT_UNITS", None)
-    else:
-        os.environ["FSF_PREFILL_SPLIT_UNITS"] = old
-
-
 @pytest.mark.parametrize("units,window,dtype", [(64, 0, "bf16"), (64, 700, "f16"), (40, 0, "bf16"), (1000, 0, "bf16")])
-def test_prefill_tiles_split_along_keys(prefill_split_env, units, window, dtype):
+def test_prefill_tiles_split_along_keys(units, window, dtype):
     """Tiles of a partial last round are cut into parts along their keys (one workgroup each,
     unnormalised partial results, merge): forced here by a small unit count.  Parts that end
     before a row's first visible key, or start after its last, contribute nothing to that row."""
-    prefill_split_env(units)
     seqs = [(700, 1500), (1, 900), (300, 2100), (1, 64)]
     spec = wl.BatchSpec("presplit", 2, 1, 128, 64, dtype, seqs, window=window, seed=31)
-    check_step(Step(spec, poison="nan"), f"prefill split units={units} window={window} {dtype}")
+    check_step(Step(spec, poison="nan"), f"prefill split units={units} window={window} {dtype}", tuning=assume_units(units))
 
 
 @pytest.mark.parametrize("heads,n_rows,block,dtype", [((16, 1), 5000, 64, "bf16"), ((8, 4), 1300, 64, "bf16"),
@@ -191,6 +172,51 @@ def test_very_long_contexts(window):
     chunk over 150 000: long block tables, large offsets, thousands of steps per tile."""
     spec = wl.BatchSpec("long", 2, 1, 128, 64, "bf16", [(1, 200_000), (300, 150_000), (1, 70_001)], window=window, seed=34)
     check_step(Step(spec), f"long contexts window={window}")
+
+
+@pytest.mark.parametrize("mult", [1.0, 1.0 / np.sqrt(128.0)])
+@pytest.mark.parametrize("block", [16, 64])
+def test_every_unit_of_a_cut_generation_row_counts(mult, block):
+    """Rows over 12 000 cached tokens, cut into units of 256 keys.  In sequence u one key inside
+    unit 3u (and the first and the last key in two more sequences) is given a dominant logit, so
+    that row's output is that key's V row: a unit that is lost, merged with the wrong weight or
+    counted twice moves it by O(1).  Also with values scaled like benchmark shape 2, where
+    ordinary outputs lie below the absolute tolerance."""
+    c, per_unit = 12_000, 256
+    n_units = -(-(c + 1) // per_unit)
+    plants = [min(3 * u * per_unit + 17 * u + 5, c) for u in range(0, (n_units + 2) // 3)] + [0, c, per_unit - 1, per_unit]
+    spec = wl.BatchSpec("plantdec", 2, 1, 128, block, "bf16", [(1, c)] * len(plants), value_mult=mult, seed=41)
+    st = Step(spec)
+    want_v = [plant_dominant_key(st, s, 0, 0, pos) for s, pos in enumerate(plants)]
+    tn = cut_rows(1 << 20, per_unit // block)
+    _, _, out_o = st.oracle()
+    _, _, out_h = run_hip(st, tuning=tn, return_cache=False)
+    assert_outputs_close(out_h, out_o, "bf16", f"planted keys mult={mult:.3f} B={block}")
+    for s, v in enumerate(want_v):
+        assert np.abs(out_o[s, 0] - v).max() <= 1e-9 * max(1.0, np.abs(v).max()), "the plant did not take"
+        assert np.abs(out_h[s, 0] - v).max() <= 2.0 ** -8 * np.abs(v).max() + 1e-30, f"sequence {s}, key {plants[s]}"
+
+
+@pytest.mark.parametrize("units,window", [(64, 0), (1000, 0), (64, 2500)])
+def test_every_part_of_a_split_tile_counts(units, window):
+    """A 300-row chunk over 3000 cached tokens whose tiles are cut into parts along their keys.
+    Sixteen of its rows get one dominant key each, spread over the whole visible range, so every
+    part holds the dominant key of some row."""
+    n, c = 300, 3000
+    spec = wl.BatchSpec("plantpre", 2, 1, 128, 64, "bf16", [(n, c), (1, 77)], window=window, seed=42)
+    st = Step(spec)
+    rows = [n - 1 - 18 * k for k in range(16)]
+    plants = []
+    for k, r in enumerate(rows):
+        lo = max(0, c + r - window + 1) if window else 0
+        pos = lo + (c + r - lo) * k // 15                  # from the row's first visible key to its own
+        plants.append((r, pos, plant_dominant_key(st, 0, r, 0, pos)))
+    _, _, out_o = st.oracle()
+    _, _, out_h = run_hip(st, tuning=assume_units(units), return_cache=False)
+    assert_outputs_close(out_h, out_o, "bf16", f"planted keys in a split tile units={units} window={window}")
+    for r, pos, v in plants:
+        assert np.abs(out_o[r, 0] - v).max() <= 1e-9 * np.abs(v).max(), "the plant did not take"
+        assert np.abs(out_h[r, 0] - v).max() <= 2.0 ** -8 * np.abs(v).max(), f"row {r}, key {pos}"
 
 
 @pytest.mark.parametrize("flags", [0, fsf.FSF_FLAG_FUSED_LAUNCH])
@@ -239,7 +265,7 @@ def test_benchmark_shapes_reduced(k, nd):
 
 
 @pytest.mark.parametrize("seed", range(10))
-def test_random_ragged_batches(seed, prefill_split_env):
+def test_random_ragged_batches(seed):
     """Seeded random passes: chunks of any length over any prefix next to generation rows, random
     head grouping, window, block size and unit count (which moves the split rules around)."""
     rng = np.random.default_rng(7000 + seed)
@@ -259,9 +285,9 @@ def test_random_ragged_batches(seed, prefill_split_env):
     seqs = [seqs[i] for i in order]
     # keep the oracle's dense score matrices small
     assert sum((n + c) * n for n, c in seqs) < 30_000_000
-    prefill_split_env(int(rng.choice([4, 16, 64, 256])))
+    tn = assume_units(int(rng.choice([4, 16, 64, 256])))
     spec = wl.BatchSpec(f"rand{seed}", Hq, Hkv, 128, block, dtype, seqs, window=window, seed=8000 + seed)
-    check_step(Step(spec, poison="nan"), f"random batch {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} {seqs}")
+    check_step(Step(spec, poison="nan"), f"random batch {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} {seqs}", tuning=tn)
 
 
 def test_a_pass_can_be_captured_in_a_graph_and_replayed():
@@ -303,7 +329,7 @@ def test_a_pass_can_be_captured_in_a_graph_and_replayed():
 
 
 @pytest.mark.parametrize("seed", range(100, 112))
-def test_random_passes_over_block_sizes_groups_and_unit_counts(seed, prefill_split_env, split_env):
+def test_random_passes_over_block_sizes_groups_and_unit_counts(seed):
     """Seeded random passes over the whole matrix-core envelope: 1 to 16 query heads per KV head,
     blocks of 16 to 128 tokens, windows, no to thousands of generation rows (one unit per workgroup,
     or one round of waves holding their results), forced fine or no cuts of the rows."""
@@ -322,8 +348,8 @@ def test_random_passes_over_block_sizes_groups_and_unit_counts(seed, prefill_spl
         seqs = [(1, 5)]
     order = rng.permutation(len(seqs))
     seqs = [seqs[i] for i in order]
-    prefill_split_env(int(rng.choice([4, 16, 64, 256])))
+    tn = assume_units(int(rng.choice([4, 16, 64, 256])))
     if rng.random() < 0.3:
-        split_env(int(rng.choice([64, 100000])), 16)
+        tn.decode_target_waves, tn.decode_min_item_blocks = int(rng.choice([64, 100000])), 16
     spec = wl.BatchSpec(f"wide{seed}", Hq, Hkv, 128, block, dtype, seqs, window=window, seed=9000 + seed)
-    check_step(Step(spec, poison="nan"), f"seed {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} n_seqs={len(seqs)}")
+    check_step(Step(spec, poison="nan"), f"seed {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} n_seqs={len(seqs)}", tuning=tn)

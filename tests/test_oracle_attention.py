@@ -328,6 +328,22 @@ def test_f32_to_bf16_rounding_matches_torch_and_ties_go_to_even():
     assert oa.f32_to_storage(ties, "bf16").tolist() == [0x3F80, 0x3F82]
 
 
+def test_f32_to_f16_rounding_matches_torch_ties_go_to_even_and_small_values_go_subnormal():
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal(200000) * np.exp(rng.uniform(-14, 9, 200000))).astype(np.float32)
+    x = x[np.abs(x) < 65504.0]               # the kernels never produce values beyond the f16 range
+    want = torch.from_numpy(x).to(torch.float16).numpy()
+    got = oa.f32_to_storage(x, "f16")
+    assert got.dtype == np.float16 and np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    # exact ties (f16 keeps 10 mantissa bits): 1 + 2^-11 lies between 1 and 1 + 2^-10 -> the even
+    # mantissa 1.0 (0x3C00); 1 + 3 * 2^-11 between 1 + 2^-10 and 1 + 2^-9 -> 1 + 2^-9 (0x3C02)
+    ties = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -(1.0 + 2.0 ** -11)], dtype=np.float32)
+    assert oa.f32_to_storage(ties, "f16").view(np.uint16).tolist() == [0x3C00, 0x3C02, 0xBC00]
+    # just above a tie rounds up; subnormal range: 2^-24 is the smallest f16, half of it ties to zero
+    more = np.array([1.0 + 2.0 ** -11 + 2.0 ** -20, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25], dtype=np.float32)
+    assert oa.f32_to_storage(more, "f16").view(np.uint16).tolist() == [0x3C01, 0x0001, 0x0000, 0x0002]
+
+
 def test_rotary_table_and_rotation_closed_forms():
     tab = oa.rotary_table(64, 8, theta=10000.0)
     assert tab.shape == (64, 4, 2) and np.all(tab[0, :, 0] == 1.0) and np.all(tab[0, :, 1] == 0.0)

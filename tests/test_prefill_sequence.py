@@ -10,18 +10,28 @@ import re
 import subprocess
 import sys
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2401_08671_amd", "csrc")
 
 
 def test_header_on_disk_matches_generator():
+    """The header is a build product (not tracked): where a build has left one, it is the generator's output."""
+    if not os.path.exists(os.path.join(CSRC, "attn_prefill_sequence.h")):
+        pytest.skip("no build has run in this tree yet")
     r = subprocess.run([sys.executable, os.path.join(CSRC, "gen_prefill_sequence.py"), "--check"],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
 
 
 def sequence_lines():
-    text = open(os.path.join(CSRC, "attn_prefill_sequence.h")).read()
+    sys.path.insert(0, CSRC)
+    try:
+        import gen_prefill_sequence
+        text = gen_prefill_sequence.render()
+    finally:
+        sys.path.remove(CSRC)
     lines = []
     for l in text.split("\n"):
         m = re.search(r'"(.*?)\\n(\\t)?"', l)
