@@ -229,6 +229,29 @@ int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_c
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * fsf_ragged_attention for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without the workspace, same kernels, same results to the same tolerance.  The work
+ * tables and partial results live in a fixed array of FSF_STATIC_SCRATCH_BYTES (64 MiB) of device
+ * memory that is part of the library image: every GPU the library runs on holds it from the
+ * first call on that GPU until the process ends, and the call allocates and frees nothing.
+ * The cutting of generation rows and prompt-chunk tiles into units with partial results is
+ * limited to what fits the array (at most 1024 extra row units and 64 tile units, fewer for
+ * passes with many sequences or heads); a pass whose tables alone exceed the array (tens of
+ * thousands of sequences at many heads) is refused with FSF_ERR_WORKSPACE and nothing is
+ * launched.  All calls on one GPU share the array: calls that overlap on one GPU (two
+ * streams, two threads) race and give wrong results; calls on one stream, or ordered by
+ * events, are safe.  The first call on a device looks the array's address up and should be
+ * made outside a graph capture.  Errors otherwise as fsf_ragged_attention.
+ */
+#define FSF_STATIC_SCRATCH_BYTES (64u << 20)
+int fsf_ragged_attention_static(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
+                                const void* v_cache, const fsf_seq_desc* descs_dev,
+                                const fsf_seq_desc* descs_host, const int32_t* block_tables_dev,
+                                int32_t n_seqs, int32_t max_blocks, int32_t n_tokens, void* out,
+                                void* hip_stream);
+
+/*
  * Host-side Dynamic SplitFuse scheduler with a block allocator (paper Sec. 2.2: one
  * batch decision per forward pass; Sec. 3.2: long prompts are split over passes with
  * only the last chunk generating, and prompts are fused with generations to meet the

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <utility>
 #include <vector>
 
@@ -356,20 +357,26 @@ extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, 
   return ws_layout(cfg, resolve_tuning(cfg), n_seqs, n_tokens).total;
 }
 
-extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
-                                    const void* v_cache, const fsf_seq_desc* descs_dev,
-                                    const fsf_seq_desc* descs_host,
-                                    const int32_t* block_tables_dev, int32_t n_seqs,
-                                    int32_t max_blocks, int32_t n_tokens, void* out,
-                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+// Checks shared by the two attention entry points; FSF_OK means there is work to launch.
+int attention_args_ok(const fsf_attn_cfg* cfg, const void* q, const void* k_cache, const void* v_cache,
+                      const fsf_seq_desc* descs_dev, const fsf_seq_desc* descs_host,
+                      const int32_t* block_tables_dev, int32_t n_seqs, int32_t max_blocks, int32_t n_tokens,
+                      const void* out) {
   if (!cfg_ok(cfg) || n_seqs < 0 || n_tokens < 0 || max_blocks < 1) return FSF_ERR_INVALID_ARG;
-  if (n_seqs == 0 && n_tokens == 0) return FSF_OK;
   if (!q || !k_cache || !v_cache || !descs_dev || !descs_host || !block_tables_dev || !out)
     return FSF_ERR_INVALID_ARG;
   if (!descs_ok(cfg, descs_host, n_seqs, max_blocks, n_tokens)) return FSF_ERR_INVALID_ARG;
   if (cfg->head_dim > 256) return FSF_ERR_UNSUPPORTED;
-  const size_t need = fsf_ragged_attention_workspace_bytes(cfg, n_seqs, n_tokens, max_blocks);
-  if (!workspace || workspace_bytes < need) return FSF_ERR_WORKSPACE;
+  return FSF_OK;
+}
+
+// The pass itself: arguments are valid, the workspace holds ws_layout(cfg, tn, ...).total bytes.
+int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, const void* k_cache,
+                  const void* v_cache, const fsf_seq_desc* descs_dev, const fsf_seq_desc* descs_host,
+                  const int32_t* block_tables_dev, int32_t n_seqs, int32_t max_blocks, int32_t n_tokens,
+                  void* out, void* workspace, void* hip_stream) {
 
   const Pass p = make_pass(cfg, descs_dev, block_tables_dev, n_seqs, max_blocks, n_tokens);
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -390,12 +397,11 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   }
   // Two rounds of the chip's 2048 wave slots: with the units launched longest first that is
   // balance enough, and every split costs partial results whose writes are expensive.
-  const Tuning tn = resolve_tuning(cfg);
   const int cus = tn.compute_units ? tn.compute_units : compute_units();
   const int min_item_blocks = tn.decode_min_item_blocks;
   int64_t target_items = tn.decode_target_waves / cfg->n_kv_heads;
-  if (target_items < 1) target_items = 1;
   if (target_items > tn.max_decode_items_extra) target_items = tn.max_decode_items_extra;
+  if (target_items < 1) target_items = 1;  // one item per row: no cuts
   int64_t sb = (dec_blocks + target_items - 1) / target_items;
   if (sb < 1) sb = 1;
 
@@ -451,4 +457,74 @@ extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, cons
   if (e == hipSuccess) e = fsf::launch_prefill_merge(p, f, out, stream);
   if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
+                                    const void* v_cache, const fsf_seq_desc* descs_dev,
+                                    const fsf_seq_desc* descs_host,
+                                    const int32_t* block_tables_dev, int32_t n_seqs,
+                                    int32_t max_blocks, int32_t n_tokens, void* out,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (cfg_ok(cfg) && n_seqs == 0 && n_tokens == 0) return FSF_OK;
+  const int st = attention_args_ok(cfg, q, k_cache, v_cache, descs_dev, descs_host, block_tables_dev, n_seqs,
+                                   max_blocks, n_tokens, out);
+  if (st != FSF_OK) return st;
+  const size_t need = fsf_ragged_attention_workspace_bytes(cfg, n_seqs, n_tokens, max_blocks);
+  if (!workspace || workspace_bytes < need) return FSF_ERR_WORKSPACE;
+  return run_attention(cfg, resolve_tuning(cfg), q, k_cache, v_cache, descs_dev, descs_host, block_tables_dev,
+                       n_seqs, max_blocks, n_tokens, out, workspace, hip_stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same pass for callers that may not allocate: the work tables and partial results live in
+// a fixed array in device memory that belongs to the library.  Every GPU the library runs on
+// holds its own copy of the array at its own address, found once per device.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)FSF_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` on device i, once known
+
+// Device address of this device's copy of `scratch` (the array's name is only a handle on the host).
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  g_scratch_ptr[dev].store(p, std::memory_order_release);
+  return p;
+}
+
+}  // namespace
+
+extern "C" int fsf_ragged_attention_static(const fsf_attn_cfg* cfg, const void* q, const void* k_cache,
+                                           const void* v_cache, const fsf_seq_desc* descs_dev,
+                                           const fsf_seq_desc* descs_host, const int32_t* block_tables_dev,
+                                           int32_t n_seqs, int32_t max_blocks, int32_t n_tokens, void* out,
+                                           void* hip_stream) {
+  if (cfg_ok(cfg) && n_seqs == 0 && n_tokens == 0) return FSF_OK;
+  const int st = attention_args_ok(cfg, q, k_cache, v_cache, descs_dev, descs_host, block_tables_dev, n_seqs,
+                                   max_blocks, n_tokens, out);
+  if (st != FSF_OK) return st;
+  Tuning tn = resolve_tuning(cfg);
+  if (fast_path_ok(cfg)) {
+    // partial results are what takes room: allow as many cut units as fit, down to none
+    tn.max_decode_items_extra = std::min(tn.max_decode_items_extra, 1024);
+    tn.max_prefill_split_units = std::min(tn.max_prefill_split_units, 64);
+    while (ws_layout(cfg, tn, n_seqs, n_tokens).total > kStaticScratchBytes) {
+      if (tn.max_decode_items_extra == 0 && tn.max_prefill_split_units == 0) return FSF_ERR_WORKSPACE;
+      tn.max_decode_items_extra /= 2;
+      tn.max_prefill_split_units /= 2;
+    }
+  }
+  void* ws = static_scratch();
+  if (!ws) return FSF_ERR_HIP;
+  return run_attention(cfg, tn, q, k_cache, v_cache, descs_dev, descs_host, block_tables_dev, n_seqs,
+                       max_blocks, n_tokens, out, ws, hip_stream);
 }

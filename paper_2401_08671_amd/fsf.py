@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
     L.fsf_ragged_attention_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
     L.fsf_ragged_attention.restype = C.c_int
     L.fsf_ragged_attention.argtypes = [cfgp, vp, vp, vp, descp, descp, i32p, i32, i32, i32, vp, vp, sz, vp]
+    L.fsf_ragged_attention_static.restype = C.c_int
+    L.fsf_ragged_attention_static.argtypes = [cfgp, vp, vp, vp, descp, descp, i32p, i32, i32, i32, vp, vp]
     L.fsf_sched_create.restype = C.c_int
     L.fsf_sched_create.argtypes = [C.POINTER(vp), i32, i32, i32, i64, vp]
     L.fsf_sched_destroy.restype = None
@@ -198,6 +200,14 @@ def ragged_attention(cfg: AttnCfg, q, k_cache, v_cache, batch: DeviceBatch, out,
                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
                                     _stream())
     _check(st, "fsf_ragged_attention")
+
+
+def ragged_attention_static(cfg: AttnCfg, q, k_cache, v_cache, batch: DeviceBatch, out) -> None:
+    """fsf_ragged_attention_static on torch's current stream: no workspace, nothing allocated."""
+    st = lib().fsf_ragged_attention_static(C.byref(cfg), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(batch.descs_dev),
+                                           C.c_void_p(batch.descs_host.ctypes.data), _ptr(batch.bt_dev), batch.n_seqs,
+                                           batch.max_blocks, batch.n_tokens, _ptr(out), _stream())
+    _check(st, "fsf_ragged_attention_static")
 
 
 def alloc_workspace(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int, device="cuda") -> torch.Tensor:

@@ -140,3 +140,22 @@ def test_rotary_append_validation_without_gpu():
     assert call(odd, 10) in (fsf.FSF_ERR_UNSUPPORTED, fsf.FSF_ERR_INVALID_ARG)
     # an empty pass is a no-op whatever the pointers
     assert L.fsf_kv_append_rotary(ctypes.byref(cfg), None, None, None, None, None, None, None, 0, 1, 0, None, 0, None) == fsf.FSF_OK
+
+
+def test_static_entry_point_refuses_on_the_host_what_does_not_fit_its_array():
+    """60 000 sequences at 64 query heads need one partial row each, far beyond 64 MiB: the call is
+    refused before any device call (the device pointers here are never dereferenced)."""
+    import numpy as np
+    L = fsf.lib()
+    n = 60_000
+    cfg = fsf.make_cfg(64, 8, 128, 64, "bf16", n)
+    descs = np.stack([np.ones(n), np.zeros(n), np.arange(n), np.arange(n)], axis=1).astype(np.int32)
+    fake = ctypes.c_void_p(0x1000)
+    st = L.fsf_ragged_attention_static(ctypes.byref(cfg), fake, fake, fake, fake, ctypes.c_void_p(descs.ctypes.data),
+                                       fake, n, 1, n, fake, None)
+    assert st == fsf.FSF_ERR_WORKSPACE
+    # and argument validation comes first
+    st = L.fsf_ragged_attention_static(ctypes.byref(cfg), None, fake, fake, fake, ctypes.c_void_p(descs.ctypes.data),
+                                       fake, n, 1, n, fake, None)
+    assert st == fsf.FSF_ERR_INVALID_ARG
+    assert L.fsf_ragged_attention_static(ctypes.byref(cfg), None, None, None, None, None, None, 0, 1, 0, None, None) == fsf.FSF_OK
