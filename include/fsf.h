@@ -89,6 +89,10 @@ typedef struct {
                                    /* KV head that may hold partial results (default 8192)               */
   int32_t max_prefill_split_units; /* bounds the workspace: (tile, head, part) workgroups with partial    */
                                    /* results, 139 KB each (default 512)                                 */
+  int32_t stream_chunk_slices;     /* a prompt chunk of at most this many slices of 16 / (query heads    */
+                                   /* per KV head) rows runs on the streaming kernel like generation      */
+                                   /* rows, every slice reading the chunk's K/V once (default 2, at most  */
+                                   /* 16; -1: only one-token sequences stream)                            */
 } fsf_tuning;
 
 /* One sequence of the pass (paper Sec. 2: tokens processed now vs tokens in the cache). */
@@ -237,9 +241,8 @@ int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_c
  * first call on that GPU until the process ends, and the call allocates and frees nothing.
  * The cutting of generation rows and prompt-chunk tiles into units with partial results is
  * limited to what fits the array (at most 1024 extra row units and 64 tile units, fewer for
- * passes with many sequences or heads); a pass whose tables alone exceed the array (tens of
- * thousands of sequences at many heads) is refused with FSF_ERR_WORKSPACE and nothing is
- * launched.  All calls on one GPU share the array: calls that overlap on one GPU (two
+ * passes with many heads); a pass whose work tables alone exceed the array (millions of
+ * tokens) is refused with FSF_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share the array: calls that overlap on one GPU (two
  * streams, two threads) race and give wrong results; calls on one stream, or ordered by
  * events, are safe.  The first call on a device looks the array's address up and should be
  * made outside a graph capture.  Errors otherwise as fsf_ragged_attention.

@@ -1,10 +1,18 @@
-// Device code for generation rows (n_new == 1): split-KV attention streaming the blocked cache once.
+// Device code for streaming sequences: generation rows (n_new == 1) and short prompt chunks;
+// split-KV attention streaming the blocked cache once.
 //
 // A generation pass adds one token and attends to the whole cached history (paper Sec. 2),
 // so every visible K/V byte is used exactly once per KV head: the kernel is bound by HBM
-// bandwidth.  One wavefront handles one (sequence, KV head, run of cache blocks); the
-// query heads that share the KV head (GQA group, up to 16) sit side by side in the N
-// dimension of the matrix-core tiles, so K/V are read once for the whole group.
+// bandwidth.  One wavefront handles one (sequence, slice of rows, KV head, run of cache
+// blocks); the query heads that share the KV head (GQA group, up to 16) sit side by side in the
+// N dimension of the matrix-core tiles, so K/V are read once for the whole group.
+//
+// Dynamic SplitFuse fills the token budget exactly, so a pass usually ends in a chunk of a few
+// rows of the next prompt, and the last chunk of a prompt is a short remainder over a long cached
+// prefix (Sec. 3.2).  Such a chunk costs its K/V bytes, not its flops, exactly like a generation
+// row, so its rows share the 16 columns with the heads: column n is (row n / group, head
+// n % group) of a slice of 16 / group consecutive rows, each column with its own causal
+// bound, and the slice's K/V are read once at streaming rate.
 //
 // Per step of 32 keys (two 16-key tiles a, b), with lane = (n = lane%16, kg = lane/16):
 //   S^T[key, head] = K[key, :] . Q[head, :]    8x mfma 16x16x32; A = K rows straight from
@@ -80,10 +88,13 @@ __device__ __forceinline__ void load_step(StepBuf& b, const T* __restrict__ kc,
     b.v[e] = load_frag8_stream(vb + ((e >> 2) * 16 + 4 * kg + (e & 3)) * kHeadDim + n * 8);
 }
 
+// [lo, hi]: keys the lane's column counts (its row's visible keys inside the unit); [nm_lo, nm_hi]:
+// keys that every column of the unit counts (a step inside needs no mask); [v_lo, v_hi]: keys that
+// any column counts (the V rows of all others are zeroed: they may be stale or not the unit's).
 template <int DT>
 __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f32x4_t (&acc)[8],
                                              float& m, float& l, float sl2, int key0, int lo,
-                                             int hi, int kg) {
+                                             int hi, int nm_lo, int nm_hi, int v_lo, int v_hi, int kg) {
   using M = Mma<DT>;
   f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -97,16 +108,13 @@ __device__ __forceinline__ void compute_step(StepBuf& b, const frag8 (&qf)[4], f
     s[r] = sa[r] * sl2;
     s[4 + r] = sb[r] * sl2;
   }
-  const bool boundary = key0 < lo || key0 + 31 > hi;  // uniform
+  const bool boundary = key0 < nm_lo || key0 + 31 > nm_hi;  // uniform
   if (boundary) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int key = key0 + (e >> 2) * 16 + 4 * kg + (e & 3);
-      const bool vis = key >= lo && key <= hi;
-      if (!vis) {
-        s[e] = -INFINITY;
-        b.v[e] = zero_frag8();
-      }
+      if (key < lo || key > hi) s[e] = -INFINITY;
+      if (key < v_lo || key > v_hi) b.v[e] = zero_frag8();
     }
   }
   float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -155,11 +163,12 @@ __device__ __forceinline__ void store_rows(char* dst, decode_lds_char* src, int 
     __builtin_nontemporal_store(*reinterpret_cast<lds_u4*>(src + off), reinterpret_cast<u4*>(dst + off));
 }
 
-// One wavefront: unit = item * n_kv_heads + kv head (item = a sequence's run of cache blocks).
-// stage: kDecodeStageBytes of LDS that belong to this wave alone.  hold: if not null, the
-// finished rows of an unsplit unit (g heads x 256 bytes) are left there instead of being
-// stored, and the byte offset in `out` where they belong is returned for the caller to store
-// them later; otherwise, and for units that write partial results, -1.
+// One wavefront: unit = item * n_kv_heads + kv head (item = a slice of a sequence's rows and a
+// run of its cache blocks).  stage: kDecodeStageBytes of LDS that belong to this wave alone.
+// hold: if not null, the finished rows of an uncut one-row unit (g heads x 256 bytes) are left
+// there instead of being stored, and the byte offset in `out` where they belong is returned for
+// the caller to store them later; otherwise, for units of several rows and for units that
+// write partial results, -1.
 template <int DT, typename T, bool kBlock16, bool kDouble = true>
 __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
                                                const T* __restrict__ kc, const T* __restrict__ vc,
@@ -170,30 +179,51 @@ __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f,
   const int hk = unit - slot * p.n_kv_heads;
   const int item = f.dec_order[slot];
   const int s = f.dec_item_seq[item];  // written by the planning kernel
-  const int split = item - f.dec_item_start[s];
   const fsf_seq_desc sd = p.descs[s];
   const int B = p.block_size;
-  int lo, hi;
-  visible_range(sd.n_cached, p.window, lo, hi);
-  const int b_lo = lo / B, b_hi = hi / B;
+  const int g = p.group;
+  // the sequence's key cuts: over the blocks any of its rows sees, the same for every slice
+  int lo_seq, hi_seq, tmp;
+  visible_range(sd.n_cached, p.window, lo_seq, tmp);
+  visible_range(sd.n_cached + sd.n_new - 1, p.window, tmp, hi_seq);
+  const int b_lo = lo_seq / B, b_hi = hi_seq / B;
   const int nblk = b_hi - b_lo + 1;
   const int n_splits = decode_splits(nblk, f.split_blocks, f.min_item_blocks);
+  const int idx = item - f.dec_item_start[s];  // slice-major
+  const int slice = idx / n_splits;
+  const int split = idx - slice * n_splits;
+  // the slice's rows, and the keys they see
+  const int rps = stream_rows_per_slice(g);
+  const int r0 = slice * rps;
+  const int rows = min(rps, sd.n_new - r0);  // >= 1
+  int lo_u, hi_u, lo_last;                   // keys any row sees; first key the last row sees
+  visible_range(sd.n_cached + r0, p.window, lo_u, tmp);
+  visible_range(sd.n_cached + r0 + rows - 1, p.window, lo_last, hi_u);
+  const int hi_first = sd.n_cached + r0;     // last key the first row sees
   // even cut: split k owns blocks [k*nblk/n_splits, (k+1)*nblk/n_splits), never empty
   const int blk0 = b_lo + (int)((int64_t)split * nblk / n_splits);
   const int blk1 = b_lo + (int)((int64_t)(split + 1) * nblk / n_splits) - 1;
-  const int key_begin = max(blk0 * B, lo & ~31);
-  const int key_end = min((blk1 + 1) * B - 1, hi);  // inclusive
+  const int key_begin = max(blk0 * B, lo_u & ~31);
+  const int key_end = min((blk1 + 1) * B - 1, hi_u);  // inclusive; below key_begin if no row of the slice sees the cut
   // keys this unit counts: a step may reach past them (into the next unit's blocks when the
   // block size is 16, past the window or the last token otherwise); those scores are masked
-  const int vis_lo = max(lo, key_begin), vis_hi = key_end;
+  const int vis_lo = max(lo_u, key_begin), vis_hi = key_end;
   const int32_t* bt = p.block_tables + (int64_t)s * p.max_blocks;
 
-  const int g = p.group;
-  const int hq = hk * g + n;
-  const bool col_live = n < g;
+  // column n = (row r0 + n / g, head hk * g + n % g)
+  const int r = n / g;
+  const int h = n - r * g;
+  const bool col_live = r < rows;
+  const int row = r0 + (col_live ? r : rows - 1);
+  const int hq = hk * g + (col_live ? h : 0);
+  int lo_n, hi_n;
+  visible_range(sd.n_cached + row, p.window, lo_n, hi_n);
+  lo_n = max(lo_n, vis_lo);
+  hi_n = min(hi_n, vis_hi);
+  const int nm_lo = max(lo_last, vis_lo), nm_hi = min(hi_first, vis_hi);
   frag8 qf[4];
   {
-    const T* qrow = q + ((int64_t)sd.q_offset * p.n_q_heads + (col_live ? hq : hk * g)) * kHeadDim;
+    const T* qrow = q + ((int64_t)(sd.q_offset + row) * p.n_q_heads + hq) * kHeadDim;
 #pragma unroll
     for (int t = 0; t < 4; ++t) qf[t] = col_live ? load_frag8(qrow + (4 * t + kg) * 8) : zero_frag8();
   }
@@ -203,6 +233,7 @@ __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f,
   float m = -1e30f, l = 0.f;
   const float sl2 = p.scale * 1.4426950408889634f;
 
+  if (key_end >= key_begin) {
   if constexpr (kDouble) {
   // Two register buffers.  The steady-state loop issues every load unconditionally, so the
   // compiler's in-order wait counts let step i compute while all of step i+1 is in flight.
@@ -213,18 +244,18 @@ __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f,
   for (; i + 2 < n_steps; i += 2) {
     const int key0 = key_begin + 32 * i;
     load_step<T, kBlock16>(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg, blk1);
-    compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
+    compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo_n, hi_n, nm_lo, nm_hi, vis_lo, vis_hi, kg);
     load_step<T, kBlock16>(b0, kc, vc, bt, key0 + 64, B, p.n_kv_heads, hk, n, kg, blk1);
-    compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, vis_lo, vis_hi, kg);
+    compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, lo_n, hi_n, nm_lo, nm_hi, vis_lo, vis_hi, kg);
   }
   {
     const int key0 = key_begin + 32 * i;
     if (n_steps - i == 2) {
       load_step<T, kBlock16>(b1, kc, vc, bt, key0 + 32, B, p.n_kv_heads, hk, n, kg, blk1);
-      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
-      compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, vis_lo, vis_hi, kg);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo_n, hi_n, nm_lo, nm_hi, vis_lo, vis_hi, kg);
+      compute_step<DT>(b1, qf, acc, m, l, sl2, key0 + 32, lo_n, hi_n, nm_lo, nm_hi, vis_lo, vis_hi, kg);
     } else {
-      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo_n, hi_n, nm_lo, nm_hi, vis_lo, vis_hi, kg);
     }
   }
 
@@ -233,59 +264,72 @@ __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f,
     StepBuf b0;
     for (int key0 = key_begin; key0 <= key_end; key0 += 32) {
       load_step<T, kBlock16>(b0, kc, vc, bt, key0, B, p.n_kv_heads, hk, n, kg, blk1);
-      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, vis_lo, vis_hi, kg);
+      compute_step<DT>(b0, qf, acc, m, l, sl2, key0, lo_n, hi_n, nm_lo, nm_hi, vis_lo, vis_hi, kg);
     }
+  }
   }
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
-  // acc[c][r] is output column d = (4kg + r)*8 + c of head n.  The rows of the group's g heads
-  // are adjacent in memory (out and the partial buffer alike): staged row-major in LDS, then
-  // written 16 bytes per lane, consecutive lanes to consecutive addresses.
+  // acc[c][r4] is output column d = (4kg + r4)*8 + c of column n.  The g heads of a row are
+  // adjacent in memory (out and the partial buffer alike): staged column-major in LDS (a row's
+  // heads side by side), then written 16 bytes per lane, consecutive lanes to consecutive addresses.
   typedef uint32_t stage_u4 __attribute__((ext_vector_type(4)));
   typedef float stage_f4 __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) stage_u4 lds_u4;
   typedef __attribute__((address_space(3))) stage_f4 lds_f4;
   if (n_splits == 1) {
-    decode_lds_char* rows = hold ? hold : stage;
+    // (a flag, not a comparison of the pointers: the staging area may sit at LDS address 0, which is
+    // also what a null LDS pointer compares equal to)
+    const bool held = hold && sd.n_new == 1;
+    decode_lds_char* staged = held ? hold : stage;
     if (col_live) {
       const float inv = 1.f / l;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r4 = 0; r4 < 4; ++r4) {
         stage_u4 w;
-        w.x = Mma<DT>::pack2(acc[0][r] * inv, acc[1][r] * inv);
-        w.y = Mma<DT>::pack2(acc[2][r] * inv, acc[3][r] * inv);
-        w.z = Mma<DT>::pack2(acc[4][r] * inv, acc[5][r] * inv);
-        w.w = Mma<DT>::pack2(acc[6][r] * inv, acc[7][r] * inv);
-        *reinterpret_cast<lds_u4*>(rows + n * (kHeadDim * 2) + (4 * kg + r) * 16) = w;
+        w.x = Mma<DT>::pack2(acc[0][r4] * inv, acc[1][r4] * inv);
+        w.y = Mma<DT>::pack2(acc[2][r4] * inv, acc[3][r4] * inv);
+        w.z = Mma<DT>::pack2(acc[4][r4] * inv, acc[5][r4] * inv);
+        w.w = Mma<DT>::pack2(acc[6][r4] * inv, acc[7][r4] * inv);
+        *reinterpret_cast<lds_u4*>(staged + n * (kHeadDim * 2) + (4 * kg + r4) * 16) = w;
       }
     }
     __builtin_amdgcn_wave_barrier();  // one wave: its LDS accesses complete in program order
-    const int64_t dst = ((int64_t)sd.q_offset * p.n_q_heads + hk * g) * kHeadDim * (int64_t)sizeof(T);
-    if (hold) return dst;
-    store_rows(reinterpret_cast<char*>(out) + dst, rows, g * kHeadDim * 2, lane);
+    const int64_t row_stride = (int64_t)p.n_q_heads * kHeadDim * (int64_t)sizeof(T);
+    const int64_t dst = ((int64_t)(sd.q_offset + r0) * p.n_q_heads + hk * g) * kHeadDim * (int64_t)sizeof(T);
+    if (held) return dst;
+    for (int rr = 0; rr < rows; ++rr)
+      store_rows(reinterpret_cast<char*>(out) + dst + rr * row_stride, staged + rr * g * (kHeadDim * 2), g * kHeadDim * 2, lane);
+    __builtin_amdgcn_wave_barrier();  // the staging area is reused by the wave's next unit
   } else {
-    const int64_t pi = (int64_t)item * p.n_q_heads + hq;
+    // partial row of (cut, row): dec_prow_start[s] + cut * n_new + row
+    const int64_t prow0 = (int64_t)f.dec_prow_start[s] + (int64_t)split * sd.n_new + r0;
     if (col_live) {
       if (kg == 0) {
+        const int64_t pi = (prow0 + r) * p.n_q_heads + hq;
         f.part_ml[pi * 2] = m;
         f.part_ml[pi * 2 + 1] = l;
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const stage_f4 lo4 = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
-        const stage_f4 hi4 = {acc[4][r], acc[5][r], acc[6][r], acc[7][r]};
-        *reinterpret_cast<lds_f4*>(stage + n * (kHeadDim * 4) + (4 * kg + r) * 32) = lo4;
-        *reinterpret_cast<lds_f4*>(stage + n * (kHeadDim * 4) + (4 * kg + r) * 32 + 16) = hi4;
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const stage_f4 lo4 = {acc[0][r4], acc[1][r4], acc[2][r4], acc[3][r4]};
+        const stage_f4 hi4 = {acc[4][r4], acc[5][r4], acc[6][r4], acc[7][r4]};
+        *reinterpret_cast<lds_f4*>(stage + n * (kHeadDim * 4) + (4 * kg + r4) * 32) = lo4;
+        *reinterpret_cast<lds_f4*>(stage + n * (kHeadDim * 4) + (4 * kg + r4) * 32 + 16) = hi4;
       }
     }
     __builtin_amdgcn_wave_barrier();
-    char* pbase = reinterpret_cast<char*>(f.part_acc + ((int64_t)item * p.n_q_heads + hk * g) * kHeadDim);
     const int n_bytes = g * kHeadDim * 4;
+    for (int rr = 0; rr < rows; ++rr) {
+      char* pbase = reinterpret_cast<char*>(f.part_acc + ((prow0 + rr) * p.n_q_heads + hk * g) * kHeadDim);
+      decode_lds_char* src = stage + rr * n_bytes;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {  // 1 KB = 2 heads per instruction
-      const int off = j * 1024 + lane * 16;
-      if (off < n_bytes) __builtin_nontemporal_store(*reinterpret_cast<lds_f4*>(stage + off), reinterpret_cast<stage_f4*>(pbase + off));
+      for (int j = 0; j < 8; ++j) {  // 1 KB = 2 heads per instruction
+        const int off = j * 1024 + lane * 16;
+        if (off < n_bytes) __builtin_nontemporal_store(*reinterpret_cast<lds_f4*>(src + off), reinterpret_cast<stage_f4*>(pbase + off));
+      }
     }
+    __builtin_amdgcn_wave_barrier();
   }
   return -1;
 }

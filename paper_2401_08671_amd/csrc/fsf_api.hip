@@ -75,7 +75,8 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace sections of the matrix-core path, in order.
 struct WsLayout {
-  size_t dec_item_start, pre_tile_start, dec_item_seq, dec_order, pre_tile_seq, split_seqs, part_ml, part_acc, pre_part, total;
+  size_t dec_item_start, pre_tile_start, dec_prow_start, dec_item_seq, dec_order, pre_tile_seq, split_rows, part_ml, part_acc, pre_part, total;
+  size_t items_cap, prow_cap;  // streaming items and partial-result rows the sections hold
 };
 
 // The caller's fsf_tuning with every default filled in.  Reads only the fields the caller's
@@ -85,6 +86,7 @@ struct Tuning {
   bool min_item_blocks_given, decode_hold, prefill_split;
   int compute_units;  // 0: ask the device (only when a launch needs it)
   int max_decode_items_extra, max_prefill_split_units;
+  int stream_max_slices;  // chunks of at most this many slices take the streaming kernel (0: one-row sequences only)
 };
 
 Tuning resolve_tuning(const fsf_attn_cfg* c) {
@@ -103,30 +105,47 @@ Tuning resolve_tuning(const fsf_attn_cfg* c) {
   r.max_decode_items_extra = t.max_decode_items_extra > 0 ? t.max_decode_items_extra : fsf::kMaxDecodeItemsExtra;
   r.max_prefill_split_units = t.max_prefill_split_units > 0 ? std::min(t.max_prefill_split_units, fsf::kMaxPrefillSplitUnits)
                                                             : fsf::kMaxPrefillSplitUnits;
+  r.stream_max_slices = t.stream_chunk_slices > 0 ? std::min(t.stream_chunk_slices, fsf::kMaxStreamSlices)
+                                                  : (t.stream_chunk_slices < 0 ? 0 : fsf::kDefaultStreamSlices);
   return r;
 }
 
+// Streaming items a pass is cut into beyond one per slice: about target_waves wave units in all.
+int64_t decode_target_items(const fsf_attn_cfg* c, const Tuning& tn) {
+  int64_t t = tn.decode_target_waves / c->n_kv_heads;
+  if (t > tn.max_decode_items_extra) t = tn.max_decode_items_extra;
+  return t;  // may be 0: no cuts
+}
+
 WsLayout ws_layout(const fsf_attn_cfg* c, const Tuning& tn, int32_t n_seqs, int32_t n_tokens) {
-  const size_t items_cap = (size_t)n_seqs + tn.max_decode_items_extra;
-  const size_t tiles_cap = (size_t)n_seqs + (size_t)n_tokens / fsf::kPrefillTileM;
   WsLayout w;
+  // every slice of every streaming sequence is an item (at most one per token), plus the cuts
+  w.items_cap = (size_t)n_tokens + (size_t)n_seqs + (size_t)decode_target_items(c, tn);
+  // Rows whose keys are cut hold one partial result per cut.  Generation rows alone need at most
+  // twice the extra items; short chunks bring up to 16 rows per item, so room for 16 per extra
+  // item is kept, but never more than twice the limit on extra items: the host coarsens the cuts
+  // of a pass that would need more.
+  w.prow_cap = std::min<size_t>((size_t)fsf::kStreamCols * decode_target_items(c, tn), 2 * (size_t)tn.max_decode_items_extra);
+  const size_t tiles_cap = (size_t)n_seqs + (size_t)n_tokens / fsf::kPrefillTileM;
   size_t off = 0;
   w.dec_item_start = off;
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
   w.pre_tile_start = off;
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
+  w.dec_prow_start = off;
+  off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
   w.dec_item_seq = off;
-  off += align256(items_cap * sizeof(int32_t));
+  off += align256(w.items_cap * sizeof(int32_t));
   w.dec_order = off;
-  off += align256(items_cap * sizeof(int32_t));
+  off += align256(w.items_cap * sizeof(int32_t));
   w.pre_tile_seq = off;
   off += align256(tiles_cap * sizeof(int32_t));
-  w.split_seqs = off;
-  off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
+  w.split_rows = off;
+  off += align256(((size_t)n_tokens + 1) * 2 * sizeof(int32_t));
   w.part_ml = off;
-  off += align256(items_cap * c->n_q_heads * 2 * sizeof(float));
+  off += align256(w.prow_cap * c->n_q_heads * 2 * sizeof(float));
   w.part_acc = off;
-  off += align256(items_cap * c->n_q_heads * fsf::kHeadDim * sizeof(float));
+  off += align256(w.prow_cap * c->n_q_heads * fsf::kHeadDim * sizeof(float));
   // partial results of split prompt-chunk tiles: at most kMaxPrefillSplitUnits (tile, head, part) workgroups
   const size_t split_units = std::min<size_t>(tn.max_prefill_split_units, tiles_cap * c->n_q_heads * 16);
   w.pre_part = off;
@@ -211,10 +230,10 @@ fsf::PrefillSplit plan_prefill_split(const std::vector<int>& n_steps, int H, int
 }
 
 // 64-key steps of every prompt-chunk tile of the pass, in tile order (sequence order, then rows)
-std::vector<int> prefill_tile_steps_of(const fsf_attn_cfg* c, const fsf_seq_desc* h, int32_t n_seqs) {
+std::vector<int> prefill_tile_steps_of(const fsf_attn_cfg* c, const Tuning& tn, const fsf_seq_desc* h, int32_t n_seqs) {
   std::vector<int> steps;
   for (int32_t s = 0; s < n_seqs; ++s) {
-    if (h[s].n_new == 1) continue;
+    if (fsf::is_streaming(h[s].n_new, c->n_q_heads / c->n_kv_heads, tn.stream_max_slices)) continue;
     for (int i0 = 0; i0 < h[s].n_new; i0 += fsf::kPrefillTileM)
       steps.push_back(fsf::prefill_tile_steps(h[s].n_cached, i0, std::min(i0 + fsf::kPrefillTileM, h[s].n_new),
                                               c->window));
@@ -228,7 +247,7 @@ bool fused_launch(const fsf_attn_cfg* c) { return (c->flags & FSF_FLAG_FUSED_LAU
 fsf::PrefillSplit choose_prefill_split(const fsf_attn_cfg* c, const Tuning& tn, const fsf_seq_desc* h, int32_t n_seqs) {
   const int cus = tn.compute_units ? tn.compute_units : compute_units();  // tests force splits with a small value
   const bool allow = !fused_launch(c) && tn.prefill_split;
-  return plan_prefill_split(prefill_tile_steps_of(c, h, n_seqs), c->n_q_heads, cus, allow, tn.max_prefill_split_units);
+  return plan_prefill_split(prefill_tile_steps_of(c, tn, h, n_seqs), c->n_q_heads, cus, allow, tn.max_prefill_split_units);
 }
 
 }  // namespace
@@ -252,7 +271,7 @@ extern "C" int32_t fsf_plan_prefill_groups(const fsf_attn_cfg* cfg, const fsf_se
                                            int32_t* groups_out, int32_t cap) {
   if (!cfg_ok(cfg) || !descs_host || n_seqs < 0 || compute_units_assumed < 1 || (cap > 0 && !groups_out))
     return -1;
-  const std::vector<int> steps = prefill_tile_steps_of(cfg, descs_host, n_seqs);
+  const std::vector<int> steps = prefill_tile_steps_of(cfg, resolve_tuning(cfg), descs_host, n_seqs);
   const fsf::PrefillSplit sp = plan_prefill_split(steps, cfg->n_q_heads, compute_units_assumed, true);
   const int n = fsf::prefill_groups((int)steps.size(), sp);
   for (int g = 0; g < n && g < cap; ++g) {
@@ -386,22 +405,23 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
   }
   if (((uintptr_t)workspace & 255) != 0) return FSF_ERR_WORKSPACE;
 
-  // ---- size the decode splits: enough items to fill the chip a few times over, few enough
-  // that the partial results stay small next to the K/V traffic
-  int64_t dec_blocks = 0;
+  // ---- size the key cuts of the streaming sequences: enough items to fill the chip a few
+  // times over, few enough that the partial results stay small next to the K/V traffic
+  const int group = cfg->n_q_heads / cfg->n_kv_heads;
+  int64_t dec_blocks = 0;  // cache blocks over all streaming units (every slice walks its sequence's blocks)
   for (int32_t s = 0; s < n_seqs; ++s) {
-    if (descs_host[s].n_new != 1) continue;
-    int lo, hi;
-    fsf::visible_range(descs_host[s].n_cached, cfg->window, lo, hi);
-    dec_blocks += hi / cfg->block_size - lo / cfg->block_size + 1;
+    const fsf_seq_desc& d = descs_host[s];
+    if (!fsf::is_streaming(d.n_new, group, tn.stream_max_slices)) continue;
+    int lo, hi, tmp;
+    fsf::visible_range(d.n_cached, cfg->window, lo, tmp);
+    fsf::visible_range(d.n_cached + d.n_new - 1, cfg->window, tmp, hi);
+    dec_blocks += (int64_t)fsf::stream_slices(d.n_new, group) * (hi / cfg->block_size - lo / cfg->block_size + 1);
   }
   // Two rounds of the chip's 2048 wave slots: with the units launched longest first that is
-  // balance enough, and every split costs partial results whose writes are expensive.
+  // balance enough, and every cut costs partial results whose writes are expensive.
   const int cus = tn.compute_units ? tn.compute_units : compute_units();
   const int min_item_blocks = tn.decode_min_item_blocks;
-  int64_t target_items = tn.decode_target_waves / cfg->n_kv_heads;
-  if (target_items > tn.max_decode_items_extra) target_items = tn.max_decode_items_extra;
-  if (target_items < 1) target_items = 1;  // one item per row: no cuts
+  const int64_t target_items = std::max<int64_t>(decode_target_items(cfg, tn), 1);  // 1: one item per slice, no cuts
   int64_t sb = (dec_blocks + target_items - 1) / target_items;
   if (sb < 1) sb = 1;
 
@@ -410,39 +430,45 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
   fsf::FastPlan f;
   f.dec_item_start = (int32_t*)(ws + w.dec_item_start);
   f.pre_tile_start = (int32_t*)(ws + w.pre_tile_start);
+  f.dec_prow_start = (int32_t*)(ws + w.dec_prow_start);
   f.dec_item_seq = (int32_t*)(ws + w.dec_item_seq);
   f.dec_order = (int32_t*)(ws + w.dec_order);
   f.pre_tile_seq = (int32_t*)(ws + w.pre_tile_seq);
-  f.split_seqs = (int32_t*)(ws + w.split_seqs);
+  f.split_rows = (int32_t*)(ws + w.split_rows);
   f.part_ml = (float*)(ws + w.part_ml);
   f.part_acc = (float*)(ws + w.part_acc);
-  f.split_blocks = (int32_t)sb;
+  f.split_blocks = (int32_t)std::min<int64_t>(sb, 1 << 30);
   f.min_item_blocks = min_item_blocks;
-  int64_t n_dec = 0, n_pre = 0;
-  int32_t n_split = 0;
+  f.stream_max_slices = tn.stream_max_slices;
+  int64_t n_dec = 0, n_pre = 0, n_split_rows = 0, n_prows = 0;
   auto count_work = [&] {
-    n_dec = n_pre = 0;
-    n_split = 0;
+    n_dec = n_pre = n_split_rows = n_prows = 0;
     for (int32_t s = 0; s < n_seqs; ++s) {
-      int d, t;
-      fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
-                    f.split_blocks, f.min_item_blocks, d, t);
-      n_dec += d;
-      n_pre += t;
-      n_split += d > 1;
+      const fsf::SeqWork sw = fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
+                                            group, f.stream_max_slices, f.split_blocks, f.min_item_blocks);
+      n_dec += sw.dec_items;
+      n_pre += sw.pre_tiles;
+      n_split_rows += sw.cuts > 1 ? descs_host[s].n_new : 0;
+      n_prows += sw.prows;
     }
   };
   count_work();
-  // A pass with so few generation rows that not even every compute unit gets a wave (one
+  // A pass with so few streaming units that not even every compute unit gets a wave (one
   // long sequence alone, say) is bound by the latency of its longest unit: cut four times finer.
   if (n_dec * cfg->n_kv_heads < cus && !tn.min_item_blocks_given) {
     f.min_item_blocks = std::max(1, min_item_blocks / 4);
     count_work();
   }
-  if (n_dec > (int64_t)n_seqs + tn.max_decode_items_extra) return FSF_ERR_WORKSPACE;  // cannot happen
+  // the partial results must fit their section: coarsen the cuts until they do (with cuts as
+  // long as the longest sequence nothing is cut and nothing is needed)
+  while (n_prows > (int64_t)w.prow_cap && f.split_blocks < (1 << 30)) {
+    f.split_blocks *= 2;
+    count_work();
+  }
+  if (n_prows > (int64_t)w.prow_cap || n_dec > (int64_t)w.items_cap) return FSF_ERR_WORKSPACE;  // cannot happen
   f.n_dec_items = (int32_t)n_dec;
   f.n_pre_tiles = (int32_t)n_pre;
-  f.n_split_seqs = n_split;
+  f.n_split_rows = (int32_t)n_split_rows;
   f.pre_part = (float*)(ws + w.pre_part);
   f.split = choose_prefill_split(cfg, tn, descs_host, n_seqs);
   f.decode_hold = tn.decode_hold;

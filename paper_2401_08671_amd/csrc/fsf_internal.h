@@ -50,12 +50,19 @@ __device__ __forceinline__ int32_t load_uniform_i32(const int32_t* ptr) {
 //
 // Work is cut on the device by a one-workgroup planning kernel; the host evaluates the
 // same formulas on its copy of the descriptors to size the grids.
-//   generation rows (n_new == 1): "items" = (sequence, run of split_blocks cache blocks)
-//   prompt chunks   (n_new  > 1): "tiles" = (sequence, kPrefillTileM consecutive rows)
+//   streaming sequences: generation rows (n_new == 1) and short prompt chunks, the 2..30-row
+//     chunks and remainders that filling the token budget exactly produces (paper Sec. 3.2):
+//     "items" = (sequence, slice of rows, run of about split_blocks cache blocks).  A slice is
+//     as many consecutive rows as fit, with the query heads of one KV head, into the 16 columns
+//     of a streaming unit (16 / group rows); a chunk of at most stream_max_slices slices streams
+//   other prompt chunks: "tiles" = (sequence, kPrefillTileM consecutive rows)
 // ---------------------------------------------------------------------------------------
 constexpr int kHeadDim = 128;
 constexpr int kPrefillTileM = 256;   // query rows per prefill workgroup (4 waves x 64 rows)
 constexpr int kMaxDecodeItemsExtra = 8192;  // items beyond one per sequence (bounds the workspace)
+constexpr int kStreamCols = 16;             // (row, query head) columns of a streaming unit
+constexpr int kMaxStreamSlices = 16;        // upper limit of stream_max_slices
+constexpr int kDefaultStreamSlices = 2;     // chunks of up to 2 slices stream by default
 // Prompt-chunk tiles may have their key range cut into parts, one workgroup each, which store
 // unnormalised partial results that a merge kernel combines.  Two cases (decided on the host
 // from counts and step numbers, passed by value):
@@ -88,20 +95,38 @@ __host__ __device__ inline int decode_splits(int nblk, int split_blocks, int min
   return want < cap ? want : cap;
 }
 
-// Number of decode items / prefill tiles a sequence contributes.
-__host__ __device__ inline void seq_work(int n_new, int n_cached, int window, int block_size,
-                                         int split_blocks, int min_item_blocks, int& dec_items,
-                                         int& pre_tiles) {
-  if (n_new == 1) {
-    int lo, hi;
-    visible_range(n_cached, window, lo, hi);
+// Rows of a streaming sequence per unit, and the units ("slices") its rows take.
+__host__ __device__ inline int stream_rows_per_slice(int group) { return kStreamCols / group; }
+__host__ __device__ inline int stream_slices(int n_new, int group) {
+  const int rps = stream_rows_per_slice(group);
+  return (n_new + rps - 1) / rps;
+}
+// Does the sequence take the streaming kernel (else its rows are tiled for the matrix-core kernel)?
+__host__ __device__ inline bool is_streaming(int n_new, int group, int max_slices) {
+  return n_new == 1 || stream_slices(n_new, group) <= max_slices;
+}
+
+// What a sequence contributes: streaming items (slices x key cuts), prompt-chunk tiles, and
+// partial-result rows (cuts x rows, for sequences whose keys are cut at all).  The key cuts are
+// taken over the cache blocks that any row of the sequence sees; every slice uses the same cuts.
+struct SeqWork {
+  int dec_items, pre_tiles, cuts, prows;
+};
+__host__ __device__ inline SeqWork seq_work(int n_new, int n_cached, int window, int block_size, int group,
+                                            int max_slices, int split_blocks, int min_item_blocks) {
+  SeqWork w = {0, 0, 0, 0};
+  if (is_streaming(n_new, group, max_slices)) {
+    int lo, hi, tmp;
+    visible_range(n_cached, window, lo, tmp);
+    visible_range(n_cached + n_new - 1, window, tmp, hi);
     const int nblk = hi / block_size - lo / block_size + 1;
-    dec_items = decode_splits(nblk, split_blocks, min_item_blocks);
-    pre_tiles = 0;
+    w.cuts = decode_splits(nblk, split_blocks, min_item_blocks);
+    w.dec_items = stream_slices(n_new, group) * w.cuts;
+    w.prows = w.cuts > 1 ? w.cuts * n_new : 0;
   } else {
-    dec_items = 0;
-    pre_tiles = (n_new + kPrefillTileM - 1) / kPrefillTileM;
+    w.pre_tiles = (n_new + kPrefillTileM - 1) / kPrefillTileM;
   }
+  return w;
 }
 
 struct PrefillSplit {
@@ -194,18 +219,20 @@ __host__ __device__ inline int prefill_tile_steps(int n_cached, int i0, int i1, 
 }
 
 struct FastPlan {
-  int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of decode items per sequence
+  int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of streaming items per sequence
   int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
-  int32_t* dec_item_seq;    // [items]  sequence index of every decode item
-  int32_t* dec_order;       // [items]  launch slot -> decode item, items with the most cache blocks first
+  int32_t* dec_prow_start;  // [n_seqs + 1] exclusive prefix of partial-result rows per sequence
+  int32_t* dec_item_seq;    // [items]  sequence index of every streaming item
+  int32_t* dec_order;       // [items]  launch slot -> streaming item, items with the most cache blocks first
   int32_t* pre_tile_seq;    // [tiles]  sequence index of every prefill tile
-  int32_t* split_seqs;      // [n_split_seqs] sequences whose generation row was cut into > 1 item
-  float* part_ml;           // [items, n_q_heads, 2]   running max (log2 domain) and sum per split
-  float* part_acc;          // [items, n_q_heads, 128] unnormalised outputs per split
+  int32_t* split_rows;      // [n_split_rows, 2] (sequence, row) of every row whose keys were cut
+  float* part_ml;           // [partial rows, n_q_heads, 2]   running max (log2 domain) and sum per cut
+  float* part_acc;          // [partial rows, n_q_heads, 128] unnormalised outputs per cut
   float* pre_part;          // [slab, 256 rows, n_q_heads, 136] partial results of split tiles
-  int32_t split_blocks;     // target cache blocks per decode item
-  int32_t min_item_blocks;  // no split leaves an item with fewer blocks than this
-  int32_t n_dec_items, n_pre_tiles, n_split_seqs;  // host-side totals (grid sizes)
+  int32_t split_blocks;     // target cache blocks per streaming item
+  int32_t min_item_blocks;  // no cut leaves an item with fewer blocks than this
+  int32_t stream_max_slices;  // chunks of at most this many slices take the streaming kernel
+  int32_t n_dec_items, n_pre_tiles, n_split_rows;  // host-side totals (grid sizes)
   PrefillSplit split;       // which prompt-chunk tiles are cut along their keys
   int32_t decode_hold;      // host side: streaming waves may hold finished rows back (see attn_decode_kernel)
 };

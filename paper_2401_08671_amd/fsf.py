@@ -32,7 +32,8 @@ class Tuning(C.Structure):
     _fields_ = [("struct_bytes", C.c_int32), ("decode_target_waves", C.c_int32),
                 ("decode_min_item_blocks", C.c_int32), ("decode_hold", C.c_int32),
                 ("prefill_split", C.c_int32), ("compute_units", C.c_int32),
-                ("max_decode_items_extra", C.c_int32), ("max_prefill_split_units", C.c_int32)]
+                ("max_decode_items_extra", C.c_int32), ("max_prefill_split_units", C.c_int32),
+                ("stream_chunk_slices", C.c_int32)]
 
     def __init__(self, **kw):
         super().__init__(**kw)

@@ -143,11 +143,11 @@ def test_rotary_append_validation_without_gpu():
 
 
 def test_static_entry_point_refuses_on_the_host_what_does_not_fit_its_array():
-    """60 000 sequences at 64 query heads need one partial row each, far beyond 64 MiB: the call is
-    refused before any device call (the device pointers here are never dereferenced)."""
+    """The work tables of three million one-token sequences exceed 64 MiB: the call is refused
+    before any device call (the device pointers here are never dereferenced)."""
     import numpy as np
     L = fsf.lib()
-    n = 60_000
+    n = 3_000_000
     cfg = fsf.make_cfg(64, 8, 128, 64, "bf16", n)
     descs = np.stack([np.ones(n), np.zeros(n), np.arange(n), np.arange(n)], axis=1).astype(np.int32)
     fake = ctypes.c_void_p(0x1000)

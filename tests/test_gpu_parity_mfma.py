@@ -219,6 +219,72 @@ def test_every_part_of_a_split_tile_counts(units, window):
         assert np.abs(out_h[r, 0] - v).max() <= 2.0 ** -8 * np.abs(v).max(), f"row {r}, key {pos}"
 
 
+SHORT_PREFIXES = [0, 5, 63, 64, 700, 31, 1, 129]
+
+
+@pytest.mark.parametrize("group", [1, 4, 8, 16])
+@pytest.mark.parametrize("window", [0, 100])
+@pytest.mark.parametrize("block", [16, 64])
+def test_short_chunks_on_the_streaming_kernel(group, window, block):
+    """Chunks of 2..17 rows (what filling the token budget exactly leaves at the end of a pass,
+    and the remainders of prompts) run on the streaming kernel with (row, head) pairs in the 16
+    columns of a unit, every column with its own causal and window bound: one slice for 16 / group
+    rows, several slices beyond.  Interleaved with an ordinary chunk and generation rows."""
+    seqs = []
+    for n in range(2, 18):
+        seqs.append((n, SHORT_PREFIXES[n % len(SHORT_PREFIXES)]))
+        if n % 5 == 0:
+            seqs.append((1, 40 * n))
+    seqs.insert(7, (300, 90))
+    spec = wl.BatchSpec("short", 2 * group, 2, 128, block, "bf16" if group != 4 else "f16", seqs, window=window, seed=60 + group)
+    tn = fsf.Tuning(stream_chunk_slices=16)
+    check_step(Step(spec, poison="nan"), f"short chunks g={group} W={window} B={block}", tuning=tn)
+
+
+@pytest.mark.parametrize("slices", [-1, 0, 1, 3])
+def test_short_chunks_either_kernel_gives_the_oracle_result(slices):
+    """The same pass with short chunks on the tiled kernel (-1), by the default rule (0: up to two
+    slices stream) and with other limits."""
+    seqs = [(2, 1000), (1, 77), (8, 3), (9, 640), (16, 0), (17, 200), (31, 64), (40, 500), (1, 0)]
+    spec = wl.BatchSpec("either", 8, 2, 128, 64, "bf16", seqs, seed=66)
+    check_step(Step(spec, poison="nan"), f"stream_chunk_slices={slices}", tuning=fsf.Tuning(stream_chunk_slices=slices))
+
+
+@pytest.mark.parametrize("group,window,block", [(1, 0, 64), (4, 0, 64), (4, 3000, 16), (16, 0, 64)])
+def test_short_chunks_with_cut_keys_every_cut_counts(group, window, block):
+    """Short chunks over long prefixes whose keys are cut into units of 128 keys with partial results
+    for every (cut, row): rows of a slice see different numbers of cuts (a cut past a row's own
+    position holds nothing for it), early slices see none of the last cuts.  One key in every
+    third cut is made dominant for one row of the chunk in turn."""
+    n, c = 14, 5000
+    spec = wl.BatchSpec("shortcut", 2 * group, 2, 128, block, "bf16", [(n, c), (1, 300), (5, 4990), (n, 70)],
+                        window=window, seed=70 + group)
+    st = Step(spec, poison="nan")
+    plants = []
+    for k in range(12):
+        r = (5 * k) % n
+        lo = max(0, c + r - window + 1) if window else 0
+        pos = lo + (c + r - lo) * k // 11
+        plants.append((r, pos, plant_dominant_key(st, 0, r, 0, pos)))
+    tn = fsf.Tuning(stream_chunk_slices=16, decode_target_waves=1 << 20, decode_min_item_blocks=128 // block)
+    _, _, out_o = st.oracle()
+    _, _, out_h = run_hip(st, tuning=tn, return_cache=False)
+    assert_outputs_close(out_h, out_o, "bf16", f"short chunk with cut keys g={group} W={window} B={block}")
+    for r, pos, v in plants[-3:]:          # the last plants of a row are the ones no later plant overrides
+        assert np.abs(out_o[r, 0] - v).max() <= 1e-6 * np.abs(v).max(), "the plant did not take"
+        assert np.abs(out_h[r, 0] - v).max() <= 2.0 ** -8 * np.abs(v).max(), f"row {r}, key {pos}"
+
+
+def test_thousands_of_two_row_chunks():
+    """Many short chunks and generation rows: more streaming units than wave slots, so waves walk
+    several units each; one-row units hold their results back, chunk units store at once."""
+    rng = np.random.default_rng(77)
+    seqs = [((2 if i % 3 else 1), int(c)) for i, c in enumerate(rng.integers(0, 150, size=2400))]
+    seqs[11] = (3, 4000)
+    spec = wl.BatchSpec("manyshort", 4, 4, 128, 64, "bf16", seqs, seed=77)
+    check_step(Step(spec, poison="nan"), "2400 short sequences")
+
+
 @pytest.mark.parametrize("flags", [0, fsf.FSF_FLAG_FUSED_LAUNCH])
 def test_mixed_batch_order_independent(flags):
     """Chunks and generations interleaved in any order (the kernels may not assume chunks come first);

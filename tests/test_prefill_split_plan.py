@@ -12,10 +12,11 @@ def plan(seqs, H=40, cus=256, window=0):
 
 
 def tiles_of(seqs):
-    """(sequence, first row, one past last row) of every 256-row tile, in tile order"""
+    """(sequence, first row, one past last row) of every 256-row tile, in tile order.  Chunks of at
+    most two slices of 16 rows (one query head per KV head here) run on the streaming kernel."""
     out = []
     for s, (n, c) in enumerate(seqs):
-        if n > 1:
+        if n > 32:
             out += [(s, i0, min(i0 + 256, n)) for i0 in range(0, n, 256)]
     return out
 
@@ -97,6 +98,20 @@ def test_random_batches_partition(seed):
         lo = max(0, c + i0 - cfgw + 1) if cfgw else 0
         steps = (c + i1 - 1 - (lo & ~63)) // 64 + 1
         assert steps // parts[t] >= 8 or parts[t] == 1
+
+
+def test_short_chunks_are_not_tiled():
+    """chunks that fit two streaming slices (32 rows at one query head per KV head, 8 rows at four)
+    leave the tiled kernel; the limit is a tuning field"""
+    seqs = [(32, 5000), (33, 5000), (2, 0), (1, 9)]
+    assert sorted(set(plan(seqs, H=8)[:, 0].tolist())) == [0]            # only the 33-row chunk
+    def plan_with(hq, hkv, tuning=None):
+        cfg = fsf.make_cfg(hq, hkv, 128, 64, "bf16", 1 << 20, tuning=tuning)
+        return len(set(fsf.plan_prefill_groups(cfg, wl.make_descs([(8, 100), (9, 100), (40, 0)]), 256)[:, 0].tolist()))
+    assert plan_with(8, 2) == 2                                           # 4 rows per slice: 9 and 40 rows are tiled
+    assert plan_with(8, 2, fsf.Tuning(stream_chunk_slices=-1)) == 3
+    assert plan_with(8, 2, fsf.Tuning(stream_chunk_slices=3)) == 1
+    assert plan_with(8, 2, fsf.Tuning(stream_chunk_slices=16)) == 0
 
 
 def test_a_lone_remainder_fills_one_round_and_no_more():

@@ -49,16 +49,16 @@ def run_both(spec, tuning_kw):
 
 
 def test_static_entry_point_equals_the_workspace_one_on_two_calls_in_a_row():
-    # first pass: generation rows cut into many units (partial results + merge), a chunk whose
-    # tiles are cut along their keys, short rows, a second chunk; 8 query heads on 2 KV heads
+    # first pass: generation rows and a short chunk cut into many units (partial results + merge), a
+    # chunk whose tiles are cut along their keys, short rows, a second chunk; 8 query heads on 2 KV heads
     big = wl.BatchSpec("static-big", 8, 2, 128, 64, "bf16",
-                       [(1, 9000), (700, 1500), (1, 63), (1, 64), (300, 2100), (1, 2500), (1, 0), (40, 3)], seed=51)
+                       [(1, 9000), (700, 1500), (1, 63), (1, 64), (300, 2100), (1, 2500), (1, 0), (40, 3), (7, 6000)], seed=51)
     tune = dict(decode_target_waves=1 << 20, decode_min_item_blocks=2, compute_units=64)
     a, b, ref = run_both(big, tune)
     assert torch.equal(a, b), "first call differs from fsf_ragged_attention"
     assert_outputs_close(b.to(torch.float64).cpu().numpy(), ref, "bf16", "static entry point, first call")
     # second pass, smaller: fewer sequences, fewer units, another head grouping and a window
-    small = wl.BatchSpec("static-small", 4, 4, 128, 64, "bf16", [(1, 3000), (260, 700), (1, 5)], window=1000, seed=52)
+    small = wl.BatchSpec("static-small", 4, 4, 128, 64, "bf16", [(1, 3000), (260, 700), (1, 5), (3, 2000)], window=1000, seed=52)
     a, b, ref = run_both(small, tune)
     assert torch.equal(a, b), "second call differs from fsf_ragged_attention"
     assert_outputs_close(b.to(torch.float64).cpu().numpy(), ref, "bf16", "static entry point, second call")
