@@ -256,10 +256,13 @@ def shape_report(config: int, steps: int, warmup: int, n_decode_check: int, with
     return rep, ds
 
 
-def stream_report(warmup: int, check: bool):
-    """Benchmark shape 5: 200 consecutive passes of the long-prompt stream, batches from fsf_compose_batch."""
+def stream_report(warmup: int, check: bool, rate: float = 1.0, warm_passes: int = 0):
+    """Benchmark shape 5: 200 consecutive passes of the long-prompt stream, batches from fsf_compose_batch.
+    rate: mean arrivals per pass (Poisson).  warm_passes: that many passes are run, untimed, before
+    the 200 timed ones, so that the timed ones see the generations of a stream in progress instead
+    of the ramp from an empty server."""
     n_steps = 200
-    run = StreamRunner(n_steps=n_steps, rate=1.0)
+    run = StreamRunner(n_steps=n_steps + warm_passes, rate=rate)
     # one fixed set of new-token tensors, sliced per pass (values do not affect timing)
     q_all, k_all, v_all = run.new_tokens(0, run.budget)
     warm = DeviceStep(wl.config(2, n_decodes=8))          # load the kernels before timing
@@ -267,11 +270,17 @@ def stream_report(warmup: int, check: bool):
         warm.step()
     torch.cuda.synchronize()
     del warm
+    for _ in range(warm_passes):                       # untimed: the stream before the timed window
+        descs, tables, _ = run.compose()
+        T = int(descs[:, 0].sum()) if len(descs) else 0
+        run.run_pass(descs, tables, q_all[:T], k_all[:T], v_all[:T])
+        run.commit()
     fsf.profile_enable(True)
     fsf.profile_read()
     per_step = []
     t_compose = 0.0
     last = None
+    n_rows_max = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for step in range(n_steps):
@@ -284,6 +293,7 @@ def stream_report(warmup: int, check: bool):
         spec = wl.BatchSpec(f"pass{step}", run.Hq, run.Hkv, run.d, run.B, run.dtype,
                             [(int(n), int(c)) for n, c, _, _ in descs])
         per_step.append((T, algorithmic_work(spec) if T else None))
+        n_rows_max = max(n_rows_max, sum(1 for n, _, _, _ in descs if n == 1))
         last = (descs, tables, T)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -300,9 +310,11 @@ def stream_report(warmup: int, check: bool):
     wall_ms = (t1 - t0) * 1e3
     rep = {
         "workload": (f"cfg5-13b-stream: Hq={run.Hq} Hkv={run.Hkv} d={run.d} block={run.B} budget={run.budget}, "
-                     f"{n_steps} consecutive passes composed by fsf_compose_batch, {len(run.requests)} requests "
-                     "(log-normal prompts, Poisson(1.0) arrivals per pass), one layer; wall clock includes "
-                     "host composition and descriptor upload"),
+                     f"{n_steps} consecutive passes composed by fsf_compose_batch"
+                     + (f" after {warm_passes} untimed passes of the same stream" if warm_passes else "") +
+                     f", {len(run.requests)} requests (log-normal prompts, Poisson({rate}) arrivals per pass), one layer; "
+                     "wall clock includes host composition and descriptor upload"),
+        "arrival_rate_per_pass": rate, "warm_passes": warm_passes, "generation_rows_per_pass_max": n_rows_max,
         "total_tokens": total_tokens, "kv_pool_blocks": run.num_blocks, "passes": n_steps,
         "ms_per_step": wall_ms / n_steps, "tokens_per_s": total_tokens / (t1 - t0),
         "gpu_kernel_ms_total": gpu_ms, "gpu_tokens_per_s": total_tokens / (gpu_ms * 1e-3),
@@ -449,6 +461,13 @@ def main():
             del d
             torch.cuda.empty_cache()
         per["cfg5_stream"] = stream_report(args.warmup, with_oracle)
+        # the same stream at half and at saturating load, and 200 passes of a stream in progress
+        slim = lambda r: {k: r[k] for k in ("workload", "total_tokens", "ms_per_step", "tokens_per_s", "gpu_tokens_per_s",
+                                             "frac_of_per_pass_roofline", "achieved_GBs", "achieved_TFLOPs",
+                                             "generation_rows_per_pass_max", "tokens_per_pass_min_median_max")}
+        per["cfg5_stream_rate_0.5"] = slim(stream_report(args.warmup, False, rate=0.5))
+        per["cfg5_stream_rate_1.4"] = slim(stream_report(args.warmup, False, rate=1.4))
+        per["cfg5_stream_in_progress"] = slim(stream_report(args.warmup, False, rate=1.0, warm_passes=300))
         line["per_config"] = per
     line["bench_seconds"] = time.perf_counter() - t_start
     print(json.dumps(line))
