@@ -48,8 +48,9 @@ def test_closed_forms():
     # linear in both arguments
     w = rng.standard_normal((4, 8)).astype(np.float32)
     np.testing.assert_allclose(linear((2 * x).astype(np.float32), w, "f32"), 2 * linear(x, w, "f32"), atol=1e-13)
-    np.testing.assert_allclose(linear(x, w, "f32") + linear(x, (3 * w).astype(np.float32), "f32"),
-                               linear(x, (4 * w).astype(np.float32), "f32"), atol=1e-12)
+    wa = rng.integers(-8, 9, size=(4, 8)).astype(np.float32)        # small integers: their sum is exact in float32
+    wb = rng.integers(-8, 9, size=(4, 8)).astype(np.float32)
+    np.testing.assert_allclose(linear(x, wa, "f32") + linear(x, wb, "f32"), linear(x, wa + wb, "f32"), atol=1e-12)
 
 
 def test_tokens_are_independent_and_storage_types_convert_exactly():
