@@ -189,6 +189,22 @@ int fsf_rotary_q(const fsf_attn_cfg* cfg, void* q, const fsf_seq_desc* descs_dev
                  const float* cos_sin_dev, int32_t table_positions, void* hip_stream);
 
 /*
+ * A linear layer over the tokens of a pass (the projections and MLP products on either side of
+ * attention; paper Sec. 3.1: they make a pass weight-bound at few tokens and compute-bound at
+ * many, which is what a token budget is chosen against):
+ *     y[t, o] = sum_k x[t, k] * w[o, k]
+ *   x  device, [n_tokens, k]      tokens of the ragged batch, row-major
+ *   w  device, [n_out, k]         one output feature per row (k contiguous)
+ *   y  device, [n_tokens, n_out]
+ * bf16 or f16 operands on the matrix cores, fp32 accumulation, the result rounded once to the
+ * storage type (nearest even).  Any n_tokens >= 0 (0 is a no-op).  Requires n_out % 256 == 0,
+ * k % 32 == 0, 16-byte aligned tensors and x, w below 2 GiB each; FSF_ERR_UNSUPPORTED otherwise
+ * and for FSF_F32.  Allocates nothing, asynchronous on hip_stream.
+ */
+int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, int32_t n_tokens, int32_t n_out,
+               int32_t k, void* hip_stream);
+
+/*
  * Bytes of device workspace fsf_ragged_attention needs for a pass of at most n_seqs
  * sequences, n_tokens tokens and max_blocks table columns.  Never zero (a small plan
  * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.  On the

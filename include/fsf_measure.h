@@ -29,7 +29,8 @@ typedef enum {
   FSF_PHASE_MERGE = 4,   /* merge of split partial results                        */
   FSF_PHASE_GENERIC = 5, /* generic fp32 attention kernel                         */
   FSF_PHASE_FUSED = 6,   /* prompt-chunk + generation-row attention in one launch  */
-  FSF_N_PHASES = 7
+  FSF_PHASE_LINEAR = 7,  /* fsf_linear                                             */
+  FSF_N_PHASES = 8
 } fsf_phase;
 int fsf_profile_enable(int on);
 int fsf_profile_read(double* ms_out, int64_t* launches_out);

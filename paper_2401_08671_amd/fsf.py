@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
     L.fsf_kv_append_rotary.argtypes = [cfgp, vp, vp, vp, vp, descp, descp, i32p, i32, i32, i32, vp, i32, vp]
     L.fsf_rotary_q.restype = C.c_int
     L.fsf_rotary_q.argtypes = [cfgp, vp, descp, descp, i32, i32, vp, i32, vp]
+    L.fsf_linear.restype = C.c_int
+    L.fsf_linear.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp]
     L.fsf_ragged_attention_workspace_bytes.restype = sz
     L.fsf_ragged_attention_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
     L.fsf_ragged_attention.restype = C.c_int
@@ -187,6 +189,14 @@ def rotary_q(cfg: AttnCfg, q, batch: DeviceBatch, cos_sin) -> None:
     st = lib().fsf_rotary_q(C.byref(cfg), _ptr(q), _ptr(batch.descs_dev), C.c_void_p(batch.descs_host.ctypes.data),
                             batch.n_seqs, batch.n_tokens, _ptr(cos_sin), cos_sin.shape[0], _stream())
     _check(st, "fsf_rotary_q")
+
+
+def linear(x, w, y) -> None:
+    """fsf_linear on torch's current stream: y[t, o] = sum_k x[t, k] w[o, k]; x [T, K], w [N, K], y [T, N]."""
+    assert x.dim() == 2 and w.dim() == 2 and y.dim() == 2 and x.is_contiguous() and w.is_contiguous() and y.is_contiguous()
+    assert x.shape[1] == w.shape[1] and y.shape == (x.shape[0], w.shape[0]) and x.dtype == w.dtype == y.dtype
+    st = lib().fsf_linear(DTYPE_CODE[x.dtype], _ptr(x), _ptr(w), _ptr(y), x.shape[0], w.shape[0], x.shape[1], _stream())
+    _check(st, "fsf_linear")
 
 
 def ragged_attention_workspace_bytes(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int) -> int:
@@ -300,7 +310,7 @@ def plan_prefill_groups(cfg, descs: np.ndarray, compute_units: int = 256) -> np.
 
 
 # ------------------------------------------------------------------ per-kernel timing aid
-PHASES = ("append", "plan", "prefill", "decode", "merge", "generic", "fused")
+PHASES = ("append", "plan", "prefill", "decode", "merge", "generic", "fused", "linear")
 
 
 def profile_enable(on: bool) -> None:

@@ -134,7 +134,10 @@ MFMA_COUNTERS = ("SQ_BUSY_CYCLES", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_INSTS_VALU_MF
                  "SQ_LDS_BANK_CONFLICT", "SQ_WAIT_INST_LDS")
 
 
-def mfma_counters(raw, cfg, out_dir, bench):
+N_SE, N_SIMD = 32, 1024      # MI355X: 8 dies x 4 shader engines; 256 compute units x 4 SIMDs
+
+
+def mfma_counters(raw, cfg, out_dir, bench, avg_ns):
     path = os.path.join(raw, f"pmc_mfma_cfg{cfg}", "bench_counter_collection.csv")
     if not os.path.exists(path):
         return
@@ -143,19 +146,26 @@ def mfma_counters(raw, cfg, out_dir, bench):
            "Command:", "",
            f"    rocprofv3 --pmc {' '.join(MFMA_COUNTERS)} --output-format csv -d RAW/pmc_mfma_cfg{cfg} -o bench -- "
            f"python3 bench.py --config {cfg} {BENCH_ARGS} --steps 5 --warmup 2", "",
-           "Averages per dispatch, summed over the chip's shader engines as rocprofv3 reports them.", "",
-           "| kernel | " + " | ".join(MFMA_COUNTERS) + " | MFMA busy / SQ busy | MFMA MOPS per busy cycle |",
-           "|---|" + "---|" * (len(MFMA_COUNTERS) + 2)]
+           "Averages per dispatch, summed over the chip as rocprofv3 reports them: SQ_BUSY_CYCLES counts once per",
+           f"shader engine ({N_SE} of them), the matrix-pipe counter once per SIMD ({N_SIMD}).  So cycles of the launch =",
+           f"SQ_BUSY_CYCLES / {N_SE}, matrix-pipe busy cycles per SIMD = SQ_VALU_MFMA_BUSY_CYCLES / {N_SIMD}, and their",
+           "ratio is the share of the launch in which a SIMD's matrix pipe was busy, at the clock the chip held",
+           "(cycles of the launch / kernel duration); share x clock / 2.4 GHz is the fraction of the published peak.", "",
+           "| kernel | " + " | ".join(MFMA_COUNTERS) + " | launch cycles | pipe busy share | clock GHz (cycles / avg duration) |",
+           "|---|" + "---|" * (len(MFMA_COUNTERS) + 3)]
     for k, cs in agg.items():
         s = short(k)
         if s not in ("attn_prefill_kernel", "attn_decode_kernel", "attn_fused_kernel", "gemm_kernel"):
             continue
         vals = [mean(cs[c]) if cs.get(c) else float("nan") for c in MFMA_COUNTERS]
         busy, mfma, mops = vals[0], vals[1], vals[2]
-        out.append(f"| {s} | " + " | ".join(f"{v:.4g}" for v in vals) + f" | {mfma / busy:.3f} | {mops / busy:.3f} |")
-    out += ["", "SQ_VALU_MFMA_BUSY_CYCLES / SQ_BUSY_CYCLES is the share of the cycles in which any wave is resident that the",
-            "matrix pipe was busy; SQ_INSTS_VALU_MFMA_MOPS_BF16 counts matrix work in units of 512 flops (a 32x32x16",
-            "instruction is 64 of them).", ""]
+        cycles = busy / N_SE
+        ghz = cycles / avg_ns[s] if avg_ns.get(s) else float("nan")
+        out.append(f"| {s} | " + " | ".join(f"{v:.4g}" for v in vals) + f" | {cycles:.4g} | {mfma / N_SIMD / cycles:.3f} | {ghz:.2f} |")
+    out += ["", "SQ_INSTS_VALU_MFMA_MOPS_BF16 counts matrix work in units of 512 flops (a 32x32x16 instruction is 64 of",
+            "them and keeps the pipe busy for 32 cycles); SQ_INSTS_VALU counts all vector instructions per wave, MFMAs",
+            "included; SQ_LDS_BANK_CONFLICT counts cycles lost to LDS bank conflicts; the kernel durations are those of",
+            "the kernel-trace run of the same shape.", ""]
     open(os.path.join(out_dir, f"bench_cfg{cfg}_mfma.md"), "w").write("\n".join(out))
 
 
@@ -172,7 +182,7 @@ def main():
             continue
         bench, avg_ns = kt
         hbm_traffic(args.raw, cfg, args.out, bench, avg_ns, scale, notes)
-        mfma_counters(args.raw, cfg, args.out, bench)
+        mfma_counters(args.raw, cfg, args.out, bench, avg_ns)
         print(f"cfg{cfg}: summaries written to {args.out}")
 
 
