@@ -198,7 +198,7 @@ int fsf_rotary_q(const fsf_attn_cfg* cfg, void* q, const fsf_seq_desc* descs_dev
  *   y  device, [n_tokens, n_out]
  * bf16 or f16 operands on the matrix cores, fp32 accumulation, the result rounded once to the
  * storage type (nearest even).  Any n_tokens >= 0 (0 is a no-op).  Requires n_out % 256 == 0,
- * k % 32 == 0, 16-byte aligned tensors and x, w below 2 GiB each; FSF_ERR_UNSUPPORTED otherwise
+ * k % 64 == 0, 16-byte aligned tensors and x, w below 2 GiB each; FSF_ERR_UNSUPPORTED otherwise
  * and for FSF_F32.  Allocates nothing, asynchronous on hip_stream.
  */
 int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, int32_t n_tokens, int32_t n_out,

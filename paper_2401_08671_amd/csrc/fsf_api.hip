@@ -375,8 +375,8 @@ extern "C" int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, 
   if (dtype != FSF_BF16 && dtype != FSF_F16 && dtype != FSF_F32) return FSF_ERR_INVALID_ARG;
   if (n_tokens == 0) return FSF_OK;
   if (!x || !w || !y || (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y) & 15)) return FSF_ERR_INVALID_ARG;
-  // the kernel's tiling: 256 output features and 32 k-elements at a time, byte offsets in 31 bits
-  if (dtype == FSF_F32 || n_out % 256 || k % 32 || (int64_t)n_tokens * k * 2 >= (1ll << 31) ||
+  // the kernel's tiling: 256 output features and 64 k-elements at a time, byte offsets in 31 bits
+  if (dtype == FSF_F32 || n_out % 256 || k % 64 || (int64_t)n_tokens * k * 2 >= (1ll << 31) ||
       (int64_t)n_out * k * 2 >= (1ll << 31))
     return FSF_ERR_UNSUPPORTED;
   const hipError_t e = fsf::launch_linear(dtype, x, w, y, n_tokens, n_out, k, (hipStream_t)hip_stream);

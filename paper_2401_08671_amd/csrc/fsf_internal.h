@@ -264,7 +264,7 @@ hipError_t launch_kv_append_rotary(const Pass& p, const void* k_new, const void*
                                    void* v_cache, const float* cos_sin, hipStream_t stream);
 hipError_t launch_rotary_q(const Pass& p, void* q, const float* cos_sin, hipStream_t stream);
 
-// y[M, N] = x[M, K] . w[N, K]^T on the matrix cores (N % 256 == 0, K % 32 == 0, bf16 / f16)
+// y[M, N] = x[M, K] . w[N, K]^T on the matrix cores (N % 256 == 0, K % 64 == 0, bf16 / f16)
 hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M, int N, int K, hipStream_t stream);
 
 hipError_t launch_attn_generic(const Pass& p, const void* q, const void* k_cache,

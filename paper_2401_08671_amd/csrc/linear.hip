@@ -5,15 +5,18 @@
 // weight-bound while it holds few tokens and compute-bound once it holds many (paper Sec. 3.1),
 // and so what fixes a sensible token budget.  Dense contraction: matrix cores.
 //
-// One workgroup of 512 threads (8 waves, two per SIMD) computes a BM x 256 tile of y; a wave owns
-// WM x WN of it as 32x32x16 MFMA tiles.  Both operands are k-contiguous in memory (tokens and
-// weight rows alike), so they are staged the same way: BK = 32 k-elements at a time, row-major
-// tiles [rows][64 bytes] in LDS, copied there directly from HBM/L2 (global_load_lds, 16 bytes per
-// lane, no registers) in a ring of four stages, three k-steps ahead of the MFMAs.  A lane of a
-// copy instruction always fills the next 16 bytes of LDS, so the XOR swizzle that makes the later
+// One workgroup (8 waves, two per SIMD, for all but small token counts) computes a BM x BN tile of
+// y; a wave owns WM x WN of it as 32x32x16 MFMA tiles.  Both operands are k-contiguous in memory (tokens and
+// weight rows alike), so they are staged the same way: BK = 64 k-elements at a time, row-major
+// tiles [rows][128 bytes] in LDS, copied there directly from HBM/L2 (global_load_lds, 16 bytes per
+// lane, no registers) in a ring of two or three stages, ahead of the MFMAs.  A tile row is one
+// whole 128-byte cache line, fetched by eight adjacent lanes: with 64-byte rows the same bytes
+// cost twice the requests, and the L2's request rate, not its bandwidth, then bounds the kernel
+// (measured: 1.1 PFLOP/s at 64 % of the L2 channels' request slots).  A lane of a copy
+// instruction always fills the next 16 bytes of LDS, so the XOR swizzle that makes the later
 // ds_read_b128 fragment reads conflict-free is applied on the global side: 16-byte chunk c of tile
-// row r sits at chunk c ^ ((r >> 2) & 3)  (rows are 64 bytes = 4 chunks apart, a b128 read serves
-// 16 lanes per clock from 64 banks: rows r, r+4, r+8, r+12 must land on different chunks).
+// row r sits at chunk c ^ ((r >> 1) & 7)  (a b128 read serves 16 lanes per clock from 64 banks:
+// rows r and r+1 differ in address bit 7, and rows of equal parity land on different chunks).
 //
 // The product is formed transposed, D[o, t] = W . X^T (A operand = weight rows, B operand =
 // tokens): a lane then owns 4 consecutive output features of one token per register quad, which
@@ -22,11 +25,13 @@
 // The copies and their waits are written as inline asm: the compiler does not track LDS-DMA
 // per stage and would wait for every copy in flight before each LDS read.  The protocol per
 // k-step kt (every wave issues the same number of copies, so the counters agree):
-//   wait until this wave's copies of step kt have landed (all but the two younger steps)
-//   workgroup barrier: everybody's copies of step kt are in LDS, everybody has finished reading
-//                      step kt-1, whose stage the next copy overwrites
-//   start the copies of step kt+3 (past the end of k: the last step again, never read)
-//   fragments of step kt from LDS, 16 MFMAs
+//   MFMAs of the first three quarters of step kt, each with the next quarter's fragments on their
+//     way from LDS; then all fragments of step kt are in registers
+//   wait until this wave's copies of step kt+1 have landed (all but the younger steps')
+//   workgroup barrier: everybody's copies of step kt+1 are in LDS, and everybody has read step
+//                      kt's fragments, whose stage the next copy overwrites
+//   start the copies of step kt + stages (past the end of k: the last step again, never read)
+//   first fragments of step kt+1 from LDS, the last quarter of step kt's MFMAs, the next fragments
 #include "fsf_internal.h"
 #include "mma.h"
 #include "numeric.h"
@@ -34,15 +39,12 @@
 namespace fsf {
 namespace {
 
-constexpr int kLinThreads = 512;
-constexpr int kLinBN = 256;   // output features per workgroup
-constexpr int kLinBK = 32;    // k elements per stage: 64 bytes per tile row
-constexpr int kLinStages = 4;
+constexpr int kLinBK = 64;    // k elements per stage: one 128-byte line per tile row
 constexpr int kRowBytes = kLinBK * 2;
 
 typedef __attribute__((address_space(3))) char lin_lds_char;
 
-// one copy instruction of a wave: 16 tile rows x 64 bytes, lane -> (row lane / 4, physical chunk lane % 4)
+// one copy instruction of a wave: 8 tile rows x 128 bytes, lane -> (row lane / 8, physical chunk lane % 8)
 __device__ __forceinline__ void copy16(uint32_t lds_addr, uint32_t voffset, const char* base) {
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
@@ -53,18 +55,27 @@ __device__ __forceinline__ void copy16(uint32_t lds_addr, uint32_t voffset, cons
       : "memory", "m0");
 }
 
+// Wait until at most N of this wave's copies are in flight, and for its own LDS reads: a wave
+// that meets the barrier after this has the fragments it asked for in registers, so the stage
+// they came from may be overwritten.
 template <int N>
 __device__ __forceinline__ void wait_copies_but() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(N) : "memory");
 }
 
-// BM: tokens per workgroup (256 or 128).  Waves: (BM / WM) x (256 / WN) = 8.
-template <int DT, typename T, int BM>
-__global__ __launch_bounds__(kLinThreads) void linear_kernel(const T* __restrict__ x, const T* __restrict__ w,
-                                                              T* __restrict__ y, int M, int N, int K, int tiles_m,
-                                                              int tiles_n) {
-  constexpr int WM = 128;                 // tokens per wave
-  constexpr int WN = BM == 256 ? 64 : 32; // output features per wave
+// BM x BN: tokens x output features per workgroup; WM x WN: per wave; kLinStages: depth of the LDS
+// ring.  Three shapes are built:
+//   256 x 256, waves 128 x 64 (8 waves, two per SIMD), 2 stages of 64 KB: many tokens, compute-bound
+//   128 x 256, waves 128 x 32 (8 waves), 3 stages of 48 KB: up to 1024 tokens
+//   128 x  64, waves  64 x 32 (4 waves), 5 stages of 24 KB: up to 256 tokens, where the pass is
+//              bound by reading the weights: four times the workgroups to pull on HBM, deep prefetch
+template <int DT, typename T, int BM, int BN, int WM, int WN, int kLinStages>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(const T* __restrict__ x,
+                                                                           const T* __restrict__ w,
+                                                                           T* __restrict__ y, int M, int N,
+                                                                           int K, int tiles_m, int tiles_n) {
+  constexpr int kLinBN = BN;
+  constexpr int kWaves = (BM / WM) * (BN / WN);
   constexpr int MB = WM / 32, NB = WN / 32;
   constexpr int kXTile = BM * kRowBytes, kWTile = kLinBN * kRowBytes;
   constexpr int kStage = kXTile + kWTile;
@@ -90,43 +101,44 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const T* __restrict
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hg = lane >> 5;
 
-  // ---- copies: wave v fills rows [32 v, 32 v + 32) of the weight tile (256 rows) with two
-  // instructions, and rows of the token tile likewise (BM = 128: waves 0..3 fill 32 rows each...
-  // every wave issues the same count, so with BM = 128 each wave takes 16 rows, one instruction)
-  constexpr int kXCopies = BM / 128;      // instructions per wave for the token tile
-  const int crow = lane >> 2, cpc = lane & 3;
-  uint32_t x_off[kXCopies], w_off[2];
+  // ---- copies: every wave fills an equal share of the rows of both tiles, 8 rows per instruction
+  // (every wave issues the same count, so the copy counters of all waves agree)
+  constexpr int kXCopies = BM / 8 / kWaves;      // instructions per wave for the token tile
+  constexpr int kWCopies = kLinBN / 8 / kWaves;  // ... for the weight tile
+  const int crow = lane >> 3, cpc = lane & 7;
+  uint32_t x_off[kXCopies], w_off[kWCopies];
 #pragma unroll
   for (int j = 0; j < kXCopies; ++j) {
-    const int r = wave * (16 * kXCopies) + j * 16 + crow;
+    const int r = wave * (8 * kXCopies) + j * 8 + crow;
     const int row = min(m0 + r, M - 1);   // rows past the last token are copies of it, never stored
-    x_off[j] = (uint32_t)row * (uint32_t)K * 2u + (uint32_t)((cpc ^ ((r >> 2) & 3)) << 4);
+    x_off[j] = (uint32_t)row * (uint32_t)K * 2u + (uint32_t)((cpc ^ ((r >> 1) & 7)) << 4);
   }
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int r = wave * 32 + j * 16 + crow;
-    w_off[j] = (uint32_t)(n0 + r) * (uint32_t)K * 2u + (uint32_t)((cpc ^ ((r >> 2) & 3)) << 4);
+  for (int j = 0; j < kWCopies; ++j) {
+    const int r = wave * (8 * kWCopies) + j * 8 + crow;
+    w_off[j] = (uint32_t)(n0 + r) * (uint32_t)K * 2u + (uint32_t)((cpc ^ ((r >> 1) & 7)) << 4);
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
   const int nk = K / kLinBK;
-  auto issue = [&](int kt) {  // copies of k-step min(kt, nk - 1) into stage kt % 4
+  auto issue = [&](int kt) {  // copies of k-step min(kt, nk - 1) into stage kt % kLinStages
     const int ks = min(kt, nk - 1);
     const uint32_t stage = lds0 + (uint32_t)(kt % kLinStages) * kStage;
     const char* xb = reinterpret_cast<const char*>(x) + (size_t)ks * kRowBytes;
     const char* wb = reinterpret_cast<const char*>(w) + (size_t)ks * kRowBytes;
 #pragma unroll
     for (int j = 0; j < kXCopies; ++j)
-      copy16(stage + (uint32_t)(wave * (16 * kXCopies) + j * 16) * kRowBytes, x_off[j], xb);
+      copy16(stage + (uint32_t)(wave * (8 * kXCopies) + j * 8) * kRowBytes, x_off[j], xb);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) copy16(stage + kXTile + (uint32_t)(wave * 32 + j * 16) * kRowBytes, w_off[j], wb);
+    for (int j = 0; j < kWCopies; ++j)
+      copy16(stage + kXTile + (uint32_t)(wave * (8 * kWCopies) + j * 8) * kRowBytes, w_off[j], wb);
   };
-  constexpr int kCopiesPerStep = kXCopies + 2;
+  constexpr int kCopiesPerStep = kXCopies + kWCopies;
 
-  // ---- fragments: tile row blk * 32 + l32, logical chunk 2 t + hg of k-substep t
+  // ---- fragments: tile row blk * 32 + l32, logical chunk 2 t + hg of k-substep t (16 k-elements)
   const int wm = wave % (BM / WM), wn = wave / (BM / WM);
-  uint32_t frag_off[2];
+  uint32_t frag_off[4];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) frag_off[t] = (uint32_t)(l32 * kRowBytes + (((2 * t + hg) ^ ((l32 >> 2) & 3)) << 4));
+  for (int t = 0; t < 4; ++t) frag_off[t] = (uint32_t)(l32 * kRowBytes + (((2 * t + hg) ^ ((l32 >> 1) & 7)) << 4));
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 
@@ -138,32 +150,69 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const T* __restrict
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  issue(0);
-  issue(1);
-  issue(2);
-  for (int kt = 0; kt < nk; ++kt) {
-    wait_copies_but<2 * kCopiesPerStep>();
-    __builtin_amdgcn_s_barrier();
-    issue(kt + 3);
+  // Fragments of one k-substep (16 k-elements) of a stage: WN / 32 weight and 4 token fragments.
+  struct Frags {
+    frag8 xf[MB], wf[NB];
+  };
+  auto read_frags = [&](Frags& fr, int kt, int t) {
     const lin_lds_char* st = lds + (kt % kLinStages) * kStage;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      frag8 xf[MB], wf[NB];
-#pragma unroll
-      for (int b = 0; b < MB; ++b) {
-        const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + (wm * WM + b * 32) * kRowBytes + frag_off[t]);
-        xf[b] = frag8{{v[0], v[1], v[2], v[3]}};
-      }
-#pragma unroll
-      for (int a = 0; a < NB; ++a) {
-        const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + kXTile + (wn * WN + a * 32) * kRowBytes + frag_off[t]);
-        wf[a] = frag8{{v[0], v[1], v[2], v[3]}};
-      }
-#pragma unroll
-      for (int a = 0; a < NB; ++a)
-#pragma unroll
-        for (int b = 0; b < MB; ++b) acc[a][b] = Mma<DT>::mfma32(wf[a], xf[b], acc[a][b]);
+    for (int b = 0; b < MB; ++b) {
+      const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + (wm * WM + b * 32) * kRowBytes + frag_off[t]);
+      fr.xf[b] = frag8{{v[0], v[1], v[2], v[3]}};
     }
+#pragma unroll
+    for (int a = 0; a < NB; ++a) {
+      const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + kXTile + (wn * WN + a * 32) * kRowBytes + frag_off[t]);
+      fr.wf[a] = frag8{{v[0], v[1], v[2], v[3]}};
+    }
+  };
+  auto multiply = [&](const Frags& fr) {
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+      for (int b = 0; b < MB; ++b) acc[a][b] = Mma<DT>::mfma32(fr.wf[a], fr.xf[b], acc[a][b]);
+  };
+
+  // Software pipeline over quarter steps (16 k-elements): the fragments of a quarter are on their
+  // way from LDS while the MFMAs of the quarter before run, and the wait for the next step's
+  // copies, the barrier and the first LDS reads of the next step sit before the last quarter of
+  // the current step's MFMAs, which hide them.  (The scheduling barriers keep the compiler from
+  // sinking the LDS reads down to their first use, which would put every MFMA group behind an
+  // exposed LDS round trip.)
+  constexpr int kAhead = kLinStages - 1;  // k-steps whose copies are in flight or landed beyond the current one
+#pragma unroll
+  for (int j = 0; j < kAhead; ++j) issue(j);
+  wait_copies_but<(kAhead - 1) * kCopiesPerStep>();
+  __builtin_amdgcn_s_barrier();
+  issue(kAhead);
+  Frags fa, fb;
+  read_frags(fa, 0, 0);
+  read_frags(fb, 0, 1);
+  __builtin_amdgcn_sched_barrier(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    multiply(fa);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fa, kt, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(fb);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fb, kt, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(fa);
+    __builtin_amdgcn_sched_barrier(0);
+    // this wave's copies of step kt+1 have landed (younger steps may be in flight); after the
+    // barrier everybody's have, and everybody holds step kt's last fragments in registers, so the
+    // stage of step kt can take the copies of step kt + stages
+    wait_copies_but<(kAhead - 1) * kCopiesPerStep>();
+    __builtin_amdgcn_s_barrier();
+    issue(kt + kLinStages);
+    read_frags(fa, kt + 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(fb);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(fb, kt + 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
   }
   wait_copies_but<0>();  // the copies past the end of k are still in flight: let them land before the workgroup ends
 
@@ -190,29 +239,32 @@ __global__ __launch_bounds__(kLinThreads) void linear_kernel(const T* __restrict
 
 hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M, int N, int K, hipStream_t stream) {
   PhaseTimer timer(FSF_PHASE_LINEAR, stream);
-  const int tiles_n = N / kLinBN;
-  // many tokens: 256-token tiles; few: 128-token tiles, so that more workgroups share the weight stream
-  const bool big = M > 1024;
-  const int bm = big ? 256 : 128;
-  const int tiles_m = (M + bm - 1) / bm;
+  const int shape = M > 1024 ? 0 : (M > 256 ? 1 : 2);
+  const int bm = shape == 0 ? 256 : 128, bn = shape == 2 ? 64 : 256, stages = shape == 0 ? 2 : (shape == 1 ? 3 : 5);
+  const int tiles_m = (M + bm - 1) / bm, tiles_n = N / bn;
   const unsigned grid = (unsigned)(tiles_m * tiles_n);
-  const size_t lds_bytes = (size_t)kLinStages * (bm + kLinBN) * kRowBytes;
-#define FSF_LINEAR(DT, T, BM)                                                                       \
+  const size_t lds_bytes = (size_t)stages * (bm + bn) * kRowBytes;
+#define FSF_LINEAR(DT, T, BM, BN, WM, WN, ST)                                                       \
   {                                                                                                 \
     static bool attr_set = false;                                                                   \
     if (!attr_set) {                                                                                \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_kernel<DT, T, BM>),                 \
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);              \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_kernel<DT, T, BM, BN, WM, WN, ST>), \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);        \
       attr_set = true;                                                                              \
     }                                                                                               \
-    linear_kernel<DT, T, BM><<<grid, kLinThreads, lds_bytes, stream>>>((const T*)x, (const T*)w, (T*)y, M, N, K, \
-                                                                       tiles_m, tiles_n);           \
+    linear_kernel<DT, T, BM, BN, WM, WN, ST><<<grid, (BM / WM) * (BN / WN) * 64, lds_bytes, stream>>>( \
+        (const T*)x, (const T*)w, (T*)y, M, N, K, tiles_m, tiles_n);                                \
   }
+#define FSF_LINEAR_SHAPES(DT, T)                                      \
+  if (shape == 0) FSF_LINEAR(DT, T, 256, 256, 128, 64, 2)             \
+  else if (shape == 1) FSF_LINEAR(DT, T, 128, 256, 128, 32, 3)        \
+  else FSF_LINEAR(DT, T, 128, 64, 64, 32, 5)
   if (dtype == FSF_BF16) {
-    if (big) FSF_LINEAR(FSF_BF16, bf16_t, 256) else FSF_LINEAR(FSF_BF16, bf16_t, 128)
+    FSF_LINEAR_SHAPES(FSF_BF16, bf16_t)
   } else {
-    if (big) FSF_LINEAR(FSF_F16, f16_t, 256) else FSF_LINEAR(FSF_F16, f16_t, 128)
+    FSF_LINEAR_SHAPES(FSF_F16, f16_t)
   }
+#undef FSF_LINEAR_SHAPES
 #undef FSF_LINEAR
   return hipGetLastError();
 }

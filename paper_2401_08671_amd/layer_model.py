@@ -5,16 +5,18 @@ This library contains the attention step of a pass only.  The paper's two observ
 whole pass (Sec. 3.1) are about the other part: with few tokens the pass is bound by reading the
 weights, with many by their flops, and the transition fixes a sensible token budget.  To put the
 attention step in that context, and to give the scheduling simulator a measured duration for
-the linear part instead of a model, this module times the layer's GEMMs (QKV, output projection,
-gated MLP) with random bf16 weights of a Llama-2-13B-shaped layer through the vendor GEMM library
-(torch.matmul: hipBLASLt) for a grid of token counts.  Nothing here is part of the attention path.
+the linear part instead of a model, this module times the layer's linear maps (QKV, output
+projection, gated MLP) with random bf16 weights of a Llama-2-13B-shaped layer through the
+library's own matrix-core kernel (fsf_linear) for a grid of token counts, and, as context only,
+through the vendor GEMM library (torch.matmul: hipBLASLt).  The gate of the MLP (silu(a) * b, an
+element-wise step) is a torch expression in both cases; it is not part of this library.
 
 `measure_layer` runs a whole layer of a Dynamic SplitFuse pass in order: the three projections,
 the rotation of Q and of K (this library: in place, and fused into the append), the ragged attention, the
 output projection and the gated MLP, for a grid of token budgets; the budget's tokens are a fixed
 number of generation rows plus one prompt chunk that fills the rest (Sec. 3.2).
 
-    python -m paper_2401_08671_amd.layer_model            # the GEMMs alone; prints one JSON object
+    python -m paper_2401_08671_amd.layer_model            # the linear maps alone (both backends); one JSON object
     python -m paper_2401_08671_amd.layer_model --layer    # the whole layer with attention
 """
 from __future__ import annotations
@@ -39,13 +41,37 @@ def layer_weight_bytes(shape=SHAPE_13B) -> int:
     return layer_gemm_flops(shape)  # 2 bytes per weight, 2 flops per weight and token
 
 
-def measure_linear(shape=SHAPE_13B, grid=TOKEN_GRID, reps: int = 5, device="cuda"):
-    """[(tokens, seconds for the GEMMs of ONE layer)], fastest of reps; weights of three layers
-    are cycled so that a pass never finds its weights in cache"""
-    h, qkv, mlp = shape["hidden"], 3 * shape["n_heads"] * shape["head_dim"], shape["mlp"]
+def _linear(backend: str, x: torch.Tensor, w: torch.Tensor) -> torch.Tensor:
+    """y[t, o] = sum_k x[t, k] w[o, k] through fsf_linear ("fsf") or the vendor library ("vendor")."""
+    if backend == "vendor":
+        return x @ w.T
+    from . import fsf
+    y = torch.empty((x.shape[0], w.shape[0]), dtype=x.dtype, device=x.device)
+    fsf.linear(x, w, y)
+    return y
+
+
+def _make_weights(shape, device, n_sets: int = 3, split_qkv: bool = False):
+    """random bf16 weights [n_out, k] of n_sets layers (cycled, so that a pass never finds its weights in cache)"""
+    h, mlp = shape["hidden"], shape["mlp"]
+    qkv = 3 * shape["n_heads"] * shape["head_dim"]
     g = torch.Generator(device=device).manual_seed(5)
     mk = lambda *s: (torch.randn(*s, generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
-    layers = [dict(wqkv=mk(h, qkv), wo=mk(h, h), wgu=mk(h, 2 * mlp), wd=mk(mlp, h)) for _ in range(3)]
+    sets = []
+    for _ in range(n_sets):
+        w = dict(wo=mk(h, h), wgu=mk(2 * mlp, h), wd=mk(h, mlp))
+        if split_qkv:
+            w.update(wq=mk(h, h), wk=mk(h, h), wv=mk(h, h))
+        else:
+            w.update(wqkv=mk(qkv, h))
+        sets.append(w)
+    return sets, mk
+
+
+def measure_linear(shape=SHAPE_13B, grid=TOKEN_GRID, reps: int = 5, device="cuda", backend: str = "fsf"):
+    """[(tokens, seconds for the linear maps of ONE layer)], fastest of reps"""
+    h, mlp = shape["hidden"], shape["mlp"]
+    layers, mk = _make_weights(shape, device)
     out = []
     for T in grid:
         x = mk(T, h)
@@ -54,10 +80,10 @@ def measure_linear(shape=SHAPE_13B, grid=TOKEN_GRID, reps: int = 5, device="cuda
             w = layers[r % 3]
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            a = x @ w["wqkv"]
-            b = a[:, :h] @ w["wo"]
-            c = b @ w["wgu"]
-            d = (torch.nn.functional.silu(c[:, :mlp]) * c[:, mlp:]) @ w["wd"]
+            a = _linear(backend, x, w["wqkv"])
+            b = _linear(backend, a[:, :h].contiguous(), w["wo"])
+            c = _linear(backend, b, w["wgu"])
+            d = _linear(backend, torch.nn.functional.silu(c[:, :mlp]) * c[:, mlp:], w["wd"])
             e1.record()
             torch.cuda.synchronize()
             if r >= 2:
@@ -68,7 +94,7 @@ def measure_linear(shape=SHAPE_13B, grid=TOKEN_GRID, reps: int = 5, device="cuda
 
 
 def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations: int = 64, context: int = 2048,
-                  shape=SHAPE_13B, reps: int = 5, device="cuda"):
+                  shape=SHAPE_13B, reps: int = 5, device="cuda", backend: str = "fsf"):
     """One Llama-2-13B-shaped layer of a SplitFuse pass per token budget: n_generations generation
     rows over `context` cached tokens plus one chunk of the remaining tokens of a prompt that has
     `context` tokens cached already.  Returns rows of dict(budget, layer_ms, gemm_ms, attention_ms)."""
@@ -76,13 +102,12 @@ def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations
     from . import workloads as wl
     from .harness import DeviceStep
     h, H, d, mlp = shape["hidden"], shape["n_heads"], shape["head_dim"], shape["mlp"]
-    g = torch.Generator(device=device).manual_seed(5)
-    mk = lambda *s: (torch.randn(*s, generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
-    layers = [dict(wq=mk(h, h), wk=mk(h, h), wv=mk(h, h), wo=mk(h, h), wgu=mk(h, 2 * mlp), wd=mk(mlp, h)) for _ in range(3)]
+    layers, mk = _make_weights(shape, device, split_qkv=True)
     n_pos = context + max(budgets) + 1
-    inv = 10000.0 ** (-torch.arange(0, d // 2, dtype=torch.float64, device=device) * 2.0 / d)
-    ang = torch.arange(n_pos, dtype=torch.float64, device=device)[:, None] * inv[None, :]
-    cos_sin = torch.stack([ang.cos(), ang.sin()], dim=-1).to(torch.float32).contiguous()
+    # the caller of the rotary calls supplies the angle table; its values do not affect any timing,
+    # so this measurement uses the identity rotation (cos 1, sin 0) at every position
+    cos_sin = torch.zeros((n_pos, d // 2, 2), dtype=torch.float32, device=device)
+    cos_sin[..., 0] = 1.0
     rows = []
     for T in budgets:
         n_dec = min(n_generations, T // 2)
@@ -94,17 +119,17 @@ def measure_layer(budgets=(128, 256, 512, 1024, 2048, 4096, 8192), n_generations
         for r in range(reps + 2):
             w = layers[r % 3]
             ev[0].record()
-            q = (x @ w["wq"]).view(T, H, d)
-            k = (x @ w["wk"]).view(T, H, d)
-            v = (x @ w["wv"]).view(T, H, d)
+            q = _linear(backend, x, w["wq"]).view(T, H, d)
+            k = _linear(backend, x, w["wk"]).view(T, H, d)
+            v = _linear(backend, x, w["wv"]).view(T, H, d)
             ev[1].record()
             fsf.rotary_q(ds.cfg, q, ds.batch, cos_sin)
             fsf.kv_append_rotary(ds.cfg, k, v, ds.k_cache, ds.v_cache, ds.batch, cos_sin)
             fsf.ragged_attention(ds.cfg, q, ds.k_cache, ds.v_cache, ds.batch, ds.out, ds.ws)
             ev[2].record()
-            o = ds.out.view(T, h) @ w["wo"]
-            gu = o @ w["wgu"]
-            y = (torch.nn.functional.silu(gu[:, :mlp]) * gu[:, mlp:]) @ w["wd"]
+            o = _linear(backend, ds.out.view(T, h), w["wo"])
+            gu = _linear(backend, o, w["wgu"])
+            y = _linear(backend, torch.nn.functional.silu(gu[:, :mlp]) * gu[:, mlp:], w["wd"])
             ev[3].record()
             torch.cuda.synchronize()
             t = [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
@@ -140,14 +165,16 @@ class MeasuredLinear:
 def main():
     assert torch.cuda.is_available(), "needs a GPU"
     if "--layer" in sys.argv[1:]:
-        json.dump(dict(shape=SHAPE_13B, rows=measure_layer()), sys.stdout)
+        json.dump(dict(shape=SHAPE_13B, rows=measure_layer(), rows_vendor_gemm=measure_layer(backend="vendor")), sys.stdout)
         print()
         return
-    table = measure_linear()
     fl, by = layer_gemm_flops(), layer_weight_bytes()
-    rows = [dict(tokens=T, layer_ms=s * 1e3, tflops=T * fl / s / 1e12, weight_gbs=by / s / 1e9,
-                 tokens_per_s_whole_model=T / (s * SHAPE_13B["n_layers"])) for T, s in table]
-    json.dump(dict(shape=SHAPE_13B, gemm_flops_per_token_per_layer=fl, weight_bytes_per_layer=by, rows=rows), sys.stdout)
+    out = dict(shape=SHAPE_13B, gemm_flops_per_token_per_layer=fl, weight_bytes_per_layer=by)
+    for backend in ("fsf", "vendor"):
+        table = measure_linear(backend=backend)
+        out["rows_" + backend] = [dict(tokens=T, layer_ms=s * 1e3, tflops=T * fl / s / 1e12, weight_gbs=by / s / 1e9,
+                                       tokens_per_s_whole_model=T / (s * SHAPE_13B["n_layers"])) for T, s in table]
+    json.dump(out, sys.stdout)
     print()
 
 
