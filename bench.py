@@ -425,7 +425,7 @@ def main():
         return
 
     head_cfg = args.config or 3
-    rep, ds = shape_report(head_cfg, args.steps, args.warmup, n_decode_check=48, with_baseline=with_oracle)
+    rep, ds = shape_report(head_cfg, args.steps, args.warmup, n_decode_check=400, with_baseline=with_oracle)
     line = {
         "metric": METRIC, "value": rep["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": rep["ms_per_step"], "higher_is_better": True, "scaling": "weak",

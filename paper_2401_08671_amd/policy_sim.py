@@ -20,9 +20,9 @@ The duration of a pass is a callable.  ``ForwardModel`` is the one used for the 
 runs: the attention part of every layer is either *measured* (``MeasuredAttention``: the
 pass's KV append and ragged attention are executed on the GPU through the library on
 buffers of the pass's real shape and block tables, and timed with events) or taken from the
-rates the kernels reach; the rest of the layer (weight GEMMs), which this library does not
-contain, is either measured as well (``layer_model``: the layer's GEMMs through the vendor
-library at the pass's token count) or a two-regime model: reading the weights once, or the
+rates the kernels reach; the rest of the layer (its linear maps) is either measured as well
+(``layer_model``: the layer's linear maps through fsf_linear at the pass's token count) or a
+two-regime model: reading the weights once, or the
 flops of the forward tokens, whichever takes longer (Sec. 3.1: few tokens are bound by weight
 reads, many by compute).
 
