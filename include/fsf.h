@@ -80,8 +80,9 @@ typedef struct {
                                    /* tokens; a quarter of that in passes with fewer units than compute   */
                                    /* units, unless set here)                                            */
   int32_t decode_hold;             /* -1: store every unit's result as it finishes; default (0, 1): with */
-                                   /* more units than wave slots, waves keep finished rows in LDS and     */
-                                   /* store them at the end                                              */
+                                   /* more units than wave slots, one round of waves (eight to a          */
+                                   /* workgroup, one workgroup per compute unit) keep finished rows in LDS */
+                                   /* and store them at the end; 2: the same with single-wave workgroups   */
   int32_t prefill_split;           /* -1: never cut prompt-chunk tiles along their keys; default: cut    */
                                    /* tiles that would outlast the pass or sit in a half-empty last round */
   int32_t compute_units;           /* compute units the cutting rules assume (default: the device's)     */
@@ -89,6 +90,13 @@ typedef struct {
                                    /* KV head that may hold partial results (default 8192)               */
   int32_t max_prefill_split_units; /* bounds the workspace: (tile, head, part) workgroups with partial    */
                                    /* results, 139 KB each (default 512)                                 */
+  int32_t overlap;                 /* 1: in passes with both kinds of work, more streaming units than     */
+                                   /* wave slots and little prompt-chunk work, the prompt-chunk tiles run  */
+                                   /* beside the streaming kernel on a second stream the library keeps per */
+                                   /* device, on 8 or 16 compute units the streaming kernel leaves empty;  */
+                                   /* forked from and joined to the caller's stream inside the call.       */
+                                   /* Default (0) and -1: one kernel after the other, which measured       */
+                                   /* faster on most passes                                               */
   int32_t stream_chunk_slices;     /* a prompt chunk of at most this many slices of 16 / (query heads    */
                                    /* per KV head) rows runs on the streaming kernel like generation      */
                                    /* rows, every slice reading the chunk's K/V once (default 2, at most  */

@@ -37,6 +37,24 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_kernel(Pass p, FastP
   prefill_tile<DT, T>(p, f, q, kc, vc, out, w, hq, (lds_char*)lds);
 }
 
+// The same tiles walked by a fixed number of workgroups (workgroup j takes tiles j, j + grid, ...
+// in start order): the kernel then occupies exactly gridDim.x compute units however long it runs
+// and whatever else is on the chip, which is what running it beside the streaming kernel needs.
+template <int DT, typename T>
+__global__ __launch_bounds__(kThreads, 1) void attn_prefill_persistent_kernel(Pass p, FastPlan f,
+                                                                            const T* __restrict__ q,
+                                                                            const T* __restrict__ kc,
+                                                                            const T* __restrict__ vc,
+                                                                            T* __restrict__ out, int n_blocks) {
+  __shared__ __attribute__((aligned(1024))) char lds[kPrefillLdsBytes];
+  for (int b = blockIdx.x; b < n_blocks; b += gridDim.x) {
+    int hq;
+    const PrefillWork w = prefill_block_to_work(p, f, b, hq);
+    prefill_tile<DT, T>(p, f, q, kc, vc, out, w, hq, (lds_char*)lds);
+    __syncthreads();  // the next tile's copies overwrite LDS slots that slower waves may still read
+  }
+}
+
 // One generation-row unit per 64-thread workgroup: a finished unit frees its slot at once,
 // which measured best on the short-sequence batches.
 // hold_slots == 0: one unit per workgroup, results stored at once.  hold_slots > 0: the grid
@@ -69,6 +87,57 @@ __global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
   };
   for (int round = 0; round * G < n_units; ++round) {
     const int unit = round * G + ((round & 1) ? G - 1 - (int)blockIdx.x : (int)blockIdx.x);
+    if (unit >= n_units) continue;
+    const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, unit, lane, stage, hold + held * row_bytes);
+    if (d >= 0) {  // the same in every lane
+      if (lane == 0) dst[held] = d;
+      ++held;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (held == hold_slots) flush();
+  }
+  flush();
+}
+
+// The same walk with eight waves to a workgroup and so much LDS that a workgroup has a compute
+// unit to itself: a grid of fewer workgroups than compute units then leaves whole units empty,
+// wherever the dispatcher puts it and whatever starts first.  That is what lets prompt-chunk
+// tiles (which need a whole empty unit each: a tile wave takes a SIMD's entire register file) run
+// on a second stream beside the streaming kernel.  (The streaming kernel's grid is one round of
+// waves that are all meant to be resident at once; a single wave slot taken by other work makes
+// one of them start only when another has finished, and the launch lasts up to twice as long:
+// measured +11 % beside one foreign wave, +23 % beside one prompt-chunk workgroup.)
+constexpr int kWideWaves = 8;
+template <int DT, typename T, bool kBlock16>
+__global__ __launch_bounds__(64 * kWideWaves) void attn_decode_wide_kernel(Pass p, FastPlan f,
+                                                                           const T* __restrict__ q,
+                                                                           const T* __restrict__ kc,
+                                                                           const T* __restrict__ vc,
+                                                                           T* __restrict__ out, int hold_slots,
+                                                                           int lds_per_wave) {
+  extern __shared__ __attribute__((aligned(16))) char decode_lds[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  lds_char* stage = (lds_char*)decode_lds + wave * lds_per_wave;
+  const int row_bytes = p.group * kHeadDim * (int)sizeof(T);
+  lds_char* hold = stage + kDecodeStageBytes;
+  auto* dst = reinterpret_cast<__attribute__((address_space(3))) int64_t*>(hold + hold_slots * row_bytes);
+  const int n_units = f.n_dec_items * p.n_kv_heads;
+  // Which slot of the launch order a wave takes.  Where a workgroup's eight waves cover whole
+  // sequences' KV heads (1, 2, 4 or 8 of them), consecutive slots: the workgroup then streams
+  // whole cache blocks, contiguous in memory (measured on 8 KV heads: 2..4 % faster).  Otherwise
+  // wave w of workgroup b takes slot w * groups + b: the eight waves of a compute unit then hold
+  // units far apart in the launch order (other sequences, other lengths), as single-wave workgroups
+  // dealt out in turn would; eight of a sequence's 40 heads side by side run in lockstep through
+  // the same blocks and were 6 % slower on the long-prompt stream.
+  const int G = gridDim.x * kWideWaves;
+  const int me = (kWideWaves % p.n_kv_heads == 0) ? blockIdx.x * kWideWaves + wave : wave * (int)gridDim.x + (int)blockIdx.x;
+  int held = 0;
+  auto flush = [&] {
+    for (int s = 0; s < held; ++s) store_rows(reinterpret_cast<char*>(out) + dst[s], hold + s * row_bytes, row_bytes, lane);
+    held = 0;
+  };
+  for (int round = 0; round * G < n_units; ++round) {
+    const int unit = round * G + ((round & 1) ? G - 1 - me : me);
     if (unit >= n_units) continue;
     const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, unit, lane, stage, hold + held * row_bytes);
     if (d >= 0) {  // the same in every lane
@@ -139,35 +208,74 @@ unsigned decode_groups(const Pass& p, const FastPlan& f) {
         p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out);
 
 hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
-                               const void* v_cache, void* out, hipStream_t stream) {
+                               const void* v_cache, void* out, hipStream_t stream, int persistent_groups) {
   if (f.n_pre_tiles == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_PREFILL, stream);
   const unsigned grid = (unsigned)prefill_groups(f.n_pre_tiles, f.split) * p.n_q_heads;
+  if (persistent_groups > 0) {
+    const unsigned g = std::min<unsigned>(grid, (unsigned)persistent_groups);
+    if (p.dtype == FSF_BF16)
+      attn_prefill_persistent_kernel<FSF_BF16, bf16_t><<<g, kThreads, 0, stream>>>(
+          p, f, (const bf16_t*)q, (const bf16_t*)k_cache, (const bf16_t*)v_cache, (bf16_t*)out, (int)grid);
+    else
+      attn_prefill_persistent_kernel<FSF_F16, f16_t><<<g, kThreads, 0, stream>>>(
+          p, f, (const f16_t*)q, (const f16_t*)k_cache, (const f16_t*)v_cache, (f16_t*)out, (int)grid);
+    return hipGetLastError();
+  }
   FSF_LAUNCH(attn_prefill_kernel, grid)
   return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
-                              const void* v_cache, void* out, hipStream_t stream) {
+                              const void* v_cache, void* out, hipStream_t stream, int reserve_units) {
   if (f.n_dec_items == 0) return hipSuccess;
   PhaseTimer timer(FSF_PHASE_DECODE, stream);
   const unsigned n_units = (unsigned)f.n_dec_items * p.n_kv_heads;
-  // With more units than wave slots (two waves per SIMD): one round of waves that hold their
-  // results back.  LDS per wave: the staging area, up to 10 KB of finished rows, their addresses.
+  const int row_bytes = p.group * kHeadDim * 2;
+  const bool b16 = p.block_size == 16;
+  const unsigned slots = 8u * (unsigned)decode_compute_units();
+  if (n_units > slots && f.decode_hold == 1) {
+    // More units than wave slots: one round of waves that hold their results back, as one
+    // workgroup of eight waves per compute unit (on all units but the reserved ones).  LDS per
+    // wave: the staging area, up to 10 KB of finished rows, their addresses; at least 12 KB, so
+    // that a workgroup takes 96 KB and no second one fits beside it: every unit then holds exactly
+    // eight waves (single-wave workgroups spread unevenly over the units: 2..4 % slower).
+    const unsigned groups = (unsigned)std::max(1, decode_compute_units() - reserve_units);
+    const int per_wave = (int)((n_units + groups * kWideWaves - 1) / (groups * kWideWaves));
+    const int hold_slots = std::max(1, std::min(per_wave, (10 * 1024) / row_bytes));
+    const int lds_per_wave = std::max(12 * 1024, (kDecodeStageBytes + hold_slots * (row_bytes + 8) + 15) & ~15);
+    const size_t lds_bytes = (size_t)lds_per_wave * kWideWaves;
+#define FSF_DECODE_WIDE(DT, T, B16)                                                                              \
+  {                                                                                                              \
+    static bool attr_set = false;                                                                                \
+    if (!attr_set) {                                                                                             \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_wide_kernel<DT, T, B16>),             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                         \
+      attr_set = true;                                                                                           \
+    }                                                                                                            \
+    attn_decode_wide_kernel<DT, T, B16><<<groups, 64 * kWideWaves, lds_bytes, stream>>>(                         \
+        p, f, (const T*)q, (const T*)k_cache, (const T*)v_cache, (T*)out, hold_slots, lds_per_wave);             \
+  }
+    if (p.dtype == FSF_BF16) {
+      if (b16) FSF_DECODE_WIDE(FSF_BF16, bf16_t, true) else FSF_DECODE_WIDE(FSF_BF16, bf16_t, false)
+    } else {
+      if (b16) FSF_DECODE_WIDE(FSF_F16, f16_t, true) else FSF_DECODE_WIDE(FSF_F16, f16_t, false)
+    }
+#undef FSF_DECODE_WIDE
+    return hipGetLastError();
+  }
+  // one unit per single-wave workgroup, results stored at once; or (decode_hold == 2, kept for
+  // comparison) one round of single-wave workgroups that hold their results back
   unsigned grid = n_units;
   int hold_slots = 0;
-  const unsigned slots = 8u * (unsigned)decode_compute_units();
-  const int row_bytes = p.group * kHeadDim * 2;
-  if (n_units > slots && f.decode_hold) {
+  if (n_units > slots && f.decode_hold == 2) {
     grid = slots;
-    const int per_wave = (int)((n_units + slots - 1) / slots);
-    hold_slots = std::min(per_wave, (10 * 1024) / row_bytes);
+    hold_slots = std::min((int)((n_units + slots - 1) / slots), (10 * 1024) / row_bytes);
   }
   const size_t lds_bytes = kDecodeStageBytes + (size_t)hold_slots * (row_bytes + 8);
 #define FSF_DECODE(DT, T, B16)                 \
   attn_decode_kernel<DT, T, B16><<<grid, 64, lds_bytes, stream>>>(p, f, (const T*)q, (const T*)k_cache, \
                                                                   (const T*)v_cache, (T*)out, hold_slots)
-  const bool b16 = p.block_size == 16;
   if (p.dtype == FSF_BF16) {
     if (b16) FSF_DECODE(FSF_BF16, bf16_t, true); else FSF_DECODE(FSF_BF16, bf16_t, false);
   } else {

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -83,10 +84,12 @@ struct WsLayout {
 // struct_bytes covers.
 struct Tuning {
   int decode_target_waves, decode_min_item_blocks;
-  bool min_item_blocks_given, decode_hold, prefill_split;
+  bool min_item_blocks_given, prefill_split;
+  int decode_hold;  // 0: results stored as units finish; 1: held back, eight-wave workgroups; 2: held back, single-wave workgroups
   int compute_units;  // 0: ask the device (only when a launch needs it)
   int max_decode_items_extra, max_prefill_split_units;
   int stream_max_slices;  // chunks of at most this many slices take the streaming kernel (0: one-row sequences only)
+  bool overlap;           // prompt-chunk tiles may run beside the streaming kernel on the library's second stream
 };
 
 Tuning resolve_tuning(const fsf_attn_cfg* c) {
@@ -99,12 +102,13 @@ Tuning resolve_tuning(const fsf_attn_cfg* c) {
   // no item shorter than 16 blocks, or 1024 keys where blocks are smaller than 64 tokens
   r.decode_min_item_blocks = r.min_item_blocks_given ? t.decode_min_item_blocks
                                                      : (c->block_size < 64 ? std::max(1, 1024 / c->block_size) : 16);
-  r.decode_hold = t.decode_hold >= 0;
+  r.decode_hold = t.decode_hold < 0 ? 0 : (t.decode_hold == 2 ? 2 : 1);
   r.prefill_split = t.prefill_split >= 0;
   r.compute_units = t.compute_units > 0 ? t.compute_units : 0;
   r.max_decode_items_extra = t.max_decode_items_extra > 0 ? t.max_decode_items_extra : fsf::kMaxDecodeItemsExtra;
   r.max_prefill_split_units = t.max_prefill_split_units > 0 ? std::min(t.max_prefill_split_units, fsf::kMaxPrefillSplitUnits)
                                                             : fsf::kMaxPrefillSplitUnits;
+  r.overlap = t.overlap > 0;
   r.stream_max_slices = t.stream_chunk_slices > 0 ? std::min(t.stream_chunk_slices, fsf::kMaxStreamSlices)
                                                   : (t.stream_chunk_slices < 0 ? 0 : fsf::kDefaultStreamSlices);
   return r;
@@ -392,6 +396,63 @@ extern "C" size_t fsf_ragged_attention_workspace_bytes(const fsf_attn_cfg* cfg, 
 
 namespace {
 
+// A second stream and two events per device, created on first use and kept until the process
+// ends (host-side runtime objects; no device memory).  Default priority, like the caller's.
+constexpr int kMaxOverlapUnits = 16;  // compute units the streaming kernel gives up without slowing down
+
+constexpr int kSideEvents = 16;       // fork/join event pairs used in turn, so that a pair is not recorded again
+                                      // while a pass a few calls back may still be waiting on it
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork[kSideEvents] = {}, join[kSideEvents] = {};
+  unsigned next = 0;
+  bool ok = false, tried = false;
+};
+SideStream g_side[64];
+std::mutex g_side_mutex;
+
+SideStream* side_stream() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  SideStream& s = g_side[dev];
+  if (!s.tried) {
+    s.tried = true;
+    s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; i < kSideEvents && s.ok; ++i)
+      s.ok = hipEventCreateWithFlags(&s.fork[i], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&s.join[i], hipEventDisableTiming) == hipSuccess;
+  }
+  return s.ok ? &s : nullptr;
+}
+
+// How many compute units the prompt-chunk tiles of a pass get when they run beside the streaming
+// kernel, so that both finish at about the same time: their share of the pass's compute-unit
+// time (a tile step, 64 keys x 256 rows of one head, takes about 1.7 us of a unit, the up to 8
+// steps with masked scores 2 us more each, a workgroup 10 us more; the streaming kernel moves
+// about 6.7 TB/s with all units).  0: the share is too
+// large, run one kernel after the other.  Measured: the streaming kernel does not notice the
+// loss of 8 or 16 units (it is bound by HBM, and the prompt-chunk work hides behind it entirely:
+// the 2048- and 4096-token benchmark passes gain 3..6 %), but with a sixth of the units gone it
+// slows down by as much (passes of the long-prompt stream whose chunk is most of the budget:
+// 3 % slower than one after the other).
+int overlap_units(const std::vector<int>& tile_steps, int n_q_heads, int64_t stream_bytes, int cus) {
+  double pre_us = 0.0;
+  for (int st : tile_steps) pre_us += (1.7 * st + 2.0 * std::min(st, 8) + 10.0) * n_q_heads;   // unit-microseconds
+  const double dec_us = (double)stream_bytes / 6.7e6 * cus;           // unit-microseconds with all units
+  if (pre_us <= 0.0 || dec_us <= 0.0) return 0;
+  // Whole multiples of 8: workgroups are dealt to the chip's 8 dies in turn, so the streaming
+  // kernel's grid then leaves the same number of units empty on every die.  (With an uneven
+  // split some die is asked to hold one workgroup more than it has units; that workgroup starts
+  // when another has finished, and the launch lasts up to twice as long.)
+  const int units = std::max(8, (int)(cus * pre_us / (pre_us + dec_us) / 8.0 + 0.5) * 8);
+  return units <= kMaxOverlapUnits ? units : 0;
+}
+
+}  // namespace
+
+namespace {
+
 // Checks shared by the two attention entry points; FSF_OK means there is work to launch.
 int attention_args_ok(const fsf_attn_cfg* cfg, const void* q, const void* k_cache, const void* v_cache,
                       const fsf_seq_desc* descs_dev, const fsf_seq_desc* descs_host,
@@ -490,10 +551,61 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
   hipError_t e = fsf::launch_plan(p, f, stream);
   if (fused_launch(cfg)) {
     if (e == hipSuccess) e = fsf::launch_attn_fused(p, f, q, k_cache, v_cache, out, stream);
-  } else {
-    if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
-    if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
+    if (e == hipSuccess) e = fsf::launch_prefill_merge(p, f, out, stream);
+    if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
+    return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
   }
+  // A pass with both kinds of work, and more streaming units than the chip has wave slots: the
+  // prompt-chunk tiles run on the library's second stream, on the compute units the streaming
+  // kernel leaves empty for them, forked after the planning and joined before the call returns
+  // to the caller's stream.  Both kernels write disjoint rows of `out` and disjoint workspace.
+  SideStream* side = nullptr;
+  int reserve = 0;
+  if (tn.overlap && tn.decode_hold == 1 && n_pre > 0 && n_dec * cfg->n_kv_heads > 8 * (int64_t)cus) {
+    int64_t stream_bytes = 0;
+    for (int32_t s = 0; s < n_seqs; ++s) {
+      const fsf_seq_desc& d = descs_host[s];
+      if (!fsf::is_streaming(d.n_new, group, tn.stream_max_slices)) continue;
+      int lo, hi, tmp;
+      fsf::visible_range(d.n_cached, cfg->window, lo, tmp);
+      fsf::visible_range(d.n_cached + d.n_new - 1, cfg->window, tmp, hi);
+      stream_bytes += (int64_t)fsf::stream_slices(d.n_new, group) * (hi - lo + 1) * cfg->n_kv_heads * fsf::kHeadDim * 4;
+    }
+    reserve = overlap_units(prefill_tile_steps_of(cfg, tn, descs_host, n_seqs), cfg->n_q_heads, stream_bytes, cus);
+    side = reserve > 0 ? side_stream() : nullptr;
+    if (!side) reserve = 0;
+    // the tiles are cut for the units they will have
+    if (side) {
+      Tuning tside = tn;
+      tside.compute_units = reserve;
+      f.split = choose_prefill_split(cfg, tside, descs_host, n_seqs);
+    }
+  }
+  if (side) {
+    hipEvent_t fork, join;
+    {
+      std::lock_guard<std::mutex> lock(g_side_mutex);
+      fork = side->fork[side->next % kSideEvents];
+      join = side->join[side->next % kSideEvents];
+      ++side->next;
+    }
+    if (e == hipSuccess) e = hipEventRecord(fork, stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, fork, 0);
+    // `reserve` workgroups walk all tiles, the streaming kernel takes every other compute unit:
+    // whichever kernel starts first, the chip is divided the same way
+    if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, side->stream, reserve);
+    if (e == hipSuccess) e = fsf::launch_prefill_merge(p, f, out, side->stream);
+    // (the join is recorded even after an error, so that the caller's stream never waits on a
+    // fork that nothing follows)
+    const hipError_t ej = hipEventRecord(join, side->stream);
+    if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream, reserve);
+    if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
+    const hipError_t ew = ej == hipSuccess ? hipStreamWaitEvent(stream, join, 0) : ej;
+    if (e == hipSuccess) e = ew;
+    return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+  }
+  if (e == hipSuccess) e = fsf::launch_attn_prefill(p, f, q, k_cache, v_cache, out, stream);
+  if (e == hipSuccess) e = fsf::launch_attn_decode(p, f, q, k_cache, v_cache, out, stream);
   if (e == hipSuccess) e = fsf::launch_prefill_merge(p, f, out, stream);
   if (e == hipSuccess) e = fsf::launch_attn_merge(p, f, out, stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;

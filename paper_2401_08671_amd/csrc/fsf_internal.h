@@ -238,12 +238,15 @@ struct FastPlan {
 };
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);
+// reserve_units > 0: the streaming kernel leaves that many compute units entirely empty (for
+// prompt-chunk tiles running beside it on another stream); 0: it may use every wave slot
 hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
-                              const void* v_cache, void* out, hipStream_t stream);
+                              const void* v_cache, void* out, hipStream_t stream, int reserve_units = 0);
 hipError_t launch_attn_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream);
 hipError_t launch_prefill_merge(const Pass& p, const FastPlan& f, void* out, hipStream_t stream);
+// persistent_groups > 0: that many workgroups walk all tiles (the kernel occupies that many compute units)
 hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
-                               const void* v_cache, void* out, hipStream_t stream);
+                               const void* v_cache, void* out, hipStream_t stream, int persistent_groups = 0);
 // prompt-chunk tiles and generation-row items in ONE launch, so the two kinds of work overlap
 hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                              const void* v_cache, void* out, hipStream_t stream);

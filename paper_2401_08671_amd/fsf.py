@@ -33,7 +33,7 @@ class Tuning(C.Structure):
                 ("decode_min_item_blocks", C.c_int32), ("decode_hold", C.c_int32),
                 ("prefill_split", C.c_int32), ("compute_units", C.c_int32),
                 ("max_decode_items_extra", C.c_int32), ("max_prefill_split_units", C.c_int32),
-                ("stream_chunk_slices", C.c_int32)]
+                ("overlap", C.c_int32), ("stream_chunk_slices", C.c_int32)]
 
     def __init__(self, **kw):
         super().__init__(**kw)

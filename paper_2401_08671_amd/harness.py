@@ -41,7 +41,7 @@ def algorithmic_work(spec: wl.BatchSpec):
 class DeviceStep:
     """All device buffers of one step, generated on the GPU with seeded generators."""
 
-    def __init__(self, spec: wl.BatchSpec, device="cuda"):
+    def __init__(self, spec: wl.BatchSpec, device="cuda", tuning=None):
         self.spec = spec
         B, Hq, Hkv, d = spec.block_size, spec.n_q_heads, spec.n_kv_heads, spec.head_dim
         need = spec.blocks_needed()
@@ -60,7 +60,8 @@ class DeviceStep:
         wl.fill_pool_(self.k_cache, spec.value_mult, spec.seed * 7 + 4)
         wl.fill_pool_(self.v_cache, spec.value_mult, spec.seed * 7 + 5)
         self.out = torch.zeros((T, Hq, d), dtype=tdt, device=device)
-        self.cfg = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window, scale=spec.scale)
+        self.cfg = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window, scale=spec.scale,
+                                tuning=tuning)
         # same pass with prompt-chunk and generation-row work in one fused grid
         self.cfg_fused = fsf.make_cfg(Hq, Hkv, d, B, spec.dtype, self.num_blocks, window=spec.window,
                                       scale=spec.scale, flags=fsf.FSF_FLAG_FUSED_LAUNCH)
@@ -80,7 +81,7 @@ class StreamRunner:
     from a seeded generator (there is no model: the "generated token" is just a counter).
     """
 
-    def __init__(self, n_steps: int = 200, rate: float = 1.0, seed: int = 1005, device="cuda"):
+    def __init__(self, n_steps: int = 200, rate: float = 1.0, seed: int = 1005, device="cuda", tuning=None):
         shp = wl.stream_shape()
         self.Hq, self.Hkv, self.d, self.B = shp["n_q_heads"], shp["n_kv_heads"], shp["head_dim"], shp["block_size"]
         self.dtype, self.budget, self.n_steps = shp["dtype"], shp["token_budget"], n_steps
@@ -99,7 +100,7 @@ class StreamRunner:
         tdt = wl.TORCH_DTYPE[self.dtype]
         self.k_cache = torch.zeros((self.num_blocks, self.Hkv, self.B, self.d), dtype=tdt, device=device)
         self.v_cache = torch.zeros_like(self.k_cache)
-        self.cfg = fsf.make_cfg(self.Hq, self.Hkv, self.d, self.B, self.dtype, self.num_blocks)
+        self.cfg = fsf.make_cfg(self.Hq, self.Hkv, self.d, self.B, self.dtype, self.num_blocks, tuning=tuning)
         self.ws = fsf.alloc_workspace(self.cfg, self.max_seqs, self.budget, self.max_blocks, device)
         self.out = torch.zeros((self.budget, self.Hq, self.d), dtype=tdt, device=device)
         self.step_index = 0

@@ -11,7 +11,8 @@ from paper_2401_08671_amd import workloads as wl
 TOL = {"bf16": (2e-2, 2e-3), "f16": (2e-2, 2e-3), "f32": (1e-4, 1e-5)}
 
 
-def run_hip(step, flags: int = 0, return_cache: bool = True, repeat_append: int = 1, tuning=None):
+def run_hip(step, flags: int = 0, return_cache: bool = True, repeat_append: int = 1, tuning=None,
+            repeat_attention: int = 1):
     """Returns (k_cache_after, v_cache_after, out) as numpy storage arrays / float64 out."""
     sp = step.spec
     dev = "cuda"
@@ -27,7 +28,8 @@ def run_hip(step, flags: int = 0, return_cache: bool = True, repeat_append: int 
     ws = fsf.alloc_workspace(cfg, batch.n_seqs, batch.n_tokens, batch.max_blocks, dev)
     for _ in range(repeat_append):
         fsf.kv_append(cfg, k_new, v_new, kc, vc, batch)
-    fsf.ragged_attention(cfg, q, kc, vc, batch, out, ws)
+    for _ in range(repeat_attention):          # back to back, no wait in between
+        fsf.ragged_attention(cfg, q, kc, vc, batch, out, ws)
     torch.cuda.synchronize()
     out64 = out.to(torch.float64).cpu().numpy()
     if return_cache:

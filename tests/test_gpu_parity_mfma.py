@@ -144,17 +144,42 @@ def test_prefill_tiles_split_along_keys(units, window, dtype):
 
 @pytest.mark.parametrize("heads,n_rows,block,dtype", [((16, 1), 5000, 64, "bf16"), ((8, 4), 1300, 64, "bf16"),
                                                       ((4, 4), 700, 64, "bf16"), ((8, 4), 1300, 16, "f16")])
-def test_more_generation_row_units_than_wave_slots(heads, n_rows, block, dtype):
+@pytest.mark.parametrize("hold", [0, 2, -1])
+def test_more_generation_row_units_than_wave_slots(heads, n_rows, block, dtype, hold):
     """With more units than resident waves the generation-row kernel runs as one round of waves
     that walk several units each and hold their results in LDS until the end: 16 heads per KV head
     leave room for two held units (stored whenever both slots are full), 2 heads for all of them;
-    the third shape stays below the wave slots and takes the one-unit-per-workgroup form."""
+    the third shape stays below the wave slots and takes the one-unit-per-workgroup form.  hold 0:
+    eight-wave workgroups, one per compute unit (consecutive launch slots where a workgroup covers
+    whole sequences' KV heads, strided otherwise); 2: single-wave workgroups; -1: nothing held."""
     Hq, Hkv = heads
     rng = np.random.default_rng(36)
     seqs = [(1, int(c)) for c in rng.integers(0, 200, size=n_rows)]
     seqs[7] = (1, 5000)                       # one long row: cut into units with partial results
     spec = wl.BatchSpec("manyunits", Hq, Hkv, 128, block, dtype, seqs, seed=36)
-    check_step(Step(spec, poison="nan"), f"{n_rows} rows, heads {heads}, block {block}, {dtype}")
+    check_step(Step(spec, poison="nan"), f"{n_rows} rows, heads {heads}, block {block}, {dtype}, hold {hold}",
+               tuning=fsf.Tuning(decode_hold=hold))
+
+
+@pytest.mark.parametrize("heads", [(8, 2), (40, 40), (6, 3)])
+def test_prompt_chunks_beside_the_streaming_kernel(heads):
+    """overlap = 1: the prompt-chunk tiles run on the library's second stream, walked by a few
+    persistent workgroups, while the streaming kernel leaves those compute units empty; forked and
+    joined inside the call.  Two passes back to back without a wait in between, then the same pass
+    again: equal bits, and the oracle's result."""
+    Hq, Hkv = heads
+    rng = np.random.default_rng(88)
+    seqs = [(1, int(c)) for c in rng.integers(0, 400, size=1500)] + [(300, 100), (40, 3), (700, 0), (1, 3000)]
+    spec = wl.BatchSpec("overlap", Hq, Hkv, 128, 64, "bf16", seqs, seed=88)
+    st = Step(spec, poison="nan")
+    tn = fsf.Tuning(overlap=1)
+    _, _, ref = st.oracle()
+    _, _, a = run_hip(st, tuning=tn, return_cache=False)
+    _, _, b = run_hip(st, tuning=tn, return_cache=False, repeat_attention=3)
+    assert_outputs_close(a, ref, "bf16", f"overlap heads {heads}")
+    assert np.array_equal(a, b)
+    _, _, c = run_hip(st, tuning=fsf.Tuning(overlap=-1), return_cache=False)
+    assert np.array_equal(a, c), "the partition of the work is the same with and without the second stream"
 
 
 def test_fifty_thousand_sequences():
@@ -356,13 +381,17 @@ def test_random_ragged_batches(seed):
     check_step(Step(spec, poison="nan"), f"random batch {seed}: Hq={Hq} Hkv={Hkv} B={block} W={window} {dtype} {seqs}", tuning=tn)
 
 
-def test_a_pass_can_be_captured_in_a_graph_and_replayed():
+@pytest.mark.parametrize("overlap", [0, 1])
+def test_a_pass_can_be_captured_in_a_graph_and_replayed(overlap):
     """Append + attention of a mixed pass recorded into a HIP graph (the library allocates nothing,
     clears nothing with memset and waits for nothing): every replay, with eager work and
     synchronisation in between, gives the bits of the eager run, which is checked against the oracle."""
     from paper_2401_08671_amd.harness import DeviceStep
-    spec = wl.BatchSpec("graph", 8, 2, 128, 64, "bf16", [(300, 100), (1, 2000), (1, 63), (700, 0), (1, 5000)], seed=35)
-    ds = DeviceStep(spec)
+    seqs = [(300, 100), (1, 2000), (1, 63), (700, 0), (1, 5000)]
+    if overlap:          # enough generation rows for the one-round streaming grid, so that the fork to the
+        seqs += [(1, 40 + (7 * i) % 300) for i in range(1200)]      # second stream is part of the recorded graph
+    spec = wl.BatchSpec("graph", 8, 2, 128, 64, "bf16", seqs, seed=35)
+    ds = DeviceStep(spec, tuning=fsf.Tuning(overlap=overlap))
     ds.step()
     torch.cuda.synchronize()
     eager = ds.out.clone()
