@@ -266,9 +266,9 @@ int fsf_ragged_attention(const fsf_attn_cfg* cfg, const void* q, const void* k_c
  * The cutting of generation rows and prompt-chunk tiles into units with partial results is
  * limited to what fits the array (at most 1024 extra row units and 64 tile units, fewer for
  * passes with many heads); a pass whose work tables alone exceed the array (millions of
- * tokens) is refused with FSF_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share the array: calls that overlap on one GPU (two
- * streams, two threads) race and give wrong results; calls on one stream, or ordered by
- * events, are safe.  The first call on a device looks the array's address up and should be
+ * tokens) is refused with FSF_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share
+ * the array: calls that overlap on one GPU (two streams, two threads) race and give wrong
+ * results; calls on one stream, or ordered by events, are safe.  The first call on a device looks the array's address up and should be
  * made outside a graph capture.  Errors otherwise as fsf_ragged_attention.
  */
 #define FSF_STATIC_SCRATCH_BYTES (64u << 20)

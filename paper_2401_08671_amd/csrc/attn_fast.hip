@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_persistent_kernel(Pa
 // slots are full).  The rows' writes then come at the end of the kernel, when the reads thin
 // out, instead of being sprinkled into the read stream, where they cost several times their bytes.
 template <int DT, typename T, bool kBlock16>
-__global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
+__global__ __launch_bounds__(64, 2) void attn_decode_single_kernel(Pass p, FastPlan f,
                                                                 const T* __restrict__ q,
                                                                 const T* __restrict__ kc,
                                                                 const T* __restrict__ vc,
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64, 2) void attn_decode_kernel(Pass p, FastPlan f,
 // measured +11 % beside one foreign wave, +23 % beside one prompt-chunk workgroup.)
 constexpr int kWideWaves = 8;
 template <int DT, typename T, bool kBlock16>
-__global__ __launch_bounds__(64 * kWideWaves) void attn_decode_wide_kernel(Pass p, FastPlan f,
+__global__ __launch_bounds__(64 * kWideWaves) void attn_decode_kernel(Pass p, FastPlan f,
                                                                            const T* __restrict__ q,
                                                                            const T* __restrict__ kc,
                                                                            const T* __restrict__ vc,
@@ -249,11 +249,11 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
   {                                                                                                              \
     static bool attr_set = false;                                                                                \
     if (!attr_set) {                                                                                             \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_wide_kernel<DT, T, B16>),             \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<DT, T, B16>),             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                         \
       attr_set = true;                                                                                           \
     }                                                                                                            \
-    attn_decode_wide_kernel<DT, T, B16><<<groups, 64 * kWideWaves, lds_bytes, stream>>>(                         \
+    attn_decode_kernel<DT, T, B16><<<groups, 64 * kWideWaves, lds_bytes, stream>>>(                         \
         p, f, (const T*)q, (const T*)k_cache, (const T*)v_cache, (T*)out, hold_slots, lds_per_wave);             \
   }
     if (p.dtype == FSF_BF16) {
@@ -274,7 +274,7 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
   }
   const size_t lds_bytes = kDecodeStageBytes + (size_t)hold_slots * (row_bytes + 8);
 #define FSF_DECODE(DT, T, B16)                 \
-  attn_decode_kernel<DT, T, B16><<<grid, 64, lds_bytes, stream>>>(p, f, (const T*)q, (const T*)k_cache, \
+  attn_decode_single_kernel<DT, T, B16><<<grid, 64, lds_bytes, stream>>>(p, f, (const T*)q, (const T*)k_cache, \
                                                                   (const T*)v_cache, (T*)out, hold_slots)
   if (p.dtype == FSF_BF16) {
     if (b16) FSF_DECODE(FSF_BF16, bf16_t, true); else FSF_DECODE(FSF_BF16, bf16_t, false);

@@ -234,7 +234,7 @@ struct FastPlan {
   int32_t stream_max_slices;  // chunks of at most this many slices take the streaming kernel
   int32_t n_dec_items, n_pre_tiles, n_split_rows;  // host-side totals (grid sizes)
   PrefillSplit split;       // which prompt-chunk tiles are cut along their keys
-  int32_t decode_hold;      // host side: streaming waves may hold finished rows back (see attn_decode_kernel)
+  int32_t decode_hold;      // host side: streaming waves may hold finished rows back (see attn_decode_kernel in attn_fast.hip)
 };
 
 hipError_t launch_plan(const Pass& p, const FastPlan& f, hipStream_t stream);

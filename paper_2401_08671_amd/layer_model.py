@@ -18,6 +18,7 @@ number of generation rows plus one prompt chunk that fills the rest (Sec. 3.2).
 
     python -m paper_2401_08671_amd.layer_model            # the linear maps alone (both backends); one JSON object
     python -m paper_2401_08671_amd.layer_model --layer    # the whole layer with attention
+    python -m paper_2401_08671_amd.layer_model --gemm T N K   # one linear map 12 times through either backend (for profilers)
 """
 from __future__ import annotations
 
@@ -162,8 +163,24 @@ class MeasuredLinear:
         return self.n_layers * per_layer
 
 
+def run_one_gemm(T: int, N: int, K: int, reps: int = 12, device="cuda"):
+    """y = x w^T for x [T, K], w [N, K], `reps` times through fsf_linear and through the vendor library."""
+    g = torch.Generator(device=device).manual_seed(1)
+    mk = lambda *s: (torch.randn(*s, generator=g, device=device, dtype=torch.float32) * 0.05).to(torch.bfloat16)
+    ws, x = [mk(N, K) for _ in range(3)], mk(T, K)
+    for backend in ("fsf", "vendor"):
+        for i in range(reps):
+            _linear(backend, x, ws[i % 3])
+    torch.cuda.synchronize()
+
+
 def main():
     assert torch.cuda.is_available(), "needs a GPU"
+    if "--gemm" in sys.argv[1:]:
+        i = sys.argv.index("--gemm")
+        run_one_gemm(*(int(a) for a in sys.argv[i + 1:i + 4]))
+        print("done")
+        return
     if "--layer" in sys.argv[1:]:
         json.dump(dict(shape=SHAPE_13B, rows=measure_layer(), rows_vendor_gemm=measure_layer(backend="vendor")), sys.stdout)
         print()

@@ -32,7 +32,7 @@ import csv
 import json
 import os
 
-KERNELS = ("attn_decode_kernel", "attn_prefill_kernel", "attn_fused_kernel", "kv_append_kernel",
+KERNELS = ("attn_decode_single_kernel", "attn_decode_kernel", "attn_prefill_kernel", "attn_fused_kernel", "kv_append_kernel",
            "prefill_merge_kernel", "merge_kernel", "plan_kernel", "attn_generic_kernel", "gemm_kernel")
 BENCH_ARGS = "--no-cpu-baseline --no-ceilings --no-sustained"
 
