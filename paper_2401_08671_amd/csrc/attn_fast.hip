@@ -1,12 +1,16 @@
 // Kernels of the matrix-core attention path and their launchers.
 //
 // A Dynamic SplitFuse pass mixes prompt chunks (dense, matrix-core bound) with one-token
-// generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  By default
-// each kind of work gets its own launch with the workgroup shape that suits it (256-thread
-// tiles with 64 KB of LDS, two to a compute unit; 64-thread streaming units).  Both kernels
-// fill the register file at two waves per SIMD, so they cannot share a compute unit and a
-// single fused grid (kept behind a flag: it saves one launch for tiny passes) measured no
-// faster than the sum.
+// generations (streaming, HBM bound) at a fixed token budget (paper Sec. 3.2).  Each kind of
+// work gets its own launch with the workgroup shape that suits it: 256-thread tiles with
+// 64 KB of LDS, two to a compute unit, for the chunks; for the streaming work one eight-wave
+// workgroup per compute unit, a persistent grid that walks the (sequence, KV head, key range)
+// units (a 64-thread kernel, one unit per workgroup, serves passes too small to fill the
+// chip).  Both kernels fill the register file at two waves per SIMD, so they cannot share a
+// compute unit; a single fused grid (kept behind a flag: it saves one launch for tiny
+// passes) measured no faster than the sum.  A persistent form of the tile kernel can run
+// beside the streaming grid on compute units that grid leaves free (an option, off by
+// default).
 #include "attn_decode_body.h"
 #include "attn_prefill_body.h"
 

@@ -123,7 +123,20 @@ def test_pool_sweep_occupancy_and_the_stuck_case():
 
 @pytest.mark.gpu
 def test_measured_attention_runs_a_small_closed_loop():
+    """with a closed loop the composer's decisions do not depend on how long a pass takes, so the
+    measured run takes the passes of the modelled one; its clock is the measured kernels' time"""
     reqs = wl.chat_requests(6, prompt_mean=700, gen_mean=6, seed=3)
     out = sim.run("splitfuse", reqs, 3, token_budget=512, measured=True)
-    assert out["requests"] == 6 and out["attention_gpu_s_one_layer_total"] > 0
-    assert math.isfinite(out["token_latency_p95_s"])
+    modelled = sim.run("splitfuse", reqs, 3, token_budget=512, measured=False)
+    assert out["requests"] == 6 and out["passes"] == modelled["passes"]
+    assert math.isfinite(out["token_latency_p95_s"]) and out["token_latency_p50_s"] > 0
+    att = out["attention_gpu_s_one_layer_total"]
+    model = sim.ForwardModel()
+    # no pass is faster than its bytes at the HBM peak: every prompt token's K and V rows are
+    # written once and read at least once, over all passes of the run
+    tokens = sum(p + g for p, g in reqs)
+    floor = 4 * model.n_kv_heads * model.head_dim * model.elem_bytes * tokens / 8e12
+    assert floor < att < 0.5
+    # the run's clock holds every layer's attention plus the other parts of each pass
+    assert out["total_time_s"] > model.n_layers * att + out["passes"] * model.fixed_s
+    assert out["total_time_s"] < out["passes"] * 0.25
