@@ -251,12 +251,8 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
     const size_t lds_bytes = (size_t)lds_per_wave * kWideWaves;
 #define FSF_DECODE_WIDE(DT, T, B16)                                                                              \
   {                                                                                                              \
-    static bool attr_set = false;                                                                                \
-    if (!attr_set) {                                                                                             \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<DT, T, B16>),             \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                         \
-      attr_set = true;                                                                                           \
-    }                                                                                                            \
+    if (const hipError_t e = allow_lds_bytes<&attn_decode_kernel<DT, T, B16>>(160 * 1024); e != hipSuccess)      \
+      return e;                                                                                                  \
     attn_decode_kernel<DT, T, B16><<<groups, 64 * kWideWaves, lds_bytes, stream>>>(                         \
         p, f, (const T*)q, (const T*)k_cache, (const T*)v_cache, (T*)out, hold_slots, lds_per_wave);             \
   }

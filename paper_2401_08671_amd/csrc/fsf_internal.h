@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdint.h>
 
 #include "fsf.h"
@@ -250,6 +252,24 @@ hipError_t launch_attn_prefill(const Pass& p, const FastPlan& f, const void* q, 
 // prompt-chunk tiles and generation-row items in ONE launch, so the two kinds of work overlap
 hipError_t launch_attn_fused(const Pass& p, const FastPlan& f, const void* q, const void* k_cache,
                              const void* v_cache, void* out, hipStream_t stream);
+
+// A kernel that uses more than 64 KB of dynamic LDS has to ask for it, once per device: called
+// before every such launch, does the asking on the first call on each device.
+template <auto Kernel>
+inline hipError_t allow_lds_bytes(int bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<bool> done[kMaxDevices];
+  int dev = 0;
+  if (const hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!done[dev].load(std::memory_order_acquire)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    done[dev].store(true, std::memory_order_release);
+  }
+  return hipSuccess;
+}
 
 // Optional per-kernel timing (see fsf_profile_enable): brackets a launch with HIP events.
 struct PhaseTimer {

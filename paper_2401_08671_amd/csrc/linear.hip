@@ -246,12 +246,9 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M
   const size_t lds_bytes = (size_t)stages * (bm + bn) * kRowBytes;
 #define FSF_LINEAR(DT, T, BM, BN, WM, WN, ST)                                                       \
   {                                                                                                 \
-    static bool attr_set = false;                                                                   \
-    if (!attr_set) {                                                                                \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&linear_kernel<DT, T, BM, BN, WM, WN, ST>), \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);        \
-      attr_set = true;                                                                              \
-    }                                                                                               \
+    if (const hipError_t e = allow_lds_bytes<&linear_kernel<DT, T, BM, BN, WM, WN, ST>>((int)lds_bytes); \
+        e != hipSuccess)                                                                            \
+      return e;                                                                                     \
     linear_kernel<DT, T, BM, BN, WM, WN, ST><<<grid, (BM / WM) * (BN / WN) * 64, lds_bytes, stream>>>( \
         (const T*)x, (const T*)w, (T*)y, M, N, K, tiles_m, tiles_n);                                \
   }
