@@ -95,6 +95,8 @@ typedef struct {
                                    /* beside the streaming kernel on a second stream the library keeps per */
                                    /* device, on 8 or 16 compute units the streaming kernel leaves empty;  */
                                    /* forked from and joined to the caller's stream inside the call.       */
+                                   /* 8 or more: the same on exactly this many units (a multiple of 8, at  */
+                                   /* most half the chip), whatever the share of the prompt-chunk work.    */
                                    /* Default (0) and -1: one kernel after the other, which measured       */
                                    /* faster on most passes                                               */
   int32_t stream_chunk_slices;     /* a prompt chunk of at most this many slices of 16 / (query heads    */

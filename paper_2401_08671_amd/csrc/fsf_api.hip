@@ -89,7 +89,8 @@ struct Tuning {
   int compute_units;  // 0: ask the device (only when a launch needs it)
   int max_decode_items_extra, max_prefill_split_units;
   int stream_max_slices;  // chunks of at most this many slices take the streaming kernel (0: one-row sequences only)
-  bool overlap;           // prompt-chunk tiles may run beside the streaming kernel on the library's second stream
+  int overlap;            // 0: one kernel after the other; 1: prompt-chunk tiles beside the streaming kernel on the
+                          // library's second stream, units from the cost model; >= 8: on exactly this many units
 };
 
 Tuning resolve_tuning(const fsf_attn_cfg* c) {
@@ -108,7 +109,7 @@ Tuning resolve_tuning(const fsf_attn_cfg* c) {
   r.max_decode_items_extra = t.max_decode_items_extra > 0 ? t.max_decode_items_extra : fsf::kMaxDecodeItemsExtra;
   r.max_prefill_split_units = t.max_prefill_split_units > 0 ? std::min(t.max_prefill_split_units, fsf::kMaxPrefillSplitUnits)
                                                             : fsf::kMaxPrefillSplitUnits;
-  r.overlap = t.overlap > 0;
+  r.overlap = t.overlap >= 8 ? (t.overlap / 8) * 8 : (t.overlap > 0 ? 1 : 0);
   r.stream_max_slices = t.stream_chunk_slices > 0 ? std::min(t.stream_chunk_slices, fsf::kMaxStreamSlices)
                                                   : (t.stream_chunk_slices < 0 ? 0 : fsf::kDefaultStreamSlices);
   return r;
@@ -571,7 +572,9 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
       fsf::visible_range(d.n_cached + d.n_new - 1, cfg->window, tmp, hi);
       stream_bytes += (int64_t)fsf::stream_slices(d.n_new, group) * (hi - lo + 1) * cfg->n_kv_heads * fsf::kHeadDim * 4;
     }
-    reserve = overlap_units(prefill_tile_steps_of(cfg, tn, descs_host, n_seqs), cfg->n_q_heads, stream_bytes, cus);
+    reserve = tn.overlap >= 8 ? std::min(tn.overlap, cus / 2 / 8 * 8)
+                              : overlap_units(prefill_tile_steps_of(cfg, tn, descs_host, n_seqs), cfg->n_q_heads,
+                                              stream_bytes, cus);
     side = reserve > 0 ? side_stream() : nullptr;
     if (!side) reserve = 0;
     // the tiles are cut for the units they will have
