@@ -74,7 +74,9 @@ typedef enum { FSF_F32 = 0, FSF_BF16 = 1, FSF_F16 = 2 } fsf_dtype;
 typedef struct {
   int32_t struct_bytes;
   int32_t decode_target_waves;     /* about how many streaming wave units a pass is at least cut into   */
-                                   /* (default 4096 = two rounds of the chip's wave slots)              */
+                                   /* (default 4096 = two rounds of the chip's wave slots; by default a  */
+                                   /* pass whose units nearly all come from cut rows is then cut a little */
+                                   /* coarser until its units fill whole rounds, a given value is kept)   */
   int32_t decode_min_item_blocks;  /* no cut of a row's keys leaves fewer cache blocks than this per     */
                                    /* unit (default 16, or 1024 tokens' worth for blocks below 64        */
                                    /* tokens; a quarter of that in passes with fewer units than compute   */

@@ -84,7 +84,7 @@ struct WsLayout {
 // struct_bytes covers.
 struct Tuning {
   int decode_target_waves, decode_min_item_blocks;
-  bool min_item_blocks_given, prefill_split;
+  bool min_item_blocks_given, target_waves_given, prefill_split;
   int decode_hold;  // 0: results stored as units finish; 1: held back, eight-wave workgroups; 2: held back, single-wave workgroups
   int compute_units;  // 0: ask the device (only when a launch needs it)
   int max_decode_items_extra, max_prefill_split_units;
@@ -100,6 +100,7 @@ Tuning resolve_tuning(const fsf_attn_cfg* c) {
   Tuning r;
   r.decode_target_waves = t.decode_target_waves > 0 ? t.decode_target_waves : 4096;
   r.min_item_blocks_given = t.decode_min_item_blocks > 0;
+  r.target_waves_given = t.decode_target_waves > 0;
   // no item shorter than 16 blocks, or 1024 keys where blocks are smaller than 64 tokens
   r.decode_min_item_blocks = r.min_item_blocks_given ? t.decode_min_item_blocks
                                                      : (c->block_size < 64 ? std::max(1, 1024 / c->block_size) : 16);
@@ -516,13 +517,14 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
   f.split_blocks = (int32_t)std::min<int64_t>(sb, 1 << 30);
   f.min_item_blocks = min_item_blocks;
   f.stream_max_slices = tn.stream_max_slices;
-  int64_t n_dec = 0, n_pre = 0, n_split_rows = 0, n_prows = 0;
+  int64_t n_dec = 0, n_pre = 0, n_split_rows = 0, n_prows = 0, n_dec_cut = 0;  // n_dec_cut: items of sequences with cut keys
   auto count_work = [&] {
-    n_dec = n_pre = n_split_rows = n_prows = 0;
+    n_dec = n_pre = n_split_rows = n_prows = n_dec_cut = 0;
     for (int32_t s = 0; s < n_seqs; ++s) {
       const fsf::SeqWork sw = fsf::seq_work(descs_host[s].n_new, descs_host[s].n_cached, cfg->window, cfg->block_size,
                                             group, f.stream_max_slices, f.split_blocks, f.min_item_blocks);
       n_dec += sw.dec_items;
+      n_dec_cut += sw.cuts > 1 ? sw.dec_items : 0;
       n_pre += sw.pre_tiles;
       n_split_rows += sw.cuts > 1 ? descs_host[s].n_new : 0;
       n_prows += sw.prows;
@@ -534,6 +536,28 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
   if (n_dec * cfg->n_kv_heads < cus && !tn.min_item_blocks_given) {
     f.min_item_blocks = std::max(1, min_item_blocks / 4);
     count_work();
+  }
+  // With only a few rounds of the wave slots, a round that is barely begun still lasts as long as
+  // a unit: 2.2 rounds of equal units take as long as 3.  Coarsen the cuts a little until the
+  // units fill whole rounds.  Only where nearly all units come from cut sequences, so that they
+  // are about equally long: in a pass of many uncut rows of all lengths and a few long cut ones,
+  // longer cuts only lengthen the longest units (measured on the long-prompt stream: 1..4 % slower).
+  if (tn.decode_hold == 1 && !tn.target_waves_given) {  // (a caller who names the number of units gets it)
+    const int64_t slots = (int64_t)cus * 8;
+    for (int it = 0; it < 16 && n_dec_cut * 5 >= n_dec * 4 && f.split_blocks < (1 << 28); ++it) {
+      const int64_t units = n_dec * cfg->n_kv_heads;
+      const int64_t full = units / slots, excess = units % slots;
+      // fine as it is: whole rounds, a last round at least 80 % full, or so many rounds that one more hardly counts
+      if (full < 1 || full >= 5 || excess == 0 || excess * 5 >= slots * 4) break;
+      const int32_t before = f.split_blocks;
+      f.split_blocks += std::max(1, f.split_blocks / 24);
+      count_work();
+      if (n_dec * cfg->n_kv_heads * 10 < full * slots * 9) {  // a step too far: a tenth of the last whole round left empty
+        f.split_blocks = before;
+        count_work();
+        break;
+      }
+    }
   }
   // the partial results must fit their section: coarsen the cuts until they do (with cuts as
   // long as the longest sequence nothing is cut and nothing is needed)

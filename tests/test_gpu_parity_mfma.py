@@ -202,6 +202,19 @@ def test_very_long_contexts(window):
     check_step(Step(spec), f"long contexts window={window}")
 
 
+@pytest.mark.parametrize("given", [False, True])
+def test_few_long_rows_cut_by_the_default_rules(given):
+    """100 rows over 8000..16000 cached tokens with 8 KV heads: every row is cut, the units come to
+    a little over two rounds of the wave slots, and the default rules then cut a little coarser so
+    that the units fill two rounds (a named number of units is taken as given).  Whatever the
+    cuts, the oracle's result."""
+    rng = np.random.default_rng(12)
+    seqs = [(1, int(c)) for c in rng.integers(8000, 16000, size=100)]
+    spec = wl.BatchSpec("fewlong", 8, 8, 128, 64, "bf16", seqs, seed=77)
+    check_step(Step(spec), f"few long rows, units given: {given}",
+               tuning=fsf.Tuning(decode_target_waves=4096) if given else None)
+
+
 @pytest.mark.parametrize("mult", [1.0, 1.0 / np.sqrt(128.0)])
 @pytest.mark.parametrize("block", [16, 64])
 def test_every_unit_of_a_cut_generation_row_counts(mult, block):
