@@ -217,6 +217,22 @@ int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, int32_t n_t
                int32_t k, void* hip_stream);
 
 /*
+ * The same product with a device workspace, which lets the library cut k into parts where the
+ * output tiles alone would leave compute units idle (few tokens and a narrow output: a pass in
+ * the weight-bound regime of paper Sec. 3.1 is then bound by how fast the few busy units pull
+ * the weights from HBM).  Each part leaves an fp32 partial result in the workspace and a second
+ * kernel sums them in a fixed order and rounds once, so results are deterministic and within
+ * fsf_linear's tolerance (not bit-equal to it: another summation order).
+ * fsf_linear_workspace_bytes: bytes that let every cut the library would choose for this shape
+ * happen (0: it would not cut; also 0 for shapes fsf_linear refuses).  A smaller or NULL
+ * workspace means fewer parts or none, never an error; a workspace that is not 16-byte aligned
+ * is FSF_ERR_WORKSPACE.  The workspace is scratch: nothing is kept in it between calls.
+ */
+size_t fsf_linear_workspace_bytes(int32_t n_tokens, int32_t n_out, int32_t k);
+int fsf_linear_ws(int32_t dtype, const void* x, const void* w, void* y, int32_t n_tokens, int32_t n_out,
+                  int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Bytes of device workspace fsf_ragged_attention needs for a pass of at most n_seqs
  * sequences, n_tokens tokens and max_blocks table columns.  Never zero (a small plan
  * area is always used); 256-byte aligned sizes.  Returns 0 on invalid cfg.  On the

@@ -185,17 +185,6 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
   }
 }
 
-int decode_compute_units() {
-  static int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
-
 unsigned decode_groups(const Pass& p, const FastPlan& f) {
   const int64_t units = (int64_t)f.n_dec_items * p.n_kv_heads;
   return (unsigned)((units + kUnitsPerGroup - 1) / kUnitsPerGroup);
@@ -237,14 +226,14 @@ hipError_t launch_attn_decode(const Pass& p, const FastPlan& f, const void* q, c
   const unsigned n_units = (unsigned)f.n_dec_items * p.n_kv_heads;
   const int row_bytes = p.group * kHeadDim * 2;
   const bool b16 = p.block_size == 16;
-  const unsigned slots = 8u * (unsigned)decode_compute_units();
+  const unsigned slots = 8u * (unsigned)device_compute_units();
   if (n_units > slots && f.decode_hold == 1) {
     // More units than wave slots: one round of waves that hold their results back, as one
     // workgroup of eight waves per compute unit (on all units but the reserved ones).  LDS per
     // wave: the staging area, up to 10 KB of finished rows, their addresses; at least 12 KB, so
     // that a workgroup takes 96 KB and no second one fits beside it: every unit then holds exactly
     // eight waves (single-wave workgroups spread unevenly over the units: 2..4 % slower).
-    const unsigned groups = (unsigned)std::max(1, decode_compute_units() - reserve_units);
+    const unsigned groups = (unsigned)std::max(1, device_compute_units() - reserve_units);
     const int per_wave = (int)((n_units + groups * kWideWaves - 1) / (groups * kWideWaves));
     const int hold_slots = std::max(1, std::min(per_wave, (10 * 1024) / row_bytes));
     const int lds_per_wave = std::max(12 * 1024, (kDecodeStageBytes + hold_slots * (row_bytes + 8) + 15) & ~15);

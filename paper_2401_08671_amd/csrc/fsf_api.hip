@@ -160,16 +160,7 @@ WsLayout ws_layout(const fsf_attn_cfg* c, const Tuning& tn, int32_t n_seqs, int3
   return w;
 }
 
-int compute_units() {
-  static int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
-      cu = 256;
-    return cu;
-  }();
-  return n;
-}
+int compute_units() { return fsf::device_compute_units(); }
 
 // Which prompt-chunk tiles are cut along their keys (see PrefillSplit).  n_steps[t] = 64-key
 // steps of tile t.  Workgroups (tile x head) take one compute unit each.
@@ -375,8 +366,10 @@ extern "C" int fsf_rotary_q(const fsf_attn_cfg* cfg, void* q, const fsf_seq_desc
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }
 
-extern "C" int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, int32_t n_tokens, int32_t n_out,
-                          int32_t k, void* hip_stream) {
+namespace {
+
+int linear_args_ok(int32_t dtype, const void* x, const void* w, const void* y, int32_t n_tokens, int32_t n_out,
+                   int32_t k) {
   if (n_tokens < 0 || n_out < 1 || k < 1) return FSF_ERR_INVALID_ARG;
   if (dtype != FSF_BF16 && dtype != FSF_F16 && dtype != FSF_F32) return FSF_ERR_INVALID_ARG;
   if (n_tokens == 0) return FSF_OK;
@@ -385,7 +378,32 @@ extern "C" int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, 
   if (dtype == FSF_F32 || n_out % 256 || k % 64 || (int64_t)n_tokens * k * 2 >= (1ll << 31) ||
       (int64_t)n_out * k * 2 >= (1ll << 31))
     return FSF_ERR_UNSUPPORTED;
-  const hipError_t e = fsf::launch_linear(dtype, x, w, y, n_tokens, n_out, k, (hipStream_t)hip_stream);
+  return FSF_OK;
+}
+
+}  // namespace
+
+extern "C" int fsf_linear(int32_t dtype, const void* x, const void* w, void* y, int32_t n_tokens, int32_t n_out,
+                          int32_t k, void* hip_stream) {
+  const int st = linear_args_ok(dtype, x, w, y, n_tokens, n_out, k);
+  if (st != FSF_OK || n_tokens == 0) return st;
+  const hipError_t e = fsf::launch_linear(dtype, x, w, y, n_tokens, n_out, k, nullptr, 0, (hipStream_t)hip_stream);
+  return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
+}
+
+extern "C" size_t fsf_linear_workspace_bytes(int32_t n_tokens, int32_t n_out, int32_t k) {
+  if (n_tokens < 1 || n_out < 1 || k < 1 || n_out % 256 || k % 64) return 0;
+  const int splits = fsf::linear_splits(n_tokens, n_out, k, compute_units(), ~(size_t)0);
+  return splits > 1 ? align256((size_t)splits * n_tokens * n_out * sizeof(float)) : 0;
+}
+
+extern "C" int fsf_linear_ws(int32_t dtype, const void* x, const void* w, void* y, int32_t n_tokens, int32_t n_out,
+                             int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int st = linear_args_ok(dtype, x, w, y, n_tokens, n_out, k);
+  if (st != FSF_OK || n_tokens == 0) return st;
+  if (workspace && ((uintptr_t)workspace & 15)) return FSF_ERR_WORKSPACE;
+  const hipError_t e = fsf::launch_linear(dtype, x, w, y, n_tokens, n_out, k, workspace, workspace ? workspace_bytes : 0,
+                                          (hipStream_t)hip_stream);
   return e == hipSuccess ? FSF_OK : FSF_ERR_HIP;
 }
 

@@ -271,6 +271,18 @@ inline hipError_t allow_lds_bytes(int bytes) {
   return hipSuccess;
 }
 
+// Compute units of the current device (asked once; 256 if the runtime does not say).
+inline int device_compute_units() {
+  static const int n = [] {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
+      cu = 256;
+    return cu;
+  }();
+  return n;
+}
+
 // Optional per-kernel timing (see fsf_profile_enable): brackets a launch with HIP events.
 struct PhaseTimer {
   PhaseTimer(int phase, hipStream_t stream);
@@ -287,8 +299,12 @@ hipError_t launch_kv_append_rotary(const Pass& p, const void* k_new, const void*
                                    void* v_cache, const float* cos_sin, hipStream_t stream);
 hipError_t launch_rotary_q(const Pass& p, void* q, const float* cos_sin, hipStream_t stream);
 
-// y[M, N] = x[M, K] . w[N, K]^T on the matrix cores (N % 256 == 0, K % 64 == 0, bf16 / f16)
-hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M, int N, int K, hipStream_t stream);
+// y[M, N] = x[M, K] . w[N, K]^T on the matrix cores (N % 256 == 0, K % 64 == 0, bf16 / f16).
+// workspace (may be null): room for fp32 partial results where cutting k into parts pays.
+hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M, int N, int K, void* workspace,
+                         size_t workspace_bytes, hipStream_t stream);
+// parts k would be cut into with a workspace of that size (1: no cut, no workspace used)
+int linear_splits(int M, int N, int K, int cus, size_t workspace_bytes);
 
 hipError_t launch_attn_generic(const Pass& p, const void* q, const void* k_cache,
                                const void* v_cache, void* out, hipStream_t stream);

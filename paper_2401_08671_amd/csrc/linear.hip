@@ -73,7 +73,8 @@ template <int DT, typename T, int BM, int BN, int WM, int WN, int kLinStages>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(const T* __restrict__ x,
                                                                            const T* __restrict__ w,
                                                                            T* __restrict__ y, int M, int N,
-                                                                           int K, int tiles_m, int tiles_n) {
+                                                                           int K, int tiles_m, int tiles_n,
+                                                                           float* __restrict__ part, int splits) {
   constexpr int kLinBN = BN;
   constexpr int kWaves = (BM / WM) * (BN / WN);
   constexpr int MB = WM / 32, NB = WN / 32;
@@ -85,8 +86,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
   // ---- which tile: workgroups are dealt to the 8 dies in turn; give each die a compact block of
   // tiles (consecutive ids on one die), walked in groups of 4 token tiles so that the tiles
   // running together on a die share weight and token panels in its L2
+  // ---- which part of k: with `splits` > 1 the k-steps are dealt to that many workgroups per tile,
+  // each of which leaves an fp32 partial tile in `part` ([split][token][feature]) for the summing kernel
   const int total = tiles_m * tiles_n;
-  int id = blockIdx.x;
+  const int split = (int)blockIdx.x / total;
+  int id = (int)blockIdx.x - split * total;
   if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
   constexpr int kGroupM = 4;
   const int per_group = kGroupM * tiles_n;
@@ -119,9 +123,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
     w_off[j] = (uint32_t)(n0 + r) * (uint32_t)K * 2u + (uint32_t)((cpc ^ ((r >> 1) & 7)) << 4);
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-  const int nk = K / kLinBK;
-  auto issue = [&](int kt) {  // copies of k-step min(kt, nk - 1) into stage kt % kLinStages
-    const int ks = min(kt, nk - 1);
+  const int nk_all = K / kLinBK;
+  const int k_first = (int)((int64_t)split * nk_all / splits);
+  const int nk = (int)((int64_t)(split + 1) * nk_all / splits) - k_first;  // >= 1: the host keeps splits <= nk_all
+  auto issue = [&](int kt) {  // copies of this part's k-step min(kt, nk - 1) into stage kt % kLinStages
+    const int ks = k_first + min(kt, nk - 1);
     const uint32_t stage = lds0 + (uint32_t)(kt % kLinStages) * kStage;
     const char* xb = reinterpret_cast<const char*>(x) + (size_t)ks * kRowBytes;
     const char* wb = reinterpret_cast<const char*>(w) + (size_t)ks * kRowBytes;
@@ -222,6 +228,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
   for (int b = 0; b < MB; ++b) {
     const int row = m0 + wm * WM + b * 32 + l32;
     if (row >= M) continue;
+    if (splits > 1) {
+      float* prow = part + ((size_t)split * M + row) * N + n0 + wn * WN + 4 * hg;
+#pragma unroll
+      for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<float4*>(prow + a * 32 + q * 8) =
+              float4{acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+      continue;
+    }
     T* yrow = y + (size_t)row * N + n0 + wn * WN + 4 * hg;
 #pragma unroll
     for (int a = 0; a < NB; ++a)
@@ -235,14 +251,91 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
   }
 }
 
+// y[t, o] = sum over the splits of part[split][t][o], rounded once; a thread takes 8 features.
+template <int DT, typename T>
+__global__ __launch_bounds__(256) void linear_sum_kernel(const float* __restrict__ part, T* __restrict__ y,
+                                                         size_t elems, int splits) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= elems) return;  // elems is a multiple of 256
+  float4 lo = *reinterpret_cast<const float4*>(part + i), hi = *reinterpret_cast<const float4*>(part + i + 4);
+  for (int s = 1; s < splits; ++s) {
+    const float4 a = *reinterpret_cast<const float4*>(part + (size_t)s * elems + i);
+    const float4 b = *reinterpret_cast<const float4*>(part + (size_t)s * elems + i + 4);
+    lo.x += a.x, lo.y += a.y, lo.z += a.z, lo.w += a.w;
+    hi.x += b.x, hi.y += b.y, hi.z += b.z, hi.w += b.w;
+  }
+  uint4 v;
+  v.x = Mma<DT>::pack2(lo.x, lo.y);
+  v.y = Mma<DT>::pack2(lo.z, lo.w);
+  v.z = Mma<DT>::pack2(hi.x, hi.y);
+  v.w = Mma<DT>::pack2(hi.z, hi.w);
+  *reinterpret_cast<uint4*>(y + i) = v;
+}
+
+struct LinearShape {
+  int shape, bm, bn, stages;
+};
+constexpr LinearShape kLinearShapes[3] = {{0, 256, 256, 2}, {1, 128, 256, 3}, {2, 128, 64, 5}};
+
+struct LinearPlan {
+  LinearShape sh;
+  int splits;
+  double cost_us;
+};
+
+// Rough time of the product with one tile shape, and in how many parts k is best cut for it.
+// A tile takes what the slowest of three things takes: its flops on one compute unit's matrix
+// cores, its weight rows from HBM at one unit's share of the bandwidth, its operand tiles from L2
+// into LDS; the launch takes ceil(tiles x parts / units) rounds of tiles of 1 / parts that
+// length.  Cutting pays where the tiles alone leave compute units idle (a 5120-wide projection of
+// up to 256 tokens is 80 tiles for 256 units); it costs a second kernel and the fp32 partial
+// results' way through memory, which is what stops it at many tokens.  (Rates fitted to
+// measurements on MI355X; the model only has to rank a handful of choices.)
+LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_t workspace_bytes) {
+  const int64_t tiles = (int64_t)((M + sh.bm - 1) / sh.bm) * (N / sh.bn);
+  const double tile_us = std::max({2.0 * sh.bm * sh.bn * K / 4.5e6, 2.0 * sh.bn * K / 45e3,
+                                   2.0 * (sh.bm + sh.bn) * K / 55e3});
+  const size_t per_part = (size_t)M * N * sizeof(float);
+  // (tiles that fill three quarters of the units by themselves are left whole)
+  const int64_t s_max = (sh.shape == 0 || tiles * 4 > (int64_t)cus * 3)
+                            ? 1
+                            : std::min<int64_t>({(int64_t)(K / kLinBK) / 8, 8, (int64_t)(workspace_bytes / per_part)});
+  LinearPlan best{sh, 1, (double)((tiles + cus - 1) / cus) * tile_us};
+  for (int64_t s = 2; s <= s_max; ++s) {
+    const double cost = (double)((tiles * s + cus - 1) / cus) / (double)s * tile_us + 4.0 + (double)s * per_part * 2.0 / 6e6;
+    if (cost < best.cost_us * 0.95) best = LinearPlan{sh, (int)s, cost};  // not for a gain the model cannot resolve
+  }
+  return best;
+}
+
+// Many tokens: 256 x 256 tiles.  Up to 1024: 128 x 256.  Up to 128: 128 x 64 (four times the
+// workgroups to pull on HBM).  Between 128 and 256 tokens whichever of the last two the model
+// prefers: the wide tile reads the tokens a quarter as often, but needs k cut into parts (a
+// workspace) to fill the chip unless the output is very wide.
+LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
+  if (M > 1024) return plan_shape(kLinearShapes[0], M, N, K, cus, 0);
+  if (M > 256) return plan_shape(kLinearShapes[1], M, N, K, cus, workspace_bytes);
+  const LinearPlan narrow = plan_shape(kLinearShapes[2], M, N, K, cus, workspace_bytes);
+  if (M <= 128) return narrow;
+  const LinearPlan wide = plan_shape(kLinearShapes[1], M, N, K, cus, workspace_bytes);
+  return wide.cost_us < narrow.cost_us ? wide : narrow;
+}
+
 }  // namespace
 
-hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M, int N, int K, hipStream_t stream) {
+int linear_splits(int M, int N, int K, int cus, size_t workspace_bytes) {
+  return linear_plan(M, N, K, cus, workspace_bytes).splits;
+}
+
+hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M, int N, int K, void* workspace,
+                         size_t workspace_bytes, hipStream_t stream) {
   PhaseTimer timer(FSF_PHASE_LINEAR, stream);
-  const int shape = M > 1024 ? 0 : (M > 256 ? 1 : 2);
-  const int bm = shape == 0 ? 256 : 128, bn = shape == 2 ? 64 : 256, stages = shape == 0 ? 2 : (shape == 1 ? 3 : 5);
+  const LinearPlan plan = linear_plan(M, N, K, device_compute_units(), workspace ? workspace_bytes : 0);
+  const int shape = plan.sh.shape, bm = plan.sh.bm, bn = plan.sh.bn, stages = plan.sh.stages;
   const int tiles_m = (M + bm - 1) / bm, tiles_n = N / bn;
-  const unsigned grid = (unsigned)(tiles_m * tiles_n);
+  const int splits = plan.splits;
+  float* part = splits > 1 ? (float*)workspace : nullptr;
+  const unsigned grid = (unsigned)(tiles_m * tiles_n * splits);
   const size_t lds_bytes = (size_t)stages * (bm + bn) * kRowBytes;
 #define FSF_LINEAR(DT, T, BM, BN, WM, WN, ST)                                                       \
   {                                                                                                 \
@@ -250,7 +343,11 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M
         e != hipSuccess)                                                                            \
       return e;                                                                                     \
     linear_kernel<DT, T, BM, BN, WM, WN, ST><<<grid, (BM / WM) * (BN / WN) * 64, lds_bytes, stream>>>( \
-        (const T*)x, (const T*)w, (T*)y, M, N, K, tiles_m, tiles_n);                                \
+        (const T*)x, (const T*)w, (T*)y, M, N, K, tiles_m, tiles_n, part, splits);                  \
+    if (splits > 1) {                                                                               \
+      const size_t elems = (size_t)M * N;                                                           \
+      linear_sum_kernel<DT, T><<<(unsigned)((elems / 8 + 255) / 256), 256, 0, stream>>>(part, (T*)y, elems, splits); \
+    }                                                                                               \
   }
 #define FSF_LINEAR_SHAPES(DT, T)                                      \
   if (shape == 0) FSF_LINEAR(DT, T, 256, 256, 128, 64, 2)             \

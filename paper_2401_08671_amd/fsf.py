@@ -191,12 +191,29 @@ def rotary_q(cfg: AttnCfg, q, batch: DeviceBatch, cos_sin) -> None:
     _check(st, "fsf_rotary_q")
 
 
-def linear(x, w, y) -> None:
-    """fsf_linear on torch's current stream: y[t, o] = sum_k x[t, k] w[o, k]; x [T, K], w [N, K], y [T, N]."""
+def linear_workspace_bytes(n_tokens: int, n_out: int, k: int) -> int:
+    L = lib()
+    L.fsf_linear_workspace_bytes.restype = C.c_size_t
+    L.fsf_linear_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+    return int(L.fsf_linear_workspace_bytes(n_tokens, n_out, k))
+
+
+def linear(x, w, y, workspace=None) -> None:
+    """fsf_linear on torch's current stream: y[t, o] = sum_k x[t, k] w[o, k]; x [T, K], w [N, K], y [T, N].
+    With ``workspace`` (a uint8 device tensor, see linear_workspace_bytes): fsf_linear_ws."""
     assert x.dim() == 2 and w.dim() == 2 and y.dim() == 2 and x.is_contiguous() and w.is_contiguous() and y.is_contiguous()
     assert x.shape[1] == w.shape[1] and y.shape == (x.shape[0], w.shape[0]) and x.dtype == w.dtype == y.dtype
-    st = lib().fsf_linear(DTYPE_CODE[x.dtype], _ptr(x), _ptr(w), _ptr(y), x.shape[0], w.shape[0], x.shape[1], _stream())
-    _check(st, "fsf_linear")
+    L = lib()
+    if workspace is None:
+        st = L.fsf_linear(DTYPE_CODE[x.dtype], _ptr(x), _ptr(w), _ptr(y), x.shape[0], w.shape[0], x.shape[1], _stream())
+        _check(st, "fsf_linear")
+        return
+    L.fsf_linear_ws.restype = C.c_int
+    L.fsf_linear_ws.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                C.c_void_p, C.c_size_t, C.c_void_p]
+    st = L.fsf_linear_ws(DTYPE_CODE[x.dtype], _ptr(x), _ptr(w), _ptr(y), x.shape[0], w.shape[0], x.shape[1],
+                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "fsf_linear_ws")
 
 
 def ragged_attention_workspace_bytes(cfg: AttnCfg, n_seqs: int, n_tokens: int, max_blocks: int) -> int:

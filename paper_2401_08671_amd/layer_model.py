@@ -48,8 +48,21 @@ def _linear(backend: str, x: torch.Tensor, w: torch.Tensor) -> torch.Tensor:
         return x @ w.T
     from . import fsf
     y = torch.empty((x.shape[0], w.shape[0]), dtype=x.dtype, device=x.device)
-    fsf.linear(x, w, y)
+    fsf.linear(x, w, y, _workspace(fsf.linear_workspace_bytes(x.shape[0], w.shape[0], x.shape[1]), x.device))
     return y
+
+
+_WORKSPACE = {}
+
+
+def _workspace(nbytes: int, device):
+    """one scratch buffer per device for fsf_linear_ws's partial results, grown as needed (None: not needed)"""
+    if nbytes == 0:
+        return None
+    ws = _WORKSPACE.get(str(device))
+    if ws is None or ws.numel() < nbytes:
+        ws = _WORKSPACE[str(device)] = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return ws
 
 
 def _make_weights(shape, device, n_sets: int = 3, split_qkv: bool = False):

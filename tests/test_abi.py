@@ -159,3 +159,15 @@ def test_static_entry_point_refuses_on_the_host_what_does_not_fit_its_array():
                                        fake, n, 1, n, fake, None)
     assert st == fsf.FSF_ERR_INVALID_ARG
     assert L.fsf_ragged_attention_static(ctypes.byref(cfg), None, None, None, None, None, None, 0, 1, 0, None, None) == fsf.FSF_OK
+
+
+def test_linear_workspace_query_without_gpu():
+    """few tokens and a narrow output are cut along k (workspace = parts x fp32 result); wide outputs,
+    many tokens and shapes the kernel refuses are not (0 bytes)"""
+    small = fsf.linear_workspace_bytes(64, 5120, 5120)
+    assert small >= 2 * 64 * 5120 * 4 and small % 256 == 0 and small <= 8 * 64 * 5120 * 4 + 256
+    assert fsf.linear_workspace_bytes(64, 5120, 13824) >= small
+    assert fsf.linear_workspace_bytes(4096, 15360, 5120) == 0      # the tiles fill the chip by themselves
+    assert fsf.linear_workspace_bytes(16, 27648, 5120) == 0
+    assert fsf.linear_workspace_bytes(16, 5120, 256) == 0          # too few k-steps to cut
+    assert fsf.linear_workspace_bytes(16, 100, 5120) == 0 and fsf.linear_workspace_bytes(0, 5120, 5120) == 0

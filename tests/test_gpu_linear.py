@@ -19,15 +19,21 @@ pytestmark = pytest.mark.gpu
 REL = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11}
 
 
-def check(M, N, K, dtype, seed=0, w_mult=None):
+def check(M, N, K, dtype, seed=0, w_mult=None, workspace_bytes=None):
+    """workspace_bytes: None = fsf_linear; a number = fsf_linear_ws with a workspace of that size
+    (-1: the size the library asks for)"""
     w_mult = K ** -0.5 if w_mult is None else w_mult
     x = wl.randn((M, K), dtype, 1.0, 9000 + seed, "cuda")
     w = wl.randn((N, K), dtype, w_mult, 9100 + seed, "cuda")
     guard = 3
     y_all = torch.full((M + guard, N), float("nan"), dtype=x.dtype, device="cuda")
     y = y_all[:M]
-    print(f"fsf_linear M={M} N={N} K={K} {dtype}", flush=True)
-    fsf.linear(x, w, y)
+    print(f"fsf_linear M={M} N={N} K={K} {dtype} workspace {workspace_bytes}", flush=True)
+    ws = None
+    if workspace_bytes is not None:
+        nbytes = fsf.linear_workspace_bytes(M, N, K) if workspace_bytes < 0 else workspace_bytes
+        ws = torch.full((max(nbytes, 16),), 0xFF, dtype=torch.uint8, device="cuda")   # NaN bit patterns
+    fsf.linear(x, w, y, ws)
     torch.cuda.synchronize()
     assert bool(torch.isnan(y_all[M:]).all()), "rows past the last token were written"
     got = y.to(torch.float64).cpu().numpy()
@@ -58,6 +64,23 @@ def test_short_and_odd_contraction_lengths(M, K):
 def test_layer_shapes_of_a_13b_model(M, N, K):
     """The projections of a Llama-2-13B-shaped layer (query/key/value, output, MLP down and gate+up)."""
     check(M, N, K, "bf16", seed=1)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,N,K", [(1, 5120, 5120), (64, 5120, 13824), (130, 5120, 5120), (256, 2560, 1024),
+                                   (300, 5120, 5120), (700, 1024, 4096), (64, 15360, 5120), (2048, 5120, 5120)])
+def test_k_cut_into_parts_with_a_workspace(M, N, K, dtype):
+    """fsf_linear_ws: narrow outputs at few tokens are cut along k (every part's partial result must
+    count: a lost or doubled part moves the result by O(1) of the bound), wide or tall products are
+    not; a workspace that holds only two parts, or none, still gives the result."""
+    if (M, N, K) in ((1, 5120, 5120), (64, 5120, 13824), (300, 5120, 5120), (700, 1024, 4096)):
+        assert fsf.linear_workspace_bytes(M, N, K) >= 2 * M * N * 4, "this product is one the library cuts"
+    if (M, N) in ((64, 15360), (2048, 5120)):
+        assert fsf.linear_workspace_bytes(M, N, K) == 0
+    check(M, N, K, dtype, seed=3, workspace_bytes=-1)
+    if dtype == "bf16":
+        check(M, N, K, dtype, seed=4, workspace_bytes=2 * M * N * 4)
+        check(M, N, K, dtype, seed=5, workspace_bytes=16)
 
 
 def test_structured_operands_catch_index_mistakes():
