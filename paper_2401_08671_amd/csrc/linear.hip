@@ -64,9 +64,10 @@ __device__ __forceinline__ void wait_copies_but() {
 }
 
 // BM x BN: tokens x output features per workgroup; WM x WN: per wave; kLinStages: depth of the LDS
-// ring.  Three shapes are built:
+// ring.  Three shapes are built (which one runs, and in how many parts k is cut, is decided by
+// linear_plan below):
 //   256 x 256, waves 128 x 64 (8 waves, two per SIMD), 2 stages of 64 KB: many tokens, compute-bound
-//   128 x 256, waves 128 x 32 (8 waves), 3 stages of 48 KB: up to 1024 tokens
+//   128 x 256, waves 128 x 32 (8 waves), 3 stages of 48 KB: a few hundred tokens
 //   128 x  64, waves  64 x 32 (4 waves), 5 stages of 24 KB: up to 256 tokens, where the pass is
 //              bound by reading the weights: four times the workgroups to pull on HBM, deep prefetch
 template <int DT, typename T, int BM, int BN, int WM, int WN, int kLinStages>
@@ -293,32 +294,43 @@ struct LinearPlan {
 // measurements on MI355X; the model only has to rank a handful of choices.)
 LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_t workspace_bytes) {
   const int64_t tiles = (int64_t)((M + sh.bm - 1) / sh.bm) * (N / sh.bn);
-  const double tile_us = std::max({2.0 * sh.bm * sh.bn * K / 4.5e6, 2.0 * sh.bn * K / 45e3,
+  // flops per microsecond of one unit: the wider tiles keep the matrix cores busier
+  const double unit_rate = sh.shape == 1 ? 4.0e6 : 4.5e6;
+  const double tile_us = std::max({2.0 * sh.bm * sh.bn * K / unit_rate, 2.0 * sh.bn * K / 45e3,
                                    2.0 * (sh.bm + sh.bn) * K / 55e3});
   const size_t per_part = (size_t)M * N * sizeof(float);
   // (tiles that fill three quarters of the units by themselves are left whole)
-  const int64_t s_max = (sh.shape == 0 || tiles * 4 > (int64_t)cus * 3)
+  const int64_t s_max = tiles * 4 > (int64_t)cus * 3
                             ? 1
                             : std::min<int64_t>({(int64_t)(K / kLinBK) / 8, 8, (int64_t)(workspace_bytes / per_part)});
-  LinearPlan best{sh, 1, (double)((tiles + cus - 1) / cus) * tile_us};
+  // the chip is power-limited: with part of the units idle the busy ones clock higher
+  auto rounds_us = [&](int64_t workgroups, int64_t parts) {
+    const double busy = (double)std::min<int64_t>(workgroups, cus) / cus;
+    return (double)((workgroups + cus - 1) / cus) / (double)parts * tile_us / (1.0 + 0.3 * (1.0 - busy));
+  };
+  LinearPlan best{sh, 1, rounds_us(tiles, 1)};
   for (int64_t s = 2; s <= s_max; ++s) {
-    const double cost = (double)((tiles * s + cus - 1) / cus) / (double)s * tile_us + 4.0 + (double)s * per_part * 2.0 / 6e6;
+    const double cost = rounds_us(tiles * s, s) + 4.0 + (double)s * per_part * 2.0 / 6e6;
     if (cost < best.cost_us * 0.95) best = LinearPlan{sh, (int)s, cost};  // not for a gain the model cannot resolve
   }
   return best;
 }
 
-// Many tokens: 256 x 256 tiles.  Up to 1024: 128 x 256.  Up to 128: 128 x 64 (four times the
-// workgroups to pull on HBM).  Between 128 and 256 tokens whichever of the last two the model
-// prefers: the wide tile reads the tokens a quarter as often, but needs k cut into parts (a
-// workspace) to fill the chip unless the output is very wide.
+// Tile shapes: 256 x 256 for many tokens; 128 x 256 up to 1024 tokens; 128 x 64 up to 256 (four
+// times the workgroups to pull on HBM).  Where two shapes are possible the model decides: between
+// 128 and 256 tokens the wide tile reads the tokens a quarter as often, but needs k cut into
+// parts (a workspace) to fill the chip unless the output is very wide; between 256 and 1024
+// tokens the larger tile wins where the smaller one's count is just over a whole number of rounds.
 LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
-  if (M > 1024) return plan_shape(kLinearShapes[0], M, N, K, cus, 0);
-  if (M > 256) return plan_shape(kLinearShapes[1], M, N, K, cus, workspace_bytes);
-  const LinearPlan narrow = plan_shape(kLinearShapes[2], M, N, K, cus, workspace_bytes);
-  if (M <= 128) return narrow;
-  const LinearPlan wide = plan_shape(kLinearShapes[1], M, N, K, cus, workspace_bytes);
-  return wide.cost_us < narrow.cost_us ? wide : narrow;
+  auto better = [&](int a, int b) {
+    const LinearPlan pa = plan_shape(kLinearShapes[a], M, N, K, cus, workspace_bytes);
+    const LinearPlan pb = plan_shape(kLinearShapes[b], M, N, K, cus, workspace_bytes);
+    return pb.cost_us < pa.cost_us ? pb : pa;
+  };
+  if (M > 1024) return plan_shape(kLinearShapes[0], M, N, K, cus, workspace_bytes);
+  if (M > 256) return better(1, 0);
+  if (M > 128) return better(2, 1);
+  return plan_shape(kLinearShapes[2], M, N, K, cus, workspace_bytes);
 }
 
 }  // namespace
