@@ -70,6 +70,10 @@ __device__ __forceinline__ void wait_copies_but() {
 //   128 x 256, waves 128 x 32 (8 waves), 3 stages of 48 KB: a few hundred tokens
 //   128 x  64, waves  64 x 32 (4 waves), 5 stages of 24 KB: up to 256 tokens, where the pass is
 //              bound by reading the weights: four times the workgroups to pull on HBM, deep prefetch
+//    64 x 128 and 32 x 128, waves 64 x 32 and 32 x 32 (4 waves), 5 and 6 stages: a few tokens.  A
+//              token tile is copied whole whatever the token count, and from 128 x 64 tiles on
+//              two thirds of what crosses from L2 into LDS are token rows; here it is a third
+//              and a fifth, and the weights can use the rest
 template <int DT, typename T, int BM, int BN, int WM, int WN, int kLinStages>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(const T* __restrict__ x,
                                                                            const T* __restrict__ w,
@@ -276,7 +280,7 @@ __global__ __launch_bounds__(256) void linear_sum_kernel(const float* __restrict
 struct LinearShape {
   int shape, bm, bn, stages;
 };
-constexpr LinearShape kLinearShapes[3] = {{0, 256, 256, 2}, {1, 128, 256, 3}, {2, 128, 64, 5}};
+constexpr LinearShape kLinearShapes[5] = {{0, 256, 256, 2}, {1, 128, 256, 3}, {2, 128, 64, 5}, {3, 64, 128, 5}, {4, 32, 128, 6}};
 
 struct LinearPlan {
   LinearShape sh;
@@ -296,7 +300,9 @@ LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_
   const int64_t tiles = (int64_t)((M + sh.bm - 1) / sh.bm) * (N / sh.bn);
   // flops per microsecond of one unit: the wider tiles keep the matrix cores busier
   const double unit_rate = sh.shape == 1 ? 4.0e6 : 4.5e6;
-  const double tile_us = std::max({2.0 * sh.bm * sh.bn * K / unit_rate, 2.0 * sh.bn * K / 45e3,
+  // bytes per microsecond one unit pulls from HBM: bounded by the copies it keeps in flight
+  const double unit_pull = sh.shape <= 1 ? 45e3 : 27e3;
+  const double tile_us = std::max({2.0 * sh.bm * sh.bn * K / unit_rate, 2.0 * sh.bn * K / unit_pull,
                                    2.0 * (sh.bm + sh.bn) * K / 55e3});
   const size_t per_part = (size_t)M * N * sizeof(float);
   // (tiles that fill three quarters of the units by themselves are left whole)
@@ -322,15 +328,22 @@ LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_
 // parts (a workspace) to fill the chip unless the output is very wide; between 256 and 1024
 // tokens the larger tile wins where the smaller one's count is just over a whole number of rounds.
 LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
-  auto better = [&](int a, int b) {
-    const LinearPlan pa = plan_shape(kLinearShapes[a], M, N, K, cus, workspace_bytes);
-    const LinearPlan pb = plan_shape(kLinearShapes[b], M, N, K, cus, workspace_bytes);
-    return pb.cost_us < pa.cost_us ? pb : pa;
+  auto best_of = [&](std::initializer_list<int> shapes) {
+    LinearPlan best{};
+    bool first = true;
+    for (int i : shapes) {
+      const LinearPlan pl = plan_shape(kLinearShapes[i], M, N, K, cus, workspace_bytes);
+      if (first || pl.cost_us < best.cost_us) best = pl;
+      first = false;
+    }
+    return best;
   };
-  if (M > 1024) return plan_shape(kLinearShapes[0], M, N, K, cus, workspace_bytes);
-  if (M > 256) return better(1, 0);
-  if (M > 128) return better(2, 1);
-  return plan_shape(kLinearShapes[2], M, N, K, cus, workspace_bytes);
+  if (M > 1024) return best_of({0});
+  if (M > 256) return best_of({1, 0});
+  if (M > 128) return best_of({2, 1});
+  if (M > 64) return best_of({2});
+  if (M > 32) return best_of({2, 3});
+  return best_of({2, 3, 4});
 }
 
 }  // namespace
@@ -364,7 +377,9 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M
 #define FSF_LINEAR_SHAPES(DT, T)                                      \
   if (shape == 0) FSF_LINEAR(DT, T, 256, 256, 128, 64, 2)             \
   else if (shape == 1) FSF_LINEAR(DT, T, 128, 256, 128, 32, 3)        \
-  else FSF_LINEAR(DT, T, 128, 64, 64, 32, 5)
+  else if (shape == 2) FSF_LINEAR(DT, T, 128, 64, 64, 32, 5)          \
+  else if (shape == 3) FSF_LINEAR(DT, T, 64, 128, 64, 32, 5)          \
+  else FSF_LINEAR(DT, T, 32, 128, 32, 32, 6)
   if (dtype == FSF_BF16) {
     FSF_LINEAR_SHAPES(FSF_BF16, bf16_t)
   } else {
