@@ -333,7 +333,7 @@ LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
     bool first = true;
     for (int i : shapes) {
       const LinearPlan pl = plan_shape(kLinearShapes[i], M, N, K, cus, workspace_bytes);
-      if (first || pl.cost_us < best.cost_us) best = pl;
+      if (first || pl.cost_us < best.cost_us * 0.95) best = pl;  // the first named is the default
       first = false;
     }
     return best;
@@ -341,7 +341,7 @@ LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
   if (M > 1024) return best_of({0});
   if (M > 256) return best_of({1, 0});
   if (M > 128) return best_of({2, 1});
-  if (M > 64) return best_of({2});
+  if (M > 64) return best_of({2, 1});
   if (M > 32) return best_of({2, 3});
   return best_of({2, 3, 4});
 }
