@@ -94,6 +94,14 @@ int main() {
     if ((st = fsf_sched_step_done(s)) != FSF_OK) die("fsf_sched_step_done", st);
     if (pass > 100000) die("too many passes", 0);
   }
+  // the linear map's choice of tile shape and parts of k over a grid of shapes (host arithmetic only)
+  for (int32_t m : {1, 31, 64, 65, 128, 129, 256, 257, 1024, 1025, 100000})
+    for (int32_t n : {256, 5120, 27648, 1 << 20})
+      for (int32_t k : {64, 512, 5120, 1 << 20}) {
+        const size_t bytes = fsf_linear_workspace_bytes(m, n, k);
+        if (bytes % 256 != 0 || bytes > (size_t)8 * m * n * sizeof(float) + 256) die("fsf_linear_workspace_bytes", (int)(bytes >> 20));
+      }
+  if (fsf_linear_workspace_bytes(0, 256, 64) != 0 || fsf_linear_workspace_bytes(1, 100, 64) != 0) die("fsf_linear_workspace_bytes on bad shapes", 0);
   long long n_pre = 0, tok = 0;
   fsf_sched_preemptions(s, (int64_t*)&n_pre, (int64_t*)&tok);
   std::printf("E %d %lld %lld\n", pass, (long long)fsf_sched_free_blocks(s), n_pre);
