@@ -33,7 +33,7 @@ import json
 import os
 
 KERNELS = ("attn_decode_single_kernel", "attn_decode_kernel", "attn_prefill_kernel", "attn_fused_kernel", "kv_append_kernel",
-           "prefill_merge_kernel", "merge_kernel", "plan_kernel", "attn_generic_kernel", "gemm_kernel")
+           "prefill_merge_kernel", "merge_kernel", "plan_kernel", "attn_generic_kernel", "linear_sum_kernel", "linear_kernel")
 BENCH_ARGS = "--no-cpu-baseline --no-ceilings --no-sustained"
 
 
@@ -155,7 +155,7 @@ def mfma_counters(raw, cfg, out_dir, bench, avg_ns):
            "|---|" + "---|" * (len(MFMA_COUNTERS) + 3)]
     for k, cs in agg.items():
         s = short(k)
-        if s not in ("attn_prefill_kernel", "attn_decode_kernel", "attn_fused_kernel", "gemm_kernel"):
+        if s not in ("attn_prefill_kernel", "attn_decode_kernel", "attn_fused_kernel", "linear_kernel"):
             continue
         vals = [mean(cs[c]) if cs.get(c) else float("nan") for c in MFMA_COUNTERS]
         busy, mfma, mops = vals[0], vals[1], vals[2]
