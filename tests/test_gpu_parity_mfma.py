@@ -185,6 +185,22 @@ def test_prompt_chunks_beside_the_streaming_kernel(heads, units):
         assert np.array_equal(a, c), "the partition of the work is the same with and without the second stream"
 
 
+@pytest.mark.parametrize("heads", [(3, 1), (10, 2), (12, 2), (36, 3), (15, 1)])
+@pytest.mark.parametrize("block", [16, 64])
+def test_head_groups_that_are_no_power_of_two(heads, block):
+    """3, 5, 6, 12 and 15 query heads per KV head: a slice of the streaming kernel then holds
+    16 // group rows and leaves columns unused; generation rows, short chunks on the streaming
+    kernel (cut and whole) and tiled chunks in one pass."""
+    Hq, Hkv = heads
+    rng = np.random.default_rng(Hq * 100 + block)
+    seqs = [(1, int(c)) for c in rng.integers(0, 2500, size=40)] + [(2, 700), (5, 0), (11, 3000), (31, 64), (300, 500)]
+    seqs = [seqs[i] for i in rng.permutation(len(seqs))]
+    spec = wl.BatchSpec("oddgroup", Hq, Hkv, 128, block, "bf16", seqs, seed=500 + Hq)
+    st = Step(spec, poison="nan")
+    check_step(st, f"heads {heads} block {block}", tuning=fsf.Tuning(stream_chunk_slices=16))
+    check_step(st, f"heads {heads} block {block}, rows cut", tuning=cut_rows(1 << 20, 256 // block))
+
+
 def test_fifty_thousand_sequences():
     """A pass of 50 000 short generation rows and two chunks: the planning kernel's prefix sums and
     counting sort over many sequences per thread, 100 000 units for 2048 wave slots."""
