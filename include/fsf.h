@@ -16,13 +16,18 @@
  * and the host-side decision that precedes it
  *     fsf_compose_batch    pick generations and prompt chunks that fill the budget and
  *                          hand out cache blocks.
+ * Beside them: the position rotation fused into the append (fsf_kv_append_rotary,
+ * fsf_rotary_q), the layer's linear maps (fsf_linear, fsf_linear_ws), a host-side check of a
+ * pass (fsf_validate_pass) and the pass for callers that may not allocate
+ * (fsf_ragged_attention_static).
  *
  * Conventions
  *   - All functions return FSF_OK (0) or a negative fsf_status; none throws, aborts or
  *     prints.  fsf_strerror() names a status.
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
  *     ordinary host memory.  The library allocates no device memory and keeps no device
- *     state between calls.  Device work is enqueued on the given hipStream_t (passed as
+ *     state between calls (fsf_ragged_attention_static alone works in a fixed array that is
+ *     part of the library's image, see there).  Device work is enqueued on the given hipStream_t (passed as
  *     void*, NULL = default stream) and is asynchronous; host arrays may be reused as
  *     soon as a call returns.
  *   - Token tensors are row-major [T, H, d], sequences back to back in descriptor
