@@ -6,7 +6,8 @@
 // and so what fixes a sensible token budget.  Dense contraction: matrix cores.
 //
 // One workgroup (8 waves, two per SIMD, for all but small token counts) computes a BM x BN tile of
-// y; a wave owns WM x WN of it as 32x32x16 MFMA tiles.  Both operands are k-contiguous in memory (tokens and
+// y; a wave owns WM x WN of it as MFMA blocks (16x16x32 in the large tile shapes, 32x32x16 in the small
+// ones, see below).  Both operands are k-contiguous in memory (tokens and
 // weight rows alike), so they are staged the same way: BK = 64 k-elements at a time, row-major
 // tiles [rows][128 bytes] in LDS, copied there directly from HBM/L2 (global_load_lds, 16 bytes per
 // lane, no registers) in a ring of two or three stages, ahead of the MFMAs.  A tile row is one
@@ -25,13 +26,16 @@
 // The copies and their waits are written as inline asm: the compiler does not track LDS-DMA
 // per stage and would wait for every copy in flight before each LDS read.  The protocol per
 // k-step kt (every wave issues the same number of copies, so the counters agree):
-//   MFMAs of the first three quarters of step kt, each with the next quarter's fragments on their
-//     way from LDS; then all fragments of step kt are in registers
+//   MFMAs of all but the last part of step kt (quarters of 16 k-elements, or halves of 32), each
+//     with the next part's fragments on their way from LDS; then all fragments of step kt are in
+//     registers
 //   wait until this wave's copies of step kt+1 have landed (all but the younger steps')
 //   workgroup barrier: everybody's copies of step kt+1 are in LDS, and everybody has read step
 //                      kt's fragments, whose stage the next copy overwrites
 //   start the copies of step kt + stages (past the end of k: the last step again, never read)
-//   first fragments of step kt+1 from LDS, the last quarter of step kt's MFMAs, the next fragments
+//   first fragments of step kt+1 from LDS, the last part of step kt's MFMAs, the next fragments
+#include <type_traits>
+
 #include "fsf_internal.h"
 #include "mma.h"
 #include "numeric.h"
@@ -64,17 +68,23 @@ __device__ __forceinline__ void wait_copies_but() {
 }
 
 // BM x BN: tokens x output features per workgroup; WM x WN: per wave; kLinStages: depth of the LDS
-// ring.  Three shapes are built (which one runs, and in how many parts k is cut, is decided by
-// linear_plan below):
+// ring; kMfma16: 16x16x32 MFMAs and a pipeline over half steps, else 32x32x16 and quarter steps.
+// Five shapes are built (which one runs, and in how many parts k is cut, is decided by linear_plan
+// below):
 //   256 x 256, waves 128 x 64 (8 waves, two per SIMD), 2 stages of 64 KB: many tokens, compute-bound
 //   128 x 256, waves 128 x 32 (8 waves), 3 stages of 48 KB: a few hundred tokens
+//      both with 16x16x32 MFMAs: under the chip's power limit that instruction sustains a tenth
+//      more flops than 32x32x16 (2.10 against 1.91 PFLOP/s in a register-resident loop on normally
+//      distributed operands), and these two kernels gain 3..6 %
 //   128 x  64, waves  64 x 32 (4 waves), 5 stages of 24 KB: up to 256 tokens, where the pass is
 //              bound by reading the weights: four times the workgroups to pull on HBM, deep prefetch
 //    64 x 128 and 32 x 128, waves 64 x 32 and 32 x 32 (4 waves), 5 and 6 stages: a few tokens.  A
 //              token tile is copied whole whatever the token count, and from 128 x 64 tiles on
 //              two thirds of what crosses from L2 into LDS are token rows; here it is a third
 //              and a fifth, and the weights can use the rest
-template <int DT, typename T, int BM, int BN, int WM, int WN, int kLinStages>
+//      these three with 32x32x16 MFMAs (bound by how fast one workgroup pulls weights, they were
+//      slower in the other form)
+template <int DT, typename T, int BM, int BN, int WM, int WN, int kLinStages, bool kMfma16>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(const T* __restrict__ x,
                                                                            const T* __restrict__ w,
                                                                            T* __restrict__ y, int M, int N,
@@ -82,20 +92,23 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
                                                                            float* __restrict__ part, int splits) {
   constexpr int kLinBN = BN;
   constexpr int kWaves = (BM / WM) * (BN / WN);
-  constexpr int MB = WM / 32, NB = WN / 32;
+  constexpr int kBlk = kMfma16 ? 16 : 32;    // rows (and columns) of one MFMA block
+  constexpr int kGroups = 64 / kBlk;         // 8-element k-groups a block's lanes hold side by side
+  constexpr int kParts = kLinBK / (8 * kGroups);  // parts of a k-step with fragments of their own: 2 halves or 4 quarters
+  constexpr int MB = WM / kBlk, NB = WN / kBlk;
   constexpr int kXTile = BM * kRowBytes, kWTile = kLinBN * kRowBytes;
   constexpr int kStage = kXTile + kWTile;
   extern __shared__ __attribute__((aligned(1024))) char lin_lds[];
   lin_lds_char* lds = (lin_lds_char*)lin_lds;
 
-  // ---- which tile: workgroups are dealt to the 8 dies in turn; give each die a compact block of
-  // tiles (consecutive ids on one die), walked in groups of 4 token tiles so that the tiles
-  // running together on a die share weight and token panels in its L2
   // ---- which part of k: with `splits` > 1 the k-steps are dealt to that many workgroups per tile,
   // each of which leaves an fp32 partial tile in `part` ([split][token][feature]) for the summing kernel
   const int total = tiles_m * tiles_n;
   const int split = (int)blockIdx.x / total;
   int id = (int)blockIdx.x - split * total;
+  // ---- which tile: workgroups are dealt to the 8 dies in turn; give each die a compact block of
+  // tiles (consecutive ids on one die), walked in groups of 4 token tiles so that the tiles
+  // running together on a die share weight and token panels in its L2
   if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
   constexpr int kGroupM = 4;
   const int per_group = kGroupM * tiles_n;
@@ -108,7 +121,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31, hg = lane >> 5;
+  const int lr = lane % kBlk, kg = lane / kBlk;  // the lane's row of a block, and its k-group
 
   // ---- copies: every wave fills an equal share of the rows of both tiles, 8 rows per instruction
   // (every wave issues the same count, so the copy counters of all waves agree)
@@ -145,23 +158,27 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
   };
   constexpr int kCopiesPerStep = kXCopies + kWCopies;
 
-  // ---- fragments: tile row blk * 32 + l32, logical chunk 2 t + hg of k-substep t (16 k-elements)
+  // ---- fragments of part t of a k-step: tile row blk * kBlk + lr, logical chunk kGroups t + kg
+  // (a block starts at a multiple of 16 rows, so the swizzle is that of row lr)
   const int wm = wave % (BM / WM), wn = wave / (BM / WM);
-  uint32_t frag_off[4];
+  uint32_t frag_off[kParts];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) frag_off[t] = (uint32_t)(l32 * kRowBytes + (((2 * t + hg) ^ ((l32 >> 1) & 7)) << 4));
+  for (int t = 0; t < kParts; ++t)
+    frag_off[t] = (uint32_t)(lr * kRowBytes + (((kGroups * t + kg) ^ ((lr >> 1) & 7)) << 4));
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 
-  f32x16_t acc[NB][MB];
+  using Acc = typename std::conditional<kMfma16, f32x4_t, f32x16_t>::type;
+  constexpr int kAccRegs = kMfma16 ? 4 : 16;
+  Acc acc[NB][MB];
 #pragma unroll
   for (int a = 0; a < NB; ++a)
 #pragma unroll
     for (int b = 0; b < MB; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+      for (int r = 0; r < kAccRegs; ++r) acc[a][b][r] = 0.f;
 
-  // Fragments of one k-substep (16 k-elements) of a stage: WN / 32 weight and 4 token fragments.
+  // Fragments of one part of a k-step: NB weight and MB token fragments.
   struct Frags {
     frag8 xf[MB], wf[NB];
   };
@@ -169,12 +186,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
     const lin_lds_char* st = lds + (kt % kLinStages) * kStage;
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
-      const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + (wm * WM + b * 32) * kRowBytes + frag_off[t]);
+      const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + (wm * WM + b * kBlk) * kRowBytes + frag_off[t]);
       fr.xf[b] = frag8{{v[0], v[1], v[2], v[3]}};
     }
 #pragma unroll
     for (int a = 0; a < NB; ++a) {
-      const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + kXTile + (wn * WN + a * 32) * kRowBytes + frag_off[t]);
+      const u32x4 v = *reinterpret_cast<const lds_u32x4*>(st + kXTile + (wn * WN + a * kBlk) * kRowBytes + frag_off[t]);
       fr.wf[a] = frag8{{v[0], v[1], v[2], v[3]}};
     }
   };
@@ -182,15 +199,20 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
 #pragma unroll
     for (int a = 0; a < NB; ++a)
 #pragma unroll
-      for (int b = 0; b < MB; ++b) acc[a][b] = Mma<DT>::mfma32(fr.wf[a], fr.xf[b], acc[a][b]);
+      for (int b = 0; b < MB; ++b) {
+        if constexpr (kMfma16)
+          acc[a][b] = Mma<DT>::mfma16(fr.wf[a], fr.xf[b], acc[a][b]);
+        else
+          acc[a][b] = Mma<DT>::mfma32(fr.wf[a], fr.xf[b], acc[a][b]);
+      }
   };
 
-  // Software pipeline over quarter steps (16 k-elements): the fragments of a quarter are on their
-  // way from LDS while the MFMAs of the quarter before run, and the wait for the next step's
-  // copies, the barrier and the first LDS reads of the next step sit before the last quarter of
-  // the current step's MFMAs, which hide them.  (The scheduling barriers keep the compiler from
-  // sinking the LDS reads down to their first use, which would put every MFMA group behind an
-  // exposed LDS round trip.)
+  // Software pipeline over the parts of a k-step: the fragments of a part are on their way from
+  // LDS while the MFMAs of the part before run, and the wait for the next step's copies, the
+  // barrier and the first LDS reads of the next step sit before the last part of the current
+  // step's MFMAs, which hide them.  (The scheduling barriers keep the compiler from sinking the
+  // LDS reads down to their first use, which would put every MFMA group behind an exposed LDS
+  // round trip.)
   constexpr int kAhead = kLinStages - 1;  // k-steps whose copies are in flight or landed beyond the current one
 #pragma unroll
   for (int j = 0; j < kAhead; ++j) issue(j);
@@ -204,14 +226,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
   for (int kt = 0; kt < nk; ++kt) {
     multiply(fa);
     __builtin_amdgcn_sched_barrier(0);
-    read_frags(fa, kt, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(fb);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(fb, kt, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(fa);
-    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (!kMfma16) {  // quarters 2 and 3 of this step
+      read_frags(fa, kt, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fb);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(fb, kt, 3);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fa);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // this wave's copies of step kt+1 have landed (younger steps may be in flight); after the
     // barrier everybody's have, and everybody holds step kt's last fragments in registers, so the
     // stage of step kt can take the copies of step kt + stages
@@ -227,31 +251,31 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void linear_kernel(cons
   }
   wait_copies_but<0>();  // the copies past the end of k are still in flight: let them land before the workgroup ends
 
-  // ---- store: acc[a][b][r] is output feature n0 + wn WN + 32 a + 8 (r / 4) + 4 hg + r % 4 of token
-  // m0 + wm WM + 32 b + l32
+  // ---- store: acc[a][b][4 q + r] is output feature n0 + wn WN + kBlk a + 8 q + 4 kg + r of token
+  // m0 + wm WM + kBlk b + lr  (one quad q per 16 x 16 block, four per 32 x 32 block)
 #pragma unroll
   for (int b = 0; b < MB; ++b) {
-    const int row = m0 + wm * WM + b * 32 + l32;
+    const int row = m0 + wm * WM + b * kBlk + lr;
     if (row >= M) continue;
     if (splits > 1) {
-      float* prow = part + ((size_t)split * M + row) * N + n0 + wn * WN + 4 * hg;
+      float* prow = part + ((size_t)split * M + row) * N + n0 + wn * WN + 4 * kg;
 #pragma unroll
       for (int a = 0; a < NB; ++a)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          *reinterpret_cast<float4*>(prow + a * 32 + q * 8) =
+        for (int q = 0; q < kAccRegs / 4; ++q)
+          *reinterpret_cast<float4*>(prow + a * kBlk + q * 8) =
               float4{acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
       continue;
     }
-    T* yrow = y + (size_t)row * N + n0 + wn * WN + 4 * hg;
+    T* yrow = y + (size_t)row * N + n0 + wn * WN + 4 * kg;
 #pragma unroll
     for (int a = 0; a < NB; ++a)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < kAccRegs / 4; ++q) {
         uint2 v;
         v.x = Mma<DT>::pack2(acc[a][b][4 * q], acc[a][b][4 * q + 1]);
         v.y = Mma<DT>::pack2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-        *reinterpret_cast<uint2*>(yrow + a * 32 + q * 8) = v;
+        *reinterpret_cast<uint2*>(yrow + a * kBlk + q * 8) = v;
       }
   }
 }
@@ -362,12 +386,12 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M
   float* part = splits > 1 ? (float*)workspace : nullptr;
   const unsigned grid = (unsigned)(tiles_m * tiles_n * splits);
   const size_t lds_bytes = (size_t)stages * (bm + bn) * kRowBytes;
-#define FSF_LINEAR(DT, T, BM, BN, WM, WN, ST)                                                       \
+#define FSF_LINEAR(DT, T, BM, BN, WM, WN, ST, M16)                                                          \
   {                                                                                                 \
-    if (const hipError_t e = allow_lds_bytes<&linear_kernel<DT, T, BM, BN, WM, WN, ST>>((int)lds_bytes); \
+    if (const hipError_t e = allow_lds_bytes<&linear_kernel<DT, T, BM, BN, WM, WN, ST, M16>>((int)lds_bytes); \
         e != hipSuccess)                                                                            \
       return e;                                                                                     \
-    linear_kernel<DT, T, BM, BN, WM, WN, ST><<<grid, (BM / WM) * (BN / WN) * 64, lds_bytes, stream>>>( \
+    linear_kernel<DT, T, BM, BN, WM, WN, ST, M16><<<grid, (BM / WM) * (BN / WN) * 64, lds_bytes, stream>>>( \
         (const T*)x, (const T*)w, (T*)y, M, N, K, tiles_m, tiles_n, part, splits);                  \
     if (splits > 1) {                                                                               \
       const size_t elems = (size_t)M * N;                                                           \
@@ -375,11 +399,11 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M
     }                                                                                               \
   }
 #define FSF_LINEAR_SHAPES(DT, T)                                      \
-  if (shape == 0) FSF_LINEAR(DT, T, 256, 256, 128, 64, 2)             \
-  else if (shape == 1) FSF_LINEAR(DT, T, 128, 256, 128, 32, 3)        \
-  else if (shape == 2) FSF_LINEAR(DT, T, 128, 64, 64, 32, 5)          \
-  else if (shape == 3) FSF_LINEAR(DT, T, 64, 128, 64, 32, 5)          \
-  else FSF_LINEAR(DT, T, 32, 128, 32, 32, 6)
+  if (shape == 0) FSF_LINEAR(DT, T, 256, 256, 128, 64, 2, true)             \
+  else if (shape == 1) FSF_LINEAR(DT, T, 128, 256, 128, 32, 3, true)        \
+  else if (shape == 2) FSF_LINEAR(DT, T, 128, 64, 64, 32, 5, false)          \
+  else if (shape == 3) FSF_LINEAR(DT, T, 64, 128, 64, 32, 5, false)          \
+  else FSF_LINEAR(DT, T, 32, 128, 32, 32, 6, false)
   if (dtype == FSF_BF16) {
     FSF_LINEAR_SHAPES(FSF_BF16, bf16_t)
   } else {
