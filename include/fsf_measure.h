@@ -44,6 +44,8 @@ int fsf_profile_read(double* ms_out, int64_t* launches_out);
  *                          the rate depends on them, because the clock the chip holds does.
  *                          iters: MFMAs per wave / 8.  Outputs (host): TFLOP/s and the shader clock
  *                          in MHz seen inside the kernel.
+ *   fsf_ceiling_mfma_bf16_16x16x32  the same loop, same flops per iteration, on 16x16x32 MFMAs
+ *                          (the power limit leaves that instruction about a tenth more flops).
  *   fsf_ceiling_hbm_read   every wave streams 32 scattered 16 KB tiles of `buf` (device, `bytes`
  *                          long, >= 512 KiB; the largest power-of-two tile count that fits is
  *                          used), with non-temporal loads if nontemporal != 0.  Output: GB/s.
@@ -51,6 +53,8 @@ int fsf_profile_read(double* ms_out, int64_t* launches_out);
  */
 int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters, void* scratch,
                           double* tflops_out, double* mhz_out, void* hip_stream);
+int fsf_ceiling_mfma_bf16_16x16x32(const void* operands, int64_t operand_bytes, int32_t iters, void* scratch,
+                                   double* tflops_out, double* mhz_out, void* hip_stream);
 int fsf_ceiling_hbm_read(const void* buf, int64_t bytes, int32_t nontemporal, void* scratch,
                          double* gbs_out, void* hip_stream);
 

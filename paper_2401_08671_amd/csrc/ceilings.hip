@@ -4,7 +4,7 @@
 // 2.5 PFLOP/s dense bf16).  Neither is reachable by any kernel: streaming reads of scattered
 // 16 KB tiles (the shape of a blocked KV cache, paper Sec. 2.1) top out below the HBM figure,
 // and a register-resident MFMA loop runs at the clock the chip can hold under that load,
-// which depends on the operand values.  These two kernels measure both, so that a kernel's
+// which depends on the operand values and on the instruction (16x16x32 sustains more than 32x32x16).  These two kernels measure both, so that a kernel's
 // distance from what is achievable can be told from its distance from the data sheet.
 #include <hip/hip_runtime.h>
 
@@ -21,8 +21,12 @@ constexpr int kMfmaBlocks = 1024;   // x 128 threads = two waves per SIMD on 256
 constexpr int kMfmaThreads = 128;
 constexpr int kMfmaPerIter = 8;
 
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
 // Each lane keeps four A and four B fragments (from `operands`, 128 bytes per lane) and two
-// 32x32 accumulators in registers; nothing but 32x32x16 MFMAs in the loop.
+// 32x32 (or eight 16x16) accumulators in registers; nothing but MFMAs in the loop, the same
+// flops per iteration in both forms: 8 x 32x32x16, or 16 x 16x16x32.
+template <bool k16>
 __global__ __launch_bounds__(kMfmaThreads) void mfma_loop_kernel(const uint4* __restrict__ operands,
                                                                  int iters, float* sink,
                                                                  unsigned long long* ticks) {
@@ -32,19 +36,48 @@ __global__ __launch_bounds__(kMfmaThreads) void mfma_loop_kernel(const uint4* __
     a[i] = __builtin_bit_cast(bf16x8_t, operands[(size_t)gid * 8 + i]);
     b[i] = __builtin_bit_cast(bf16x8_t, operands[(size_t)gid * 8 + 4 + i]);
   }
-  f32x16_t c0, c1;
-  for (int i = 0; i < 16; ++i) c0[i] = c1[i] = 0.f;
-  const uint64_t t0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(j + 1) & 3], b[j], c1, 0, 0, 0);
-    }
-  }
-  const uint64_t t1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
   float s = 0.f;
-  for (int i = 0; i < 16; ++i) s += c0[i] + c1[i];
+  uint64_t t0, t1, r0, r1;
+  if constexpr (k16) {
+    // eight independent accumulators (with four the loop waits on its own results); the
+    // instruction is written out so that each accumulator stays in the registers it starts in
+    // (through the builtin the compiler moved them between register files every iteration)
+    auto mfma16 = [](f32x4_t& c, const bf16x8_t& x, const bf16x8_t& y) {
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(x), "v"(y));
+    };
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t c0 = zero, c1 = zero, c2 = zero, c3 = zero, c4 = zero, c5 = zero, c6 = zero, c7 = zero;
+    t0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        mfma16(c0, a[0], b[2 * j]);
+        mfma16(c1, a[1], b[2 * j]);
+        mfma16(c2, a[2], b[2 * j]);
+        mfma16(c3, a[3], b[2 * j]);
+        mfma16(c4, a[0], b[2 * j + 1]);
+        mfma16(c5, a[1], b[2 * j + 1]);
+        mfma16(c6, a[2], b[2 * j + 1]);
+        mfma16(c7, a[3], b[2 * j + 1]);
+      }
+    }
+    t1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+    const f32x4_t t = c0 + c1 + c2 + c3 + c4 + c5 + c6 + c7;
+    s = t[0] + t[1] + t[2] + t[3];
+  } else {
+    f32x16_t c0, c1;
+    for (int i = 0; i < 16; ++i) c0[i] = c1[i] = 0.f;
+    t0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(j + 1) & 3], b[j], c1, 0, 0, 0);
+      }
+    }
+    t1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i];
+  }
   if (s == 123.456f) sink[gid & 63] = s;  // keeps the loop alive; practically never true
   if (gid == 0) {
     ticks[0] = t1 - t0;  // shader clock
@@ -85,9 +118,11 @@ int timed(hipStream_t stream, hipEvent_t& e0, hipEvent_t& e1, float& ms) {
 
 }  // namespace
 
-extern "C" int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters,
-                                     void* scratch, double* tflops_out, double* mhz_out,
-                                     void* hip_stream) {
+namespace {
+
+template <bool k16>
+int mfma_ceiling(const void* operands, int64_t operand_bytes, int32_t iters, void* scratch, double* tflops_out,
+                 double* mhz_out, void* hip_stream) {
   const int64_t need = (int64_t)kMfmaBlocks * kMfmaThreads * 128;
   if (!operands || operand_bytes < need || iters < 1 || !scratch || !tflops_out || !mhz_out)
     return FSF_ERR_INVALID_ARG;
@@ -96,9 +131,9 @@ extern "C" int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes
   unsigned long long* ticks = (unsigned long long*)((char*)scratch + 1024);
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return FSF_ERR_HIP;
-  mfma_loop_kernel<<<kMfmaBlocks, kMfmaThreads, 0, stream>>>((const uint4*)operands, 64, sink, ticks);  // warm-up
+  mfma_loop_kernel<k16><<<kMfmaBlocks, kMfmaThreads, 0, stream>>>((const uint4*)operands, 64, sink, ticks);  // warm-up
   int st = hipEventRecord(e0, stream) == hipSuccess ? FSF_OK : FSF_ERR_HIP;
-  mfma_loop_kernel<<<kMfmaBlocks, kMfmaThreads, 0, stream>>>((const uint4*)operands, iters, sink, ticks);
+  mfma_loop_kernel<k16><<<kMfmaBlocks, kMfmaThreads, 0, stream>>>((const uint4*)operands, iters, sink, ticks);
   float ms = 0.f;
   if (st == FSF_OK) st = timed(stream, e0, e1, ms);
   unsigned long long h[2] = {0, 0};
@@ -110,6 +145,20 @@ extern "C" int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes
   *tflops_out = flops / (ms * 1e-3) / 1e12;
   *mhz_out = h[1] ? 100.0 * (double)h[0] / (double)h[1] : 0.0;
   return FSF_OK;
+}
+
+}  // namespace
+
+extern "C" int fsf_ceiling_mfma_bf16(const void* operands, int64_t operand_bytes, int32_t iters,
+                                     void* scratch, double* tflops_out, double* mhz_out,
+                                     void* hip_stream) {
+  return mfma_ceiling<false>(operands, operand_bytes, iters, scratch, tflops_out, mhz_out, hip_stream);
+}
+
+extern "C" int fsf_ceiling_mfma_bf16_16x16x32(const void* operands, int64_t operand_bytes, int32_t iters,
+                                              void* scratch, double* tflops_out, double* mhz_out,
+                                              void* hip_stream) {
+  return mfma_ceiling<true>(operands, operand_bytes, iters, scratch, tflops_out, mhz_out, hip_stream);
 }
 
 extern "C" int fsf_ceiling_hbm_read(const void* buf, int64_t bytes, int32_t nontemporal, void* scratch,

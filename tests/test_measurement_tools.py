@@ -83,6 +83,9 @@ def test_one_point_of_each_sweep_and_of_the_layer_model():
     assert len(rows) == 1 and rows[0][0] == 64
     assert layer_model.layer_weight_bytes() / 8e12 < rows[0][1] < 5e-3
     # the matrix-core probe stays below the published peak
-    probe = ceilings.mfma_probe(iters=2000)
+    probe = ceilings.mfma_probe(iters=20000)
     assert 100.0 < probe["TFLOPs"] < 2500.0
+    # the 16x16x32 instruction sustains at least what 32x32x16 does under the power limit
+    probe16 = ceilings.mfma_probe(iters=20000, shape=16)
+    assert probe["TFLOPs"] * 0.97 < probe16["TFLOPs"] < 2500.0
     torch.cuda.synchronize()
