@@ -69,13 +69,15 @@ __device__ __forceinline__ void wait_copies_but() {
 
 // BM x BN: tokens x output features per workgroup; WM x WN: per wave; kLinStages: depth of the LDS
 // ring; kMfma16: 16x16x32 MFMAs and a pipeline over half steps, else 32x32x16 and quarter steps.
-// Five shapes are built (which one runs, and in how many parts k is cut, is decided by linear_plan
+// Six shapes are built (which one runs, and in how many parts k is cut, is decided by linear_plan
 // below):
 //   256 x 256, waves 128 x 64 (8 waves, two per SIMD), 2 stages of 64 KB: many tokens, compute-bound
+//   192 x 256, waves  96 x 64 (8 waves), 2 stages of 56 KB: where 256-row tiles come to just over a
+//              whole number of rounds of the compute units and three quarters of a tile fill them
 //   128 x 256, waves 128 x 32 (8 waves), 3 stages of 48 KB: a few hundred tokens
-//      both with 16x16x32 MFMAs: under the chip's power limit that instruction sustains a tenth
+//      all three with 16x16x32 MFMAs: under the chip's power limit that instruction sustains a tenth
 //      more flops than 32x32x16 (2.10 against 1.91 PFLOP/s in a register-resident loop on normally
-//      distributed operands), and these two kernels gain 3..6 %
+//      distributed operands), and these kernels gain 3..6 %
 //   128 x  64, waves  64 x 32 (4 waves), 5 stages of 24 KB: up to 256 tokens, where the pass is
 //              bound by reading the weights: four times the workgroups to pull on HBM, deep prefetch
 //    64 x 128 and 32 x 128, waves 64 x 32 and 32 x 32 (4 waves), 5 and 6 stages: a few tokens.  A
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(256) void linear_sum_kernel(const float* __restrict
 struct LinearShape {
   int shape, bm, bn, stages;
 };
-constexpr LinearShape kLinearShapes[5] = {{0, 256, 256, 2}, {1, 128, 256, 3}, {2, 128, 64, 5}, {3, 64, 128, 5}, {4, 32, 128, 6}};
+constexpr LinearShape kLinearShapes[6] = {{0, 256, 256, 2}, {1, 128, 256, 3}, {2, 128, 64, 5}, {3, 64, 128, 5}, {4, 32, 128, 6}, {5, 192, 256, 2}};
 
 struct LinearPlan {
   LinearShape sh;
@@ -315,17 +317,17 @@ struct LinearPlan {
 // Rough time of the product with one tile shape, and in how many parts k is best cut for it.
 // A tile takes what the slowest of three things takes: its flops on one compute unit's matrix
 // cores, its weight rows from HBM at one unit's share of the bandwidth, its operand tiles from L2
-// into LDS; the launch takes ceil(tiles x parts / units) rounds of tiles of 1 / parts that
-// length.  Cutting pays where the tiles alone leave compute units idle (a 5120-wide projection of
+// into LDS; the launch takes tiles x parts / units rounds (a round only begun counting for a
+// little less than a whole one) of tiles of 1 / parts that length.  Cutting pays where the tiles alone leave compute units idle (a 5120-wide projection of
 // up to 256 tokens is 80 tiles for 256 units); it costs a second kernel and the fp32 partial
 // results' way through memory, which is what stops it at many tokens.  (Rates fitted to
 // measurements on MI355X; the model only has to rank a handful of choices.)
 LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_t workspace_bytes) {
   const int64_t tiles = (int64_t)((M + sh.bm - 1) / sh.bm) * (N / sh.bn);
-  // flops per microsecond of one unit: the wider tiles keep the matrix cores busier
-  const double unit_rate = sh.shape == 1 ? 4.0e6 : 4.5e6;
+  // flops per microsecond of one unit with this shape's wave tiles (measured, every unit busy)
+  const double unit_rate = sh.shape == 0 ? 5.0e6 : (sh.shape == 1 ? 4.0e6 : 4.4e6);
   // bytes per microsecond one unit pulls from HBM: bounded by the copies it keeps in flight
-  const double unit_pull = sh.shape <= 1 ? 45e3 : 27e3;
+  const double unit_pull = (sh.shape <= 1 || sh.shape == 5) ? 45e3 : 27e3;
   const double tile_us = std::max({2.0 * sh.bm * sh.bn * K / unit_rate, 2.0 * sh.bn * K / unit_pull,
                                    2.0 * (sh.bm + sh.bn) * K / 55e3});
   const size_t per_part = (size_t)M * N * sizeof(float);
@@ -333,10 +335,12 @@ LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_
   const int64_t s_max = tiles * 4 > (int64_t)cus * 3
                             ? 1
                             : std::min<int64_t>({(int64_t)(K / kLinBK) / 8, 8, (int64_t)(workspace_bytes / per_part)});
-  // the chip is power-limited: with part of the units idle the busy ones clock higher
+  // A round that is only begun costs less than a whole one (the chip is power-limited: with part
+  // of the units idle the busy ones clock higher, and the workgroups of a launch do not run in
+  // lockstep): 0.6 of the missing part, fitted.
   auto rounds_us = [&](int64_t workgroups, int64_t parts) {
-    const double busy = (double)std::min<int64_t>(workgroups, cus) / cus;
-    return (double)((workgroups + cus - 1) / cus) / (double)parts * tile_us / (1.0 + 0.3 * (1.0 - busy));
+    const double r = (double)workgroups / cus, whole = (double)((workgroups + cus - 1) / cus);
+    return (r + 0.6 * (whole - r)) / (double)parts * tile_us;
   };
   LinearPlan best{sh, 1, rounds_us(tiles, 1)};
   for (int64_t s = 2; s <= s_max; ++s) {
@@ -362,8 +366,8 @@ LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
     }
     return best;
   };
-  if (M > 1024) return best_of({0});
-  if (M > 256) return best_of({1, 0});
+  if (M > 1024) return best_of({0, 5});
+  if (M > 256) return best_of({1, 0, 5});
   if (M > 128) return best_of({2, 1});
   if (M > 64) return best_of({2, 1});
   if (M > 32) return best_of({2, 3});
@@ -403,7 +407,8 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, void* y, int M
   else if (shape == 1) FSF_LINEAR(DT, T, 128, 256, 128, 32, 3, true)        \
   else if (shape == 2) FSF_LINEAR(DT, T, 128, 64, 64, 32, 5, false)          \
   else if (shape == 3) FSF_LINEAR(DT, T, 64, 128, 64, 32, 5, false)          \
-  else FSF_LINEAR(DT, T, 32, 128, 32, 32, 6, false)
+  else if (shape == 4) FSF_LINEAR(DT, T, 32, 128, 32, 32, 6, false)   \
+  else FSF_LINEAR(DT, T, 192, 256, 96, 64, 2, true)
   if (dtype == FSF_BF16) {
     FSF_LINEAR_SHAPES(FSF_BF16, bf16_t)
   } else {
