@@ -83,6 +83,13 @@ def test_k_cut_into_parts_with_a_workspace(M, N, K, dtype):
         check(M, N, K, dtype, seed=5, workspace_bytes=16)
 
 
+@pytest.mark.parametrize("M,N,K", [(384, 27648, 512), (768, 15360, 1024), (700, 15360, 1024), (4000, 5120, 1024)])
+def test_token_counts_that_take_the_192_row_tile(M, N, K):
+    """Shapes for which the library's cost model prefers tiles of 192 x 256 (a ragged last tile among them)."""
+    check(M, N, K, "bf16", seed=7)
+    check(M, N, K, "f16", seed=8)
+
+
 def test_structured_operands_catch_index_mistakes():
     """x = one-hot rows, w = distinct small integers: y[t, o] = w[o, k(t)] exactly."""
     M, N, K = 300, 512, 192
