@@ -163,8 +163,16 @@ __device__ __forceinline__ void store_rows(char* dst, decode_lds_char* src, int 
     __builtin_nontemporal_store(*reinterpret_cast<lds_u4*>(src + off), reinterpret_cast<u4*>(dst + off));
 }
 
-// One wavefront: unit = item * n_kv_heads + kv head (item = a slice of a sequence's rows and a
-// run of its cache blocks).  stage: kDecodeStageBytes of LDS that belong to this wave alone.
+// The record of launch slot `slot`, as two 16-byte loads from an address that is the same in every lane.
+__device__ __forceinline__ UnitRec load_unit_rec(const FastPlan& f, int slot) {
+  typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+  const i32x4* r = reinterpret_cast<const i32x4*>(f.dec_rec + slot);
+  const i32x4 a = r[0], b = r[1];
+  return UnitRec{a[0], a[1], a[2], a[3], b[0], b[1], {0, 0}};
+}
+
+// One wavefront: unit = (launch slot, kv head); rec = the slot's record (item = a slice of a
+// sequence's rows and a run of its cache blocks).  stage: kDecodeStageBytes of LDS that belong to this wave alone.
 // hold: if not null, the finished rows of an uncut one-row unit (g heads x 256 bytes) are left
 // there instead of being stored, and the byte offset in `out` where they belong is returned for
 // the caller to store them later; otherwise, for units of several rows and for units that
@@ -172,14 +180,11 @@ __device__ __forceinline__ void store_rows(char* dst, decode_lds_char* src, int 
 template <int DT, typename T, bool kBlock16, bool kDouble = true>
 __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f, const T* __restrict__ q,
                                                const T* __restrict__ kc, const T* __restrict__ vc,
-                                               T* __restrict__ out, int unit, int lane,
+                                               T* __restrict__ out, const UnitRec& rec, int hk, int lane,
                                                decode_lds_char* stage, decode_lds_char* hold) {
   const int n = lane & 15, kg = lane >> 4;
-  const int slot = unit / p.n_kv_heads;  // launch order: items with the most cache blocks first
-  const int hk = unit - slot * p.n_kv_heads;
-  const int item = f.dec_order[slot];
-  const int s = f.dec_item_seq[item];  // written by the planning kernel
-  const fsf_seq_desc sd = p.descs[s];
+  const int s = rec.seq;
+  const fsf_seq_desc sd = {rec.n_new, rec.n_cached, rec.q_offset, 0};
   const int B = p.block_size;
   const int g = p.group;
   // the sequence's key cuts: over the blocks any of its rows sees, the same for every slice
@@ -189,7 +194,7 @@ __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f,
   const int b_lo = lo_seq / B, b_hi = hi_seq / B;
   const int nblk = b_hi - b_lo + 1;
   const int n_splits = decode_splits(nblk, f.split_blocks, f.min_item_blocks);
-  const int idx = item - f.dec_item_start[s];  // slice-major
+  const int idx = rec.idx;  // slice-major
   const int slice = idx / n_splits;
   const int split = idx - slice * n_splits;
   // the slice's rows, and the keys they see
@@ -303,7 +308,7 @@ __device__ __forceinline__ int64_t decode_unit(const Pass& p, const FastPlan& f,
     __builtin_amdgcn_wave_barrier();  // the staging area is reused by the wave's next unit
   } else {
     // partial row of (cut, row): dec_prow_start[s] + cut * n_new + row
-    const int64_t prow0 = (int64_t)f.dec_prow_start[s] + (int64_t)split * sd.n_new + r0;
+    const int64_t prow0 = (int64_t)rec.prow_start + (int64_t)split * sd.n_new + r0;
     if (col_live) {
       if (kg == 0) {
         const int64_t pi = (prow0 + r) * p.n_q_heads + hq;

@@ -76,7 +76,9 @@ __global__ __launch_bounds__(64, 2) void attn_decode_single_kernel(Pass p, FastP
   extern __shared__ __attribute__((aligned(16))) char decode_lds[];
   lds_char* stage = (lds_char*)decode_lds;
   if (hold_slots == 0) {
-    decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, blockIdx.x, threadIdx.x, stage, nullptr);
+    const int slot = (int)blockIdx.x / p.n_kv_heads;
+    decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, load_unit_rec(f, slot), (int)blockIdx.x - slot * p.n_kv_heads,
+                                 threadIdx.x, stage, nullptr);
     return;
   }
   const int row_bytes = p.group * kHeadDim * (int)sizeof(T);
@@ -92,7 +94,9 @@ __global__ __launch_bounds__(64, 2) void attn_decode_single_kernel(Pass p, FastP
   for (int round = 0; round * G < n_units; ++round) {
     const int unit = round * G + ((round & 1) ? G - 1 - (int)blockIdx.x : (int)blockIdx.x);
     if (unit >= n_units) continue;
-    const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, unit, lane, stage, hold + held * row_bytes);
+    const int slot = unit / p.n_kv_heads;
+    const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, load_unit_rec(f, slot), unit - slot * p.n_kv_heads,
+                                                   lane, stage, hold + held * row_bytes);
     if (d >= 0) {  // the same in every lane
       if (lane == 0) dst[held] = d;
       ++held;
@@ -143,7 +147,9 @@ __global__ __launch_bounds__(64 * kWideWaves) void attn_decode_kernel(Pass p, Fa
   for (int round = 0; round * G < n_units; ++round) {
     const int unit = round * G + ((round & 1) ? G - 1 - me : me);
     if (unit >= n_units) continue;
-    const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, unit, lane, stage, hold + held * row_bytes);
+    const int slot = unit / p.n_kv_heads;
+    const int64_t d = decode_unit<DT, T, kBlock16>(p, f, q, kc, vc, out, load_unit_rec(f, slot), unit - slot * p.n_kv_heads,
+                                                   lane, stage, hold + held * row_bytes);
     if (d >= 0) {  // the same in every lane
       if (lane == 0) dst[held] = d;
       ++held;
@@ -180,7 +186,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fused_kernel(Pass p, FastPla
     const int unit = idx * kUnitsPerGroup + (threadIdx.x >> 6);
     if (unit >= f.n_dec_items * p.n_kv_heads) return;
     // (the host launches this kernel for blocks of 32 tokens or more only)
-    decode_unit<DT, T, false>(p, f, q, kc, vc, out, unit, threadIdx.x & 63,
+    const int slot = unit / p.n_kv_heads;
+    decode_unit<DT, T, false>(p, f, q, kc, vc, out, load_unit_rec(f, slot), unit - slot * p.n_kv_heads, threadIdx.x & 63,
                               (lds_char*)lds + (threadIdx.x >> 6) * kDecodeStageBytes, nullptr);
   }
 }

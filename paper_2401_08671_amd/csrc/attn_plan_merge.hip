@@ -70,7 +70,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
     f.pre_tile_start[s] = pre_run;
     f.dec_prow_start[s] = prw_run;
     const SeqWork w = work_of(s);
-    for (int k = 0; k < w.dec_items; ++k) f.dec_item_seq[dec_run + k] = s;
     for (int k = 0; k < w.pre_tiles; ++k) f.pre_tile_seq[pre_run + k] = s;
     if (w.cuts > 1)
       for (int r = 0; r < p.descs[s].n_new; ++r, ++spl_run) {
@@ -95,7 +94,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
     return kPlanThreads - 1 - min(per_item, kPlanThreads - 1);
   };
   __syncthreads();  // s_bucket zeroed by every thread above
-  dec_run = dec_incl - dec;
   for (int s = s0; s < s1; ++s) {
     const SeqWork w = work_of(s);
     if (w.dec_items > 0) atomicAdd(&s_bucket[bucket_of(s, w.cuts)], w.dec_items);
@@ -105,13 +103,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Pass p, FastPlan f) 
   const int start = block_inclusive_scan(mine, s_totals[0]) - mine;  // scan over the buckets
   s_bucket[tid] = start;  // next free launch slot of the bucket (every thread touches its own entry only)
   __syncthreads();
+  prw_run = prw_incl - prw;
   for (int s = s0; s < s1; ++s) {
     const SeqWork w = work_of(s);
     if (w.dec_items > 0) {
       const int pos = atomicAdd(&s_bucket[bucket_of(s, w.cuts)], w.dec_items);
-      for (int k = 0; k < w.dec_items; ++k) f.dec_order[pos + k] = dec_run + k;
+      const fsf_seq_desc sd = p.descs[s];
+      for (int k = 0; k < w.dec_items; ++k)
+        f.dec_rec[pos + k] = UnitRec{s, k, sd.n_new, sd.n_cached, sd.q_offset, prw_run, {0, 0}};
     }
-    dec_run += w.dec_items;
+    prw_run += w.prows;
   }
 }
 

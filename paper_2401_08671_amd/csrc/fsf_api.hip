@@ -76,7 +76,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace sections of the matrix-core path, in order.
 struct WsLayout {
-  size_t dec_item_start, pre_tile_start, dec_prow_start, dec_item_seq, dec_order, pre_tile_seq, split_rows, part_ml, part_acc, pre_part, total;
+  size_t dec_item_start, pre_tile_start, dec_prow_start, dec_rec, pre_tile_seq, split_rows, part_ml, part_acc, pre_part, total;
   size_t items_cap, prow_cap;  // streaming items and partial-result rows the sections hold
 };
 
@@ -140,10 +140,8 @@ WsLayout ws_layout(const fsf_attn_cfg* c, const Tuning& tn, int32_t n_seqs, int3
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
   w.dec_prow_start = off;
   off += align256(((size_t)n_seqs + 1) * sizeof(int32_t));
-  w.dec_item_seq = off;
-  off += align256(w.items_cap * sizeof(int32_t));
-  w.dec_order = off;
-  off += align256(w.items_cap * sizeof(int32_t));
+  w.dec_rec = off;
+  off += align256(w.items_cap * sizeof(fsf::UnitRec));
   w.pre_tile_seq = off;
   off += align256(tiles_cap * sizeof(int32_t));
   w.split_rows = off;
@@ -526,8 +524,7 @@ int run_attention(const fsf_attn_cfg* cfg, const Tuning& tn, const void* q, cons
   f.dec_item_start = (int32_t*)(ws + w.dec_item_start);
   f.pre_tile_start = (int32_t*)(ws + w.pre_tile_start);
   f.dec_prow_start = (int32_t*)(ws + w.dec_prow_start);
-  f.dec_item_seq = (int32_t*)(ws + w.dec_item_seq);
-  f.dec_order = (int32_t*)(ws + w.dec_order);
+  f.dec_rec = (fsf::UnitRec*)(ws + w.dec_rec);
   f.pre_tile_seq = (int32_t*)(ws + w.pre_tile_seq);
   f.split_rows = (int32_t*)(ws + w.split_rows);
   f.part_ml = (float*)(ws + w.part_ml);

@@ -220,12 +220,24 @@ __host__ __device__ inline int prefill_tile_steps(int n_cached, int i0, int i1, 
   return (hi - (lo & ~63)) / 64 + 1;
 }
 
+// A streaming item as its units find it: one 32-byte record per launch slot, written by the
+// planning kernel, so that a unit starts from one load instead of a chain of four dependent ones
+// (launch slot -> item -> sequence -> descriptor and item offset), and a wave that walks several
+// units can have the next record on its way while it works.
+struct __attribute__((aligned(32))) UnitRec {
+  int32_t seq;         // sequence index (block-table row)
+  int32_t idx;         // the item's index among its sequence's items (slice-major)
+  int32_t n_new, n_cached, q_offset;  // the sequence's descriptor
+  int32_t prow_start;  // first partial-result row of the sequence (used when its keys are cut)
+  int32_t pad[2];
+};
+
 struct FastPlan {
   int32_t* dec_item_start;  // [n_seqs + 1] exclusive prefix of streaming items per sequence
   int32_t* pre_tile_start;  // [n_seqs + 1] exclusive prefix of prefill tiles per sequence
   int32_t* dec_prow_start;  // [n_seqs + 1] exclusive prefix of partial-result rows per sequence
-  int32_t* dec_item_seq;    // [items]  sequence index of every streaming item
-  int32_t* dec_order;       // [items]  launch slot -> streaming item, items with the most cache blocks first
+  UnitRec* dec_rec;         // [items]  what a streaming unit needs of its item, in launch order (items with
+                            //          the most cache blocks first)
   int32_t* pre_tile_seq;    // [tiles]  sequence index of every prefill tile
   int32_t* split_rows;      // [n_split_rows, 2] (sequence, row) of every row whose keys were cut
   float* part_ml;           // [partial rows, n_q_heads, 2]   running max (log2 domain) and sum per cut
