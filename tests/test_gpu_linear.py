@@ -90,6 +90,19 @@ def test_token_counts_that_take_the_192_row_tile(M, N, K):
     check(M, N, K, "f16", seed=8)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(seed):
+    """Seeded random token counts, widths and contraction lengths, with and without a workspace of any size."""
+    rng = np.random.default_rng(4000 + seed)
+    M = int(rng.choice([int(rng.integers(1, 40)), int(rng.integers(40, 300)), int(rng.integers(300, 1100)), int(rng.integers(1100, 2600))]))
+    N = 256 * int(rng.choice([1, 2, 3, 5, 8, 20]))
+    K = 64 * int(rng.choice([1, 2, 3, 5, 9, 16, 33, 80]))
+    if M * N * K > 2e10:
+        K = 64 * 5
+    ws = [None, -1, 16, 2 * M * N * 4, 3 * M * N * 4 + 16][int(rng.integers(0, 5))]
+    check(M, N, K, "bf16" if seed % 3 else "f16", seed=seed, workspace_bytes=ws)
+
+
 def test_structured_operands_catch_index_mistakes():
     """x = one-hot rows, w = distinct small integers: y[t, o] = w[o, k(t)] exactly."""
     M, N, K = 300, 512, 192
