@@ -318,9 +318,10 @@ struct LinearPlan {
 // A tile takes what the slowest of three things takes: its flops on one compute unit's matrix
 // cores, its weight rows from HBM at one unit's share of the bandwidth, its operand tiles from L2
 // into LDS; the launch takes tiles x parts / units rounds (a round only begun counting for a
-// little less than a whole one) of tiles of 1 / parts that length.  Cutting pays where the tiles alone leave compute units idle (a 5120-wide projection of
-// up to 256 tokens is 80 tiles for 256 units); it costs a second kernel and the fp32 partial
-// results' way through memory, which is what stops it at many tokens.  (Rates fitted to
+// little less than a whole one) of tiles of 1 / parts that length.  Cutting pays where the tiles
+// alone leave compute units idle (a 5120-wide projection of up to 256 tokens is 80 tiles for 256
+// units); it costs a second kernel and the fp32 partial results' way through memory, which is
+// what stops it at many tokens.  (Rates fitted to
 // measurements on MI355X; the model only has to rank a handful of choices.)
 LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_t workspace_bytes) {
   const int64_t tiles = (int64_t)((M + sh.bm - 1) / sh.bm) * (N / sh.bn);
@@ -350,11 +351,12 @@ LinearPlan plan_shape(const LinearShape& sh, int M, int N, int K, int cus, size_
   return best;
 }
 
-// Tile shapes: 256 x 256 for many tokens; 128 x 256 up to 1024 tokens; 128 x 64 up to 256 (four
-// times the workgroups to pull on HBM).  Where two shapes are possible the model decides: between
-// 128 and 256 tokens the wide tile reads the tokens a quarter as often, but needs k cut into
-// parts (a workspace) to fill the chip unless the output is very wide; between 256 and 1024
-// tokens the larger tile wins where the smaller one's count is just over a whole number of rounds.
+// Tile shapes: 256 x 256 (or 192 x 256) for many tokens; 128 x 256 up to 1024 tokens; 128 x 64 up
+// to 256 (four times the workgroups to pull on HBM); 64 x 128 and 32 x 128 for a few.  Where
+// several shapes are possible the model decides, the first named being kept unless another is 5 %
+// better: from 64 to 256 tokens the wide tile reads the tokens a quarter as often, but needs k
+// cut into parts (a workspace) to fill the chip unless the output is very wide; from 256 tokens
+// on the larger tiles win where the smaller ones' count is just over a whole number of rounds.
 LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
   auto best_of = [&](std::initializer_list<int> shapes) {
     LinearPlan best{};
@@ -368,7 +370,6 @@ LinearPlan linear_plan(int M, int N, int K, int cus, size_t workspace_bytes) {
   };
   if (M > 1024) return best_of({0, 5});
   if (M > 256) return best_of({1, 0, 5});
-  if (M > 128) return best_of({2, 1});
   if (M > 64) return best_of({2, 1});
   if (M > 32) return best_of({2, 3});
   return best_of({2, 3, 4});
